@@ -1,0 +1,214 @@
+"""numpy front end of the CPU oracle (oracle/amq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  The GPU package never imports this module, and
+this module never imports the GPU package.  Every function is argument
+marshalling around one C function of the same name; the arithmetic and its
+citations live in the C file.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+_f32p = np.ctypeslib.ndpointer(dtype=np.float32, flags="C_CONTIGUOUS")
+_u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
+_u32p = np.ctypeslib.ndpointer(dtype=np.uint32, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_i64 = C.c_int64
+_int = C.c_int
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build()
+        L = C.CDLL(path)
+        L.amq_oracle_set_threads.argtypes = [_int]
+        L.amq_oracle_get_threads.restype = _int
+        L.amq_oracle_wpr.argtypes = [_i64]
+        L.amq_oracle_wpr.restype = _i64
+        L.amq_oracle_greedy.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
+        L.amq_oracle_ls.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
+        L.amq_oracle_ls.restype = _int
+        L.amq_oracle_code_table.argtypes = [_f32p, _int, _f32p, _i32p, _f32p]
+        L.amq_oracle_bst.argtypes = [_f32p, _i64, _int, _f32p, _u8p]
+        L.amq_oracle_error.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
+        L.amq_oracle_error.restype = C.c_double
+        L.amq_oracle_quantize.argtypes = [_f32p, _i64, _int, _int, _u8p, _f32p, C.c_void_p]
+        L.amq_oracle_pack.argtypes = [_u8p, _i64, _u32p]
+        L.amq_oracle_quantize_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _int, _u32p, _f32p]
+        L.amq_oracle_binary_dots.argtypes = [_u32p, _i64, _i64, _int, _u32p, _i64, _int, _i32p]
+        L.amq_oracle_binary_gemm.argtypes = [_u32p, _f32p, _i64, _i64, _int, _u32p, _f32p, _i64, _int,
+                                             C.c_void_p, _int, _f32p]
+        L.amq_oracle_lstm_step.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
+                                           _f32p, _f32p, _f32p, _i64, _int, _int, _f32p, _f32p]
+        L.amq_oracle_gru_step.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
+                                          C.c_void_p, _f32p, _f32p, _i64, _int, _int, _f32p]
+        L.amq_oracle_gamma.argtypes = [C.c_double] * 4
+        L.amq_oracle_gamma.restype = C.c_double
+        _lib = L
+    return _lib
+
+
+def set_threads(t: int) -> int:
+    lib().amq_oracle_set_threads(int(t))
+    return lib().amq_oracle_get_threads()
+
+
+def host_threads() -> int:
+    """Threads the host offers this process (its CPU affinity)."""
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def wpr(n: int) -> int:
+    return int(lib().amq_oracle_wpr(int(n)))
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _opt(a):
+    if a is None:
+        return None, None
+    a = _f32(a)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def greedy(w, k):
+    w = _f32(w)
+    n = w.shape[0]
+    code = np.zeros((k, n), np.uint8)
+    alpha = np.zeros(k, np.float32)
+    lib().amq_oracle_greedy(w, n, k, code, alpha)
+    return code, alpha
+
+
+def ls(w, code, alpha):
+    """Returns (alpha_new, solved)."""
+    w = _f32(w)
+    code = np.ascontiguousarray(code, np.uint8)
+    k, n = code.shape
+    alpha = _f32(alpha).copy()
+    ok = lib().amq_oracle_ls(w, n, k, code, alpha)
+    return alpha, bool(ok)
+
+
+def code_table(alpha):
+    alpha = _f32(alpha)
+    k = alpha.shape[0]
+    v = np.zeros(1 << k, np.float32)
+    pat = np.zeros(1 << k, np.int32)
+    mid = np.zeros(1 << k, np.float32)
+    lib().amq_oracle_code_table(alpha, k, v, pat, mid)
+    return v, pat, mid[: (1 << k) - 1]
+
+
+def bst(w, alpha):
+    w = _f32(w)
+    alpha = _f32(alpha)
+    k, n = alpha.shape[0], w.shape[0]
+    code = np.zeros((k, n), np.uint8)
+    lib().amq_oracle_bst(w, n, k, alpha, code)
+    return code
+
+
+def error(w, code, alpha):
+    w = _f32(w)
+    code = np.ascontiguousarray(code, np.uint8)
+    k, n = code.shape
+    return float(lib().amq_oracle_error(w, n, k, code, _f32(alpha)))
+
+
+def quantize(w, k, T, trace=False):
+    w = _f32(w)
+    n = w.shape[0]
+    code = np.zeros((k, n), np.uint8)
+    alpha = np.zeros(k, np.float32)
+    tr = np.zeros(1 + 2 * T, np.float64) if trace else None
+    lib().amq_oracle_quantize(w, n, k, T, code, alpha, tr.ctypes.data_as(C.c_void_p) if trace else None)
+    return (code, alpha, tr) if trace else (code, alpha)
+
+
+def pack(code_plane):
+    code_plane = np.ascontiguousarray(code_plane, np.uint8)
+    n = code_plane.shape[0]
+    words = np.zeros(wpr(n), np.uint32)
+    lib().amq_oracle_pack(code_plane, n, words)
+    return words
+
+
+def quantize_rows(W, k, T):
+    """W [rows, cols] -> planes [k, rows, wpr] uint32, alpha [rows, k] float32."""
+    W = _f32(W)
+    rows, cols = W.shape
+    planes = np.zeros((k, rows, wpr(cols)), np.uint32)
+    alpha = np.zeros((rows, k), np.float32)
+    lib().amq_oracle_quantize_rows(W, rows, cols, cols, k, T, planes, alpha)
+    return planes, alpha
+
+
+def binary_dots(Wp, n, Xp):
+    """Wp [k_w, m, wpr], Xp [k_a, batch, wpr] -> D [batch, m, k_w, k_a] int32."""
+    Wp = np.ascontiguousarray(Wp, np.uint32)
+    Xp = np.ascontiguousarray(Xp, np.uint32)
+    k_w, m, _ = Wp.shape
+    k_a, batch, _ = Xp.shape
+    D = np.zeros((batch, m, k_w, k_a), np.int32)
+    lib().amq_oracle_binary_dots(Wp, m, n, k_w, Xp, batch, k_a, D)
+    return D
+
+
+def binary_gemm(Wp, alpha, n, Xp, beta, bias=None, Y=None):
+    """Y [batch, m].  If Y is given the product is added to it (accumulate)."""
+    Wp = np.ascontiguousarray(Wp, np.uint32)
+    Xp = np.ascontiguousarray(Xp, np.uint32)
+    k_w, m, _ = Wp.shape
+    k_a, batch, _ = Xp.shape
+    acc = Y is not None
+    out = _f32(Y).copy() if acc else np.zeros((batch, m), np.float32)
+    bias_a, bias_p = _opt(bias)
+    lib().amq_oracle_binary_gemm(Wp, _f32(alpha), m, n, k_w, Xp, _f32(beta), batch, k_a, bias_p,
+                                 1 if acc else 0, out)
+    return out
+
+
+def lstm_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias, x, h_prev, c_prev, k_a, T):
+    Wxp = np.ascontiguousarray(Wxp, np.uint32)
+    Whp = np.ascontiguousarray(Whp, np.uint32)
+    k_w = Wxp.shape[0]
+    x, h_prev, c_prev = _f32(x), _f32(h_prev), _f32(c_prev)
+    B = x.shape[0]
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    bias_a, bias_p = _opt(bias)
+    lib().amq_oracle_lstm_step(Wxp, _f32(alpha_x), Whp, _f32(alpha_h), I, H, k_w, bias_p, x, h_prev,
+                               c_prev, B, k_a, T, h, c)
+    return h, c
+
+
+def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T):
+    Wxp = np.ascontiguousarray(Wxp, np.uint32)
+    Whp = np.ascontiguousarray(Whp, np.uint32)
+    k_w = Wxp.shape[0]
+    x, h_prev = _f32(x), _f32(h_prev)
+    B = x.shape[0]
+    h = np.zeros((B, H), np.float32)
+    bx_a, bx_p = _opt(bias_x)
+    bh_a, bh_p = _opt(bias_h)
+    lib().amq_oracle_gru_step(Wxp, _f32(alpha_x), Whp, _f32(alpha_h), I, H, k_w, bx_p, bh_p, x, h_prev,
+                              B, k_a, T, h)
+    return h
+
+
+def gamma(m, n, k_w, k_h):
+    return float(lib().amq_oracle_gamma(m, n, k_w, k_h))

@@ -1,0 +1,448 @@
+/*
+ * amq_oracle.c -- plain CPU oracle for alternating multi-bit quantization and
+ * the quantized LSTM / GRU inference step built on it.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the GPU
+ * library can be checked against something written directly from the paper.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.  It shares no code, header, table or helper with the GPU library.
+ *
+ * Style: scalar loops in the paper's order and notation, no blocking, no
+ * fusion, no intrinsics.  Precision rule (one place, applies everywhere):
+ *   - every quantity the method stores (w, residual r, alpha, the code table
+ *     v, the midpoints, outputs y / h / c) is IEEE binary32;
+ *   - a single operation on stored values (r - alpha, v sums, 0.5*(a+b)) is
+ *     done in binary32, so that the comparison "w >= midpoint" which decides a
+ *     binary code is taken in binary32 on both sides of a parity test;
+ *   - every reduction (sum |r|, B^T w, the error, the coefficient epilogue,
+ *     gate pre-activations), the k x k solve and the transcendental functions
+ *     are done in binary64 and rounded to binary32 once.
+ *
+ * Pinned (tests/test_oracle_*.py): greedy against Eq. 4 closed forms on
+ * Gaussian data; k = 1 closed form; BST against brute-force nearest code;
+ * Fig. 1 boundaries; k = 2 closed form; LS against a library least-squares
+ * routine; non-increasing error over the half-steps of Alg. 2; binary dots
+ * against an integer matrix product on unpacked +-1 codes; GEMM and the two
+ * cells against dense fp64 products of the de-quantized operands; the
+ * operation-count model of Sec. 4.
+ * Parity unpinned: nothing in this file.  (Trained-model accuracy tables are
+ * outside what this oracle computes.)
+ *
+ * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (see oracle/build.py).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_MAX_K 4
+
+static int g_threads = 1;
+
+/* Number of host threads the row- / batch-parallel entry points may use. */
+void amq_oracle_set_threads(int t) { g_threads = t < 1 ? 1 : t; }
+
+int amq_oracle_get_threads(void) {
+#ifdef _OPENMP
+  int mx = omp_get_max_threads();
+  return g_threads < mx ? g_threads : mx;
+#else
+  return 1;
+#endif
+}
+
+/* Packing convention of the exchange format: 32-bit words per row per plane,
+ * rows padded to a multiple of 128 entries (16 bytes). */
+int64_t amq_oracle_wpr(int64_t n) { return 4 * ((n + 127) / 128); }
+
+/* sign(x) = +1 iff x >= 0 (so -0.0 maps to +1), as a 0/1 code.  Matches the
+ * ">=" of Alg. 1. */
+static uint8_t sign_code(float x) { return x >= 0.0f ? 1 : 0; }
+
+static float code_value(uint8_t c) { return c ? 1.0f : -1.0f; }
+
+/* ------------------------------------------------------------------ *
+ * Greedy approximation, Eq. 3-4: r_0 = w; alpha_i = ||r_{i-1}||_1 / n,
+ * b_i = sign(r_{i-1}), r_i = r_{i-1} - alpha_i b_i.
+ * code is [k][n] with entries 0 (-1) / 1 (+1).
+ * ------------------------------------------------------------------ */
+void amq_oracle_greedy(const float* w, int64_t n, int k, uint8_t* code, float* alpha) {
+  float* r = (float*)malloc(sizeof(float) * (size_t)n);
+  memcpy(r, w, sizeof(float) * (size_t)n);
+  for (int i = 0; i < k; ++i) {
+    double l1 = 0.0;
+    for (int64_t l = 0; l < n; ++l) l1 += fabs((double)r[l]);
+    alpha[i] = (float)(l1 / (double)n);
+    for (int64_t l = 0; l < n; ++l) {
+      uint8_t b = sign_code(r[l]);
+      code[(size_t)i * n + l] = b;
+      r[l] = r[l] - alpha[i] * code_value(b); /* binary32; the product is exact */
+    }
+  }
+  free(r);
+}
+
+/* Exact determinant of a k x k integer matrix by cofactor expansion. */
+static __int128 int_det(const int64_t* G, int k, int stride) {
+  if (k == 1) return (__int128)G[0];
+  __int128 d = 0;
+  int64_t M[ORACLE_MAX_K * ORACLE_MAX_K];
+  for (int c = 0; c < k; ++c) {
+    for (int i = 1; i < k; ++i) {
+      int cc = 0;
+      for (int j = 0; j < k; ++j) {
+        if (j == c) continue;
+        M[(i - 1) * (k - 1) + cc] = G[i * stride + j];
+        ++cc;
+      }
+    }
+    __int128 minor = int_det(M, k - 1, k - 1);
+    d += ((c & 1) ? -1 : 1) * (__int128)G[c] * minor;
+  }
+  return d;
+}
+
+/* ------------------------------------------------------------------ *
+ * Least-squares coefficients, Eq. 5: alpha = (B^T B)^{-1} B^T w with
+ * B = [b_1 .. b_k].  B^T B is an integer matrix (entries n - 2 * #disagree).
+ * If it is singular (exact integer test) the coefficients are left as they
+ * are and 0 is returned; otherwise alpha is overwritten and 1 is returned.
+ * The solve is Gaussian elimination with partial pivoting in binary64.
+ * ------------------------------------------------------------------ */
+int amq_oracle_ls(const float* w, int64_t n, int k, const uint8_t* code, float* alpha) {
+  int64_t G[ORACLE_MAX_K * ORACLE_MAX_K];
+  double q[ORACLE_MAX_K];
+  for (int i = 0; i < k; ++i) {
+    for (int j = 0; j < k; ++j) {
+      int64_t s = 0;
+      for (int64_t l = 0; l < n; ++l) {
+        int bi = code[(size_t)i * n + l] ? 1 : -1;
+        int bj = code[(size_t)j * n + l] ? 1 : -1;
+        s += bi * bj;
+      }
+      G[i * k + j] = s;
+    }
+    double acc = 0.0;
+    for (int64_t l = 0; l < n; ++l)
+      acc += code[(size_t)i * n + l] ? (double)w[l] : -(double)w[l];
+    q[i] = acc;
+  }
+  if (int_det(G, k, k) == 0) return 0;
+
+  double A[ORACLE_MAX_K][ORACLE_MAX_K + 1];
+  for (int i = 0; i < k; ++i) {
+    for (int j = 0; j < k; ++j) A[i][j] = (double)G[i * k + j];
+    A[i][k] = q[i];
+  }
+  for (int c = 0; c < k; ++c) {
+    int p = c;
+    for (int i = c + 1; i < k; ++i)
+      if (fabs(A[i][c]) > fabs(A[p][c])) p = i;
+    if (p != c)
+      for (int j = 0; j <= k; ++j) { double t = A[c][j]; A[c][j] = A[p][j]; A[p][j] = t; }
+    for (int i = c + 1; i < k; ++i) {
+      double f = A[i][c] / A[c][c];
+      for (int j = c; j <= k; ++j) A[i][j] -= f * A[c][j];
+    }
+  }
+  double x[ORACLE_MAX_K];
+  for (int i = k - 1; i >= 0; --i) {
+    double s = A[i][k];
+    for (int j = i + 1; j < k; ++j) s -= A[i][j] * x[j];
+    x[i] = s / A[i][i];
+  }
+  for (int i = 0; i < k; ++i) alpha[i] = (float)x[i];
+  return 1;
+}
+
+/* ------------------------------------------------------------------ *
+ * Code table of Alg. 2 ("construct v in ascending order"): all 2^k values
+ * s_1 alpha_1 + ... + s_k alpha_k.  Pattern p in [0, 2^k) has s_i = +1 iff bit
+ * (k - i) of p is set, so that for alpha_1 >= ... >= alpha_k >= 0 the natural
+ * order of p is already ascending.  Values are summed left to right in
+ * binary32.  Pairs (value, p) are sorted ascending by value, ties by p.
+ * mid[j] = 0.5 * (v[j] + v[j+1]) in binary32, j = 0 .. 2^k - 2.
+ * ------------------------------------------------------------------ */
+void amq_oracle_code_table(const float* alpha, int k, float* v, int32_t* pattern, float* mid) {
+  int m = 1 << k;
+  for (int p = 0; p < m; ++p) {
+    float s = 0.0f;
+    for (int i = 1; i <= k; ++i) {
+      float term = ((p >> (k - i)) & 1) ? alpha[i - 1] : -alpha[i - 1];
+      s = (i == 1) ? term : s + term;
+    }
+    v[p] = s;
+    pattern[p] = p;
+  }
+  /* insertion sort: stable, so equal values keep ascending p */
+  for (int a = 1; a < m; ++a) {
+    float va = v[a];
+    int32_t pa = pattern[a];
+    int b = a - 1;
+    while (b >= 0 && v[b] > va) {
+      v[b + 1] = v[b];
+      pattern[b + 1] = pattern[b];
+      --b;
+    }
+    v[b + 1] = va;
+    pattern[b + 1] = pa;
+  }
+  for (int j = 0; j + 1 < m; ++j) mid[j] = 0.5f * (v[j] + v[j + 1]);
+}
+
+/* Alg. 1 for one entry: walk the sorted table, halving the feasible range,
+ * going to the upper half iff w >= midpoint of the two codes at the split.
+ * Returns the position in the sorted table. */
+static int bst_walk(float w, const float* mid, int lo, int hi) {
+  int len = hi - lo;
+  if (len == 1) return lo;
+  int half = lo + len / 2;
+  if (w >= mid[half - 1]) return bst_walk(w, mid, half, hi);
+  return bst_walk(w, mid, lo, half);
+}
+
+/* ------------------------------------------------------------------ *
+ * Binary codes with the coefficients fixed (Alg. 1 applied to every entry).
+ * ------------------------------------------------------------------ */
+void amq_oracle_bst(const float* w, int64_t n, int k, const float* alpha, uint8_t* code) {
+  float v[1 << ORACLE_MAX_K], mid[1 << ORACLE_MAX_K];
+  int32_t pattern[1 << ORACLE_MAX_K];
+  amq_oracle_code_table(alpha, k, v, pattern, mid);
+  for (int64_t l = 0; l < n; ++l) {
+    int pos = bst_walk(w[l], mid, 0, 1 << k);
+    int p = pattern[pos];
+    for (int i = 1; i <= k; ++i) code[(size_t)(i - 1) * n + l] = (uint8_t)((p >> (k - i)) & 1);
+  }
+}
+
+/* Objective of Eq. 2 in binary64: || w - sum_i alpha_i b_i ||^2. */
+double amq_oracle_error(const float* w, int64_t n, int k, const uint8_t* code, const float* alpha) {
+  double e = 0.0;
+  for (int64_t l = 0; l < n; ++l) {
+    double rec = 0.0;
+    for (int i = 0; i < k; ++i) rec += code[(size_t)i * n + l] ? (double)alpha[i] : -(double)alpha[i];
+    double d = (double)w[l] - rec;
+    e += d * d;
+  }
+  return e;
+}
+
+/* ------------------------------------------------------------------ *
+ * Alg. 2: greedy initialisation, then T times { Eq. 5; code table; Alg. 1 }.
+ * No trailing least-squares step: the returned alpha are those used by the
+ * last code assignment.  trace (nullable) receives 1 + 2T objective values:
+ * after greedy, then after each coefficient update and each code update.
+ * ------------------------------------------------------------------ */
+void amq_oracle_quantize(const float* w, int64_t n, int k, int T, uint8_t* code, float* alpha,
+                         double* trace) {
+  amq_oracle_greedy(w, n, k, code, alpha);
+  if (trace) trace[0] = amq_oracle_error(w, n, k, code, alpha);
+  for (int it = 0; it < T; ++it) {
+    amq_oracle_ls(w, n, k, code, alpha);
+    if (trace) trace[1 + 2 * it] = amq_oracle_error(w, n, k, code, alpha);
+    amq_oracle_bst(w, n, k, alpha, code);
+    if (trace) trace[2 + 2 * it] = amq_oracle_error(w, n, k, code, alpha);
+  }
+}
+
+/* Pack one plane of n 0/1 codes: entry l -> word l / 32, bit l % 32, bit 1
+ * means +1.  All wpr(n) words are written; bits past n are 0. */
+void amq_oracle_pack(const uint8_t* code, int64_t n, uint32_t* words) {
+  int64_t wpr = amq_oracle_wpr(n);
+  for (int64_t j = 0; j < wpr; ++j) words[j] = 0u;
+  for (int64_t l = 0; l < n; ++l)
+    if (code[l]) words[l / 32] |= (uint32_t)1 << (l % 32);
+}
+
+static int unpack_bit(const uint32_t* words, int64_t l) { return (int)((words[l / 32] >> (l % 32)) & 1u); }
+
+/* ------------------------------------------------------------------ *
+ * Row-wise quantization of a matrix (Sec. 4: "row by row"), also used for a
+ * batch of activation vectors.  W is rows x cols with leading dimension ld.
+ * planes: [k][rows][wpr] words, alpha: [rows][k].
+ * ------------------------------------------------------------------ */
+void amq_oracle_quantize_rows(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T,
+                              uint32_t* planes, float* alpha) {
+  int64_t wpr = amq_oracle_wpr(cols);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(amq_oracle_get_threads()) schedule(static)
+#endif
+  for (int64_t r = 0; r < rows; ++r) {
+    uint8_t* code = (uint8_t*)malloc((size_t)k * (size_t)cols);
+    float a[ORACLE_MAX_K];
+    amq_oracle_quantize(W + r * ld, cols, k, T, code, a, NULL);
+    for (int i = 0; i < k; ++i) {
+      amq_oracle_pack(code + (size_t)i * cols, cols, planes + ((size_t)i * rows + r) * wpr);
+      alpha[r * k + i] = a[i];
+    }
+    free(code);
+  }
+}
+
+/* ------------------------------------------------------------------ *
+ * Binary inner products (App. A): for every batch entry b, row r, weight
+ * plane i and activation plane j,
+ *   D[b][r][i][j] = sum_l Bw_i[r][l] * c_j[b][l]   with entries in {-1,+1}.
+ * Wp: [k_w][m][wpr], Xp: [k_a][batch][wpr], D: [batch][m][k_w][k_a].
+ * ------------------------------------------------------------------ */
+void amq_oracle_binary_dots(const uint32_t* Wp, int64_t m, int64_t n, int k_w, const uint32_t* Xp,
+                            int64_t batch, int k_a, int32_t* D) {
+  int64_t wpr = amq_oracle_wpr(n);
+  /* activation codes unpacked once to +-1 */
+  int8_t* xs = (int8_t*)malloc((size_t)k_a * (size_t)batch * (size_t)n);
+  for (int j = 0; j < k_a; ++j)
+    for (int64_t b = 0; b < batch; ++b)
+      for (int64_t l = 0; l < n; ++l)
+        xs[((size_t)j * batch + b) * n + l] =
+            unpack_bit(Xp + ((size_t)j * batch + b) * wpr, l) ? 1 : -1;
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(amq_oracle_get_threads()) schedule(static)
+#endif
+  for (int64_t r = 0; r < m; ++r) {
+    int8_t* ws = (int8_t*)malloc((size_t)n);
+    for (int i = 0; i < k_w; ++i) {
+      for (int64_t l = 0; l < n; ++l) ws[l] = unpack_bit(Wp + ((size_t)i * m + r) * wpr, l) ? 1 : -1;
+      for (int64_t b = 0; b < batch; ++b) {
+        for (int j = 0; j < k_a; ++j) {
+          const int8_t* x = xs + ((size_t)j * batch + b) * n;
+          int32_t s = 0;
+          for (int64_t l = 0; l < n; ++l) s += (int32_t)ws[l] * (int32_t)x[l];
+          D[(((size_t)b * m + r) * k_w + i) * k_a + j] = s;
+        }
+      }
+    }
+    free(ws);
+  }
+  free(xs);
+}
+
+/* ------------------------------------------------------------------ *
+ * Quantized matrix product (Sec. 4, Fig. 3 left): binary products first,
+ * then the coefficients:
+ *   Y[b][r] = (accumulate ? Y[b][r] : 0) + bias[r]
+ *             + sum_i alpha[r][i] * sum_j beta[b][j] * D[b][r][i][j]
+ * evaluated in binary64 and rounded once.  bias may be NULL.
+ * ------------------------------------------------------------------ */
+void amq_oracle_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                            const uint32_t* Xp, const float* beta, int64_t batch, int k_a,
+                            const float* bias, int accumulate, float* Y) {
+  int32_t* D = (int32_t*)malloc(sizeof(int32_t) * (size_t)batch * (size_t)m * (size_t)(k_w * k_a));
+  amq_oracle_binary_dots(Wp, m, n, k_w, Xp, batch, k_a, D);
+  for (int64_t b = 0; b < batch; ++b)
+    for (int64_t r = 0; r < m; ++r) {
+      double y = accumulate ? (double)Y[b * m + r] : 0.0;
+      if (bias) y += (double)bias[r];
+      for (int i = 0; i < k_w; ++i) {
+        double inner = 0.0;
+        for (int j = 0; j < k_a; ++j)
+          inner += (double)beta[b * k_a + j] * (double)D[(((size_t)b * m + r) * k_w + i) * k_a + j];
+        y += (double)alpha[r * k_w + i] * inner;
+      }
+      Y[b * m + r] = (float)y;
+    }
+  free(D);
+}
+
+/* Pre-activations a[b][r] = bias[r] + quantized product, kept in binary64. */
+static void preact(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                   const float* X, int64_t batch, int k_a, int T, const float* bias, double* a) {
+  int64_t wpr = amq_oracle_wpr(n);
+  uint32_t* Xp = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)k_a * (size_t)batch * (size_t)wpr);
+  float* beta = (float*)malloc(sizeof(float) * (size_t)batch * (size_t)k_a);
+  int32_t* D = (int32_t*)malloc(sizeof(int32_t) * (size_t)batch * (size_t)m * (size_t)(k_w * k_a));
+  amq_oracle_quantize_rows(X, batch, n, n, k_a, T, Xp, beta);
+  amq_oracle_binary_dots(Wp, m, n, k_w, Xp, batch, k_a, D);
+  for (int64_t b = 0; b < batch; ++b)
+    for (int64_t r = 0; r < m; ++r) {
+      double y = bias ? (double)bias[r] : 0.0;
+      for (int i = 0; i < k_w; ++i) {
+        double inner = 0.0;
+        for (int j = 0; j < k_a; ++j)
+          inner += (double)beta[b * k_a + j] * (double)D[(((size_t)b * m + r) * k_w + i) * k_a + j];
+        y += (double)alpha[r * k_w + i] * inner;
+      }
+      a[b * m + r] = y;
+    }
+  free(D);
+  free(beta);
+  free(Xp);
+}
+
+static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+
+/* ------------------------------------------------------------------ *
+ * One quantized LSTM step, Eq. 6.  Wx is 4H x I, Wh is 4H x H, each row-wise
+ * k_w-bit (planes + alpha); gate row blocks in the paper's order i, f, o, g;
+ * sigmoid for i, f, o and tanh for g.  x_t and h_{t-1} are quantized on line
+ * to k_a bits with T alternating cycles, each vector on its own.  bias is
+ * the sum b_i + b_h, [4H], nullable.  State h, c is carried in binary32.
+ * ------------------------------------------------------------------ */
+void amq_oracle_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                          const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                          const float* x, const float* h_prev, const float* c_prev, int64_t B,
+                          int k_a, int T, float* h_out, float* c_out) {
+  int64_t m = 4 * H;
+  double* ax = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  double* ah = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  preact(Wxp, alpha_x, m, I, k_w, x, B, k_a, T, bias, ax);
+  preact(Whp, alpha_h, m, H, k_w, h_prev, B, k_a, T, NULL, ah);
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t u = 0; u < H; ++u) {
+      double gi = sigmoid(ax[b * m + u] + ah[b * m + u]);
+      double gf = sigmoid(ax[b * m + H + u] + ah[b * m + H + u]);
+      double go = sigmoid(ax[b * m + 2 * H + u] + ah[b * m + 2 * H + u]);
+      double gg = tanh(ax[b * m + 3 * H + u] + ah[b * m + 3 * H + u]);
+      double c = gf * (double)c_prev[b * H + u] + gi * gg;
+      double h = go * tanh(c);
+      c_out[b * H + u] = (float)c;
+      h_out[b * H + u] = (float)h;
+    }
+  free(ax);
+  free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * One quantized GRU step.  The paper evaluates GRUs but prints no equations;
+ * this is the textbook cell in the form where the reset gate multiplies the
+ * hidden-side product of the candidate, so that one quantization of h_{t-1}
+ * serves all three gates:
+ *   r = sigmoid(ax_r + ah_r), z = sigmoid(ax_z + ah_z),
+ *   n = tanh(ax_n + r * ah_n), h = (1 - z) * n + z * h_prev,
+ * with ax = Wx x + bias_x, ah = Wh h_prev + bias_h, row blocks r, z, n.
+ * ------------------------------------------------------------------ */
+void amq_oracle_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                         const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias_x,
+                         const float* bias_h, const float* x, const float* h_prev, int64_t B,
+                         int k_a, int T, float* h_out) {
+  int64_t m = 3 * H;
+  double* ax = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  double* ah = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  preact(Wxp, alpha_x, m, I, k_w, x, B, k_a, T, bias_x, ax);
+  preact(Whp, alpha_h, m, H, k_w, h_prev, B, k_a, T, bias_h, ah);
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t u = 0; u < H; ++u) {
+      double r = sigmoid(ax[b * m + u] + ah[b * m + u]);
+      double z = sigmoid(ax[b * m + H + u] + ah[b * m + H + u]);
+      double nn = tanh(ax[b * m + 2 * H + u] + r * ah[b * m + 2 * H + u]);
+      double h = (1.0 - z) * nn + z * (double)h_prev[b * H + u];
+      h_out[b * H + u] = (float)h;
+    }
+  free(ax);
+  free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * Operation-count model of Sec. 3-4 (used only by a test that pins the
+ * printed speed-up figures).
+ *   quantizer:  2 T k^2 n binary, 2 (T + 1) k n non-binary
+ *   product:    2 k_w k_h m n + 4 k_h^2 n binary, 6 k_h n + 2 k_w k_h m non-binary
+ *   gamma = 2 m n / ( binary / 32 + non-binary )
+ * ------------------------------------------------------------------ */
+double amq_oracle_gamma(double m, double n, double k_w, double k_h) {
+  double bin = 2.0 * k_w * k_h * m * n + 4.0 * k_h * k_h * n;
+  double nonbin = 6.0 * k_h * n + 2.0 * k_w * k_h * m;
+  return 2.0 * m * n / (bin / 32.0 + nonbin);
+}

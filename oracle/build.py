@@ -1,0 +1,28 @@
+"""Compile the CPU oracle (plain C) into oracle/libamq_oracle.so with gcc.
+
+Test infrastructure only; the GPU library never links or loads this.
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "amq_oracle.c")
+LIB = os.path.join(HERE, "libamq_oracle.so")
+
+# -ffp-contract=off: single binary32 operations must stay single operations.
+FLAGS = ["-O2", "-std=gnu99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+         "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", *FLAGS, SRC, "-o", tmp, "-lm"])
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))
