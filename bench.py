@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized LSTM step (and the kernels it is made of) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lstm_b64] [--no-cpu]
+
+A step is one pass of the whole hot path -- on-line quantization of x_t and h_{t-1}, the
+binary products with both weight blocks, the coefficient epilogue and the cell -- over one
+batch of synthetic input that already sits in HBM.  The primary line reports the batch-64
+LSTM (hidden 1024, W3/A3) in steps/s; `also` carries the batch-1 LSTM (hidden 300, W2/A2),
+the streamed batch-1 binary GEMV in GB/s (the HBM-bound kernel), the cache-resident GEMV
+latency, the GRU + projection step and the offline weight quantizer.  `roofline` describes the
+dominant kernel of the primary workload, `roofline_gemv` the HBM-bound GEMV.  `cpu_baseline`
+is the CPU oracle timed on a bounded sample of the primary workload.
+
+One GPU only: nothing here shards, and --gpus above 1 is refused.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0                       # MI355X HBM3E
+VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T integer lane-ops/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+
+
+def dv(a, dev):
+    import torch
+    a = np.ascontiguousarray(a)
+    return torch.from_numpy(a.view(np.int32) if a.dtype == np.uint32 else a).to(dev)
+
+
+def event_time_ms(fn, iters, warmup):
+    """Average duration of fn() in ms from HIP events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def wall_time_ms(fn, iters, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / iters
+
+
+# ------------------------------------------------------------------------------ workloads
+
+def setup_lstm(amq, cfg, dev):
+    k_w, T = cfg["k_w"], cfg["T"]
+    Wxp, ax = amq.quantize_weights(dv(cfg["Wx"], dev), k_w, T)
+    Whp, ah = amq.quantize_weights(dv(cfg["Wh"], dev), k_w, T)
+    return Wxp, ax, Whp, ah
+
+
+def bench_lstm_steps(amq, cfg, dev, steps, warmup):
+    """Per-step launches of lstm_step over resident inputs, state carried on the GPU."""
+    import torch
+    I, H, B, k_a, T = cfg["I"], cfg["H"], cfg["B"], cfg["k_a"], cfg["T"]
+    q = setup_lstm(amq, cfg, dev)
+    xs = dv(cfg["xs"], dev)
+    S = xs.shape[0]
+    h = torch.zeros((B, H), device=dev)
+    c = torch.zeros((B, H), device=dev)
+    ws = amq.lstm_workspace(I, H, B, k_a, dev)
+    state = {"t": 0}
+
+    def step():
+        t = state["t"]
+        if t % S == 0:
+            h.zero_()
+            c.zero_()
+        amq.lstm_step(*q, I, H, None, xs[t % S], h, c, k_a, T, ws=ws, h_out=h, c_out=c)
+        state["t"] = t + 1
+
+    ms = wall_time_ms(step, steps, warmup)
+    return ms, q
+
+
+def bench_lstm_sequence(amq, cfg, dev, seqs, warmup):
+    import torch
+    I, H, B, k_a, T = cfg["I"], cfg["H"], cfg["B"], cfg["k_a"], cfg["T"]
+    q = setup_lstm(amq, cfg, dev)
+    xs = dv(cfg["xs"], dev)
+    S = xs.shape[0]
+    h = torch.zeros((B, H), device=dev)
+    c = torch.zeros((B, H), device=dev)
+    ws = amq.lstm_workspace(I, H, B, k_a, dev)
+
+    def seq():
+        h.zero_()
+        c.zero_()
+        amq.lstm_sequence(*q, I, H, None, xs, h, c, k_a, T, ws=ws)
+
+    return wall_time_ms(seq, seqs, warmup) / S
+
+
+def gemm_algorithmic(m, n, k_w, k_a, batch):
+    """Bit-MACs, integer lane-ops (xor + popcount-accumulate per 32 bit-MACs) and bytes of one product."""
+    macs = float(m) * n * k_w * k_a * batch
+    lane_ops = 2.0 * macs / 32.0
+    wpr = 4 * ((n + 127) // 128)
+    nbytes = k_w * m * wpr * 4 + m * k_w * 4 + batch * (k_a * wpr * 4 + k_a * 4) + batch * m * 4
+    return macs, lane_ops, nbytes
+
+
+def bench_gemm_kernel(amq, dev, m, n, k_w, k_a, batch, iters=200):
+    """Average launch duration of the binary GEMM kernel at the shape the LSTM step uses."""
+    import torch
+    g = torch.Generator(device="cpu").manual_seed(1)
+    wpr = amq.wpr(n)
+    Wp = torch.randint(-2 ** 31, 2 ** 31 - 1, (k_w, m, wpr), dtype=torch.int32, generator=g).to(dev)
+    Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (k_a, batch, wpr), dtype=torch.int32, generator=g).to(dev)
+    alpha = torch.rand((m, k_w), generator=g).to(dev)
+    beta = torch.rand((batch, k_a), generator=g).to(dev)
+    Y = torch.empty((batch, m), device=dev)
+    ms = event_time_ms(lambda: amq.binary_gemm(Wp, alpha, n, Xp, beta, Y=None if False else None) if False else
+                       amq.binding.lib().amq_binary_gemm(Wp.data_ptr(), alpha.data_ptr(), m, n, k_w, Xp.data_ptr(),
+                                                         beta.data_ptr(), batch, k_a, None, 0, Y.data_ptr(),
+                                                         torch.cuda.current_stream().cuda_stream), iters, 20)
+    return ms
+
+
+def bench_gemv_stream(amq, dev, m, n, k_w, k_a, total_bytes=512 << 20, iters=20):
+    """Grouped batch-1 GEMV over enough independent matrices that every plane byte comes from HBM."""
+    import torch
+    wpr = amq.wpr(n)
+    per = k_w * m * wpr * 4
+    G = max(1, total_bytes // per)
+    g = torch.Generator(device="cpu").manual_seed(2)
+    Wp = torch.randint(-2 ** 31, 2 ** 31 - 1, (G, k_w, m, wpr), dtype=torch.int32, generator=g).to(dev)
+    Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (G, k_a, wpr), dtype=torch.int32, generator=g).to(dev)
+    alpha = torch.rand((G, m, k_w), generator=g).to(dev)
+    beta = torch.rand((G, k_a), generator=g).to(dev)
+    Y = torch.empty((G, m), device=dev)
+    ms = event_time_ms(lambda: amq.binary_gemv_grouped(Wp, alpha, n, Xp, beta, Y=Y), iters, 3)
+    _, _, nbytes = gemm_algorithmic(m, n, k_w, k_a, 1)
+    return ms, G, G * nbytes
+
+
+def bench_gemv_warm(amq, dev, m, n, k, iters=2000):
+    import torch
+    g = torch.Generator(device="cpu").manual_seed(3)
+    wpr = amq.wpr(n)
+    Wp = torch.randint(-2 ** 31, 2 ** 31 - 1, (k, m, wpr), dtype=torch.int32, generator=g).to(dev)
+    Xp = torch.randint(-2 ** 31, 2 ** 31 - 1, (k, 1, wpr), dtype=torch.int32, generator=g).to(dev)
+    alpha = torch.rand((m, k), generator=g).to(dev)
+    beta = torch.rand((1, k), generator=g).to(dev)
+    Y = torch.empty((1, m), device=dev)
+    L = amq.binding.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    return event_time_ms(lambda: L.amq_binary_gemv(Wp.data_ptr(), alpha.data_ptr(), m, n, k, Xp.data_ptr(),
+                                                   beta.data_ptr(), k, None, 0, Y.data_ptr(), s), iters, 50)
+
+
+def bench_quantizer(amq, dev, k, iters=10):
+    import torch
+    from paper_1802_00150_amd import inputs
+    W = dv(inputs.heavy_tailed(), dev)
+    rows, cols = W.shape
+    planes = torch.empty((k, rows, amq.wpr(cols)), dtype=torch.int32, device=dev)
+    alpha = torch.empty((rows, k), device=dev)
+    L = amq.binding.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    ms = event_time_ms(lambda: L.amq_quantize_weights(W.data_ptr(), rows, cols, cols, k, 2, planes.data_ptr(),
+                                                      alpha.data_ptr(), s), iters, 2)
+    nbytes = rows * cols * 4 + planes.numel() * 4 + alpha.numel() * 4
+    return ms, nbytes
+
+
+def bench_gru(amq, dev, steps, warmup):
+    import torch
+    from paper_1802_00150_amd import inputs
+    cfg = inputs.gru_proj(steps=8)
+    I, H, B, k_w, k_a, k_p, T = cfg["I"], cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"], cfg["k_proj"], cfg["T"]
+    q = setup_lstm(amq, cfg, dev)
+    Wsp, as_ = amq.quantize_weights(dv(cfg["Ws"], dev), k_w, T)
+    xs = dv(cfg["xs"], dev)
+    h = torch.zeros((B, H), device=dev)
+    ws = amq.gru_workspace(I, H, B, k_a, dev)
+    logits = torch.empty((B, cfg["V"]), device=dev)
+    state = {"t": 0}
+
+    def step():
+        t = state["t"]
+        amq.gru_step(*q, I, H, None, None, xs[t % 8], h, k_a, T, ws=ws, h_out=h)
+        pH, bH = amq.quantize_activations(h, k_p, T)
+        amq.binary_gemm(Wsp, as_, H, pH, bH, Y=None)
+        state["t"] = t + 1
+
+    return wall_time_ms(step, steps, warmup)
+
+
+def cpu_baseline_lstm(cfg, budget_s=15.0):
+    """The oracle, as it stands, on the same LSTM workload: whole steps on all host threads."""
+    import oracle
+    threads = oracle.set_threads(oracle.host_threads())
+    I, H, B, k_w, k_a, T = cfg["I"], cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"], cfg["T"]
+    Wxp, ax = oracle.quantize_rows(cfg["Wx"], k_w, T)
+    Whp, ah = oracle.quantize_rows(cfg["Wh"], k_w, T)
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    n = 0
+    t0 = time.perf_counter()
+    while True:
+        h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, None, cfg["xs"][n % cfg["xs"].shape[0]], h, c, k_a, T)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or n >= 140:
+            break
+    return {"value": n / el, "unit": "steps/s", "cores": threads, "kind": "oracle",
+            "sample": "%d whole LSTM steps of the primary workload (B=%d, hidden %d, W%d/A%d), OpenMP over rows"
+                      % (n, B, H, k_w, k_a)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=700)
+    ap.add_argument("--warmup", type=int, default=70)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--quick", action="store_true", help="primary workload only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported "
+              "(no sharding or collectives are part of it)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1802_00150_amd as amq
+    from paper_1802_00150_amd import inputs
+    amq.binding.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # ---- primary: config 3, LSTM 1024/1024, batch 64, W3/A3, T=2
+    cfg = inputs.lstm_large()
+    ms_step, q = bench_lstm_steps(amq, cfg, dev, args.steps, args.warmup)
+    I, H, B, k_w, k_a = cfg["I"], cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"]
+
+    # dominant kernel of that step: the binary GEMM (two launches per step, x block and h block)
+    ms_gemm = bench_gemm_kernel(amq, dev, 4 * H, H, k_w, k_a, B)
+    macs, lane_ops, _ = gemm_algorithmic(4 * H, H, k_w, k_a, B)
+    achieved = lane_ops / (ms_gemm * 1e-3) / 1e12
+    roofline = {"kernel": "binary GEMM 4096x1024 W3/A3 B=64 (xor+popcount)", "bound": "alu",
+                "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "TOP/s (integer lane-ops)",
+                "frac": achieved / VALU_PEAK_TOPS, "traffic": None, "launch_ms": ms_gemm,
+                "bit_macs_per_launch": macs}
+
+    out = {"metric": "quantized LSTM steps/sec (batch 64)", "value": 1e3 / ms_step, "unit": "steps/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 popcount + f32",
+           "data": "synthetic",
+           "config": {"workload": "config 3: LSTM input 1024 hidden 1024, batch 64, 35-step sequences, "
+                                  "weights row-wise 3-bit, activations 3-bit on line, T=2",
+                      "global_batch": B, "seq_len": 35},
+           "roofline": roofline}
+
+    also = {}
+    if not args.quick:
+        # ---- batch-1 LSTM, config 1 (hidden 300): per-step launches and one call per sequence
+        c1 = inputs.lstm_small()
+        ms1, _ = bench_lstm_steps(amq, c1, dev, 700, 70)
+        ms1_seq = bench_lstm_sequence(amq, c1, dev, 20, 2)
+        also["lstm_b1_hidden300_steps_per_s"] = 1e3 / ms1
+        also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 / ms1_seq
+        # ---- batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency
+        for k in (2, 3):
+            ms, G, nbytes = bench_gemv_stream(amq, dev, 4096, 1024, k, k)
+            gbps = nbytes / (ms * 1e-3) / 1e9
+            also["gemv_b1_w%da%d_streamed_GBps" % (k, k)] = gbps
+            if k == 2:
+                out["roofline_gemv"] = {"kernel": "binary GEMV 4096x1024 W2/A2 batch 1, %d matrices streamed" % G,
+                                        "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                        "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launch_ms": ms,
+                                        "bytes_per_launch": nbytes}
+            also["gemv_b1_w%da%d_warm_call_us" % (k, k)] = bench_gemv_warm(amq, dev, 4096, 1024, k) * 1e3
+        for b in (8, 64):
+            for k in (2, 3):
+                ms = bench_gemm_kernel(amq, dev, 4096, 1024, k, k, b)
+                also["gemm_b%d_w%da%d_us" % (b, k, k)] = ms * 1e3
+        # ---- config 4: GRU step + projection
+        also["gru_b256_with_projection_steps_per_s"] = 1e3 / bench_gru(amq, dev, 100, 10)
+        # ---- config 5: offline weight quantizer
+        for k in (1, 2, 3, 4):
+            ms, nbytes = bench_quantizer(amq, dev, k)
+            also["quantize_weights_16384x4096_k%d_GBps" % k] = nbytes / (ms * 1e-3) / 1e9
+    out["also"] = also
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline_lstm(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

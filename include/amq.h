@@ -1,0 +1,170 @@
+/*
+ * amq.h -- C ABI of the MI355X (gfx950) library for alternating multi-bit
+ * quantization and the quantized LSTM / GRU inference step built on it
+ * (arXiv 1802.00150).
+ *
+ * Conventions (all entry points):
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer, including workspaces.  The library
+ *     allocates nothing and keeps no state between calls (except the entry
+ *     point marked "static scratch").  Inputs are never modified.  Outputs must
+ *     not alias inputs unless stated.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise the host.
+ *   - Return value: AMQ_OK, or an error code.  Arguments are validated on the
+ *     host before anything is launched, so AMQ_ERR_INVALID / AMQ_ERR_UNSUPPORTED
+ *     leave the device untouched.  No C++ exception crosses this boundary.
+ *   - Inputs must be finite; NaN / Inf give unspecified results.
+ *
+ * Packed code layout (the exchange format for every `planes` argument):
+ *   a k-bit quantization of `rows` vectors of length n is k bit-planes of
+ *   uint32 words, indexed [plane][row][word], with wpr = amq_wpr(n) =
+ *   4 * ceil(n / 128) words per row (rows are 16-byte aligned).  Entry l of a
+ *   row is bit (l % 32) of word (l / 32); bit 1 means +1, bit 0 means -1.
+ *   Bits at positions >= n are 0 in every operand.  Plane i (0-based) pairs
+ *   with coefficient i of that row: coef[row * k + i].
+ */
+#ifndef AMQ_H_
+#define AMQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AMQ_OK 0
+#define AMQ_ERR_INVALID 1     /* null pointer, k outside 1..4, T < 0, non-positive size, bad workspace */
+#define AMQ_ERR_UNSUPPORTED 2 /* a size beyond the limits below */
+#define AMQ_ERR_HIP 3         /* HIP runtime error; see amq_last_hip_error() */
+
+#define AMQ_MAX_BITS 4
+#define AMQ_MAX_QUANT_N 16384 /* longest vector the quantizers accept */
+#define AMQ_MAX_DOT_N (1 << 20) /* longest vector the binary products accept */
+
+/* Host-only helpers. */
+int64_t amq_wpr(int64_t n);               /* words per row per plane, 4 * ceil(n / 128) */
+const char* amq_version(void);
+const char* amq_status_string(int status);
+int amq_last_hip_error(void);             /* hipError_t of the last AMQ_ERR_HIP on this thread */
+
+/*
+ * Row-wise alternating multi-bit quantization of a weight matrix (Sec. 4,
+ * "row by row"; Alg. 2 on every row): greedy initialisation (Eq. 4), then T
+ * times { least-squares coefficients (Eq. 5); sorted code table; binary-search
+ * code assignment (Alg. 1) }.  No trailing least-squares step.  T = 0 returns
+ * the greedy result.  If the k x k Gram matrix of the codes is singular the
+ * coefficient update of that cycle is skipped.
+ *   W      [rows][ld] float, ld >= cols (row stride in elements)
+ *   planes [k][rows][wpr(cols)] uint32 out
+ *   alpha  [rows][k] float out
+ * Throughput-oriented: one wavefront (or one workgroup) per row.
+ */
+int amq_quantize_weights(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T,
+                         uint32_t* planes, float* alpha, void* stream);
+
+/*
+ * On-line quantization of a batch of activation vectors (Sec. 4: h_t "needs to
+ * be quantized on-line"); the same mathematics as amq_quantize_weights on the
+ * rows of X, X dense [batch][n].
+ *   planes [k][batch][wpr(n)] uint32 out,  beta [batch][k] float out
+ */
+int amq_quantize_activations(const float* X, int64_t batch, int64_t n, int k, int T,
+                             uint32_t* planes, float* beta, void* stream);
+
+/*
+ * Staged hooks of the quantizer (for step-by-step parity checks):
+ *   amq_ls_update : Eq. 5 with the codes given; coef [rows][k] is updated in
+ *                   place (left unchanged for a row whose Gram matrix is singular).
+ *   amq_bst_assign: Alg. 1 for every entry with the coefficients given.
+ */
+int amq_ls_update(const float* X, int64_t rows, int64_t n, int k, const uint32_t* planes,
+                  float* coef, void* stream);
+int amq_bst_assign(const float* X, int64_t rows, int64_t n, int k, const float* coef,
+                   uint32_t* planes, void* stream);
+
+/*
+ * Binary inner products (App. A: XNOR then bit count) of every weight plane
+ * with every activation plane:
+ *   D[b][r][i][j] = sum_l Bw_i[r][l] * c_j[b][l] = n - 2 * popcount(Bw_i[r] xor c_j[b])
+ *   Wp [k_w][m][wpr(n)],  Xp [k_a][batch][wpr(n)],  D [batch][m][k_w][k_a] int32 out
+ */
+int amq_binary_dots(const uint32_t* Wp, int64_t m, int64_t n, int k_w, const uint32_t* Xp,
+                    int64_t batch, int k_a, int32_t* D, void* stream);
+
+/*
+ * Quantized matrix product (Sec. 4, Fig. 3): binary products first, then the
+ * coefficients,
+ *   Y[b][r] = (accumulate ? Y[b][r] : 0) + bias[r]
+ *             + sum_i alpha[r][i] * sum_j beta[b][j] * D[b][r][i][j].
+ *   alpha [m][k_w], beta [batch][k_a], bias [m] or NULL, Y [batch][m] float.
+ * amq_binary_gemv is the batch-1 case (memory-bound streaming of the weight
+ * planes); amq_binary_gemm takes any batch.
+ */
+int amq_binary_gemv(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                    const uint32_t* Xp, const float* beta, int k_a, const float* bias,
+                    int accumulate, float* Y, void* stream);
+int amq_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                    const uint32_t* Xp, const float* beta, int64_t batch, int k_a,
+                    const float* bias, int accumulate, float* Y, void* stream);
+
+/*
+ * `groups` independent batch-1 products in one launch, group g using
+ *   Wp + g * k_w * m * wpr, alpha + g * m * k_w, Xp + g * k_a * wpr,
+ *   beta + g * k_a, Y + g * m   (bias, if given, is shared).
+ * This is how the memory-bound product is measured from HBM rather than from
+ * cache: many matrices of the benchmark's shape, each read once.
+ */
+int amq_binary_gemv_grouped(int64_t groups, const uint32_t* Wp, const float* alpha, int64_t m,
+                            int64_t n, int k_w, const uint32_t* Xp, const float* beta, int k_a,
+                            const float* bias, float* Y, void* stream);
+
+/*
+ * One quantized LSTM step (Eq. 6).  Wx is 4H x I and Wh is 4H x H, each
+ * row-wise k_w-bit (planes + alpha as produced by amq_quantize_weights); gate
+ * row blocks in the order i, f, o, g; sigmoid for i, f, o and tanh for g.
+ * x_t and h_{t-1} are quantized on line to k_a bits with T alternating cycles,
+ * each vector on its own.
+ *   bias [4H] (b_i + b_h) or NULL;  x [B][I];  h_prev, c_prev, h_out, c_out [B][H]
+ *   h_out may alias h_prev and c_out may alias c_prev.
+ *   workspace: at least amq_lstm_workspace_bytes(I, H, B, k_a) bytes, 256-byte aligned.
+ */
+size_t amq_lstm_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a);
+int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                  const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                  const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
+                  int T, float* h_out, float* c_out, void* workspace, size_t workspace_bytes,
+                  void* stream);
+
+/*
+ * `steps` consecutive LSTM steps in one call (the recurrence of Eq. 6 over a
+ * sequence): xs [steps][B][I]; h and c [B][H] are read as the initial state and
+ * overwritten with the final state; hs [steps][B][H] (nullable) receives every
+ * h_t.  Same arithmetic as `steps` calls of amq_lstm_step.
+ */
+int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                      const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                      const float* xs, int64_t steps, float* h, float* c, int64_t B, int k_a, int T,
+                      float* hs, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One quantized GRU step.  The paper evaluates GRUs (Tables 2-5) without
+ * printing the cell; this is the textbook cell in the form where the reset
+ * gate multiplies the hidden-side product of the candidate, so that one
+ * quantization of h_{t-1} serves all gates:
+ *   ax = Wx x + bias_x, ah = Wh h_prev + bias_h   (3H rows, blocks r, z, n)
+ *   r = sigmoid(ax_r + ah_r), z = sigmoid(ax_z + ah_z), n = tanh(ax_n + r * ah_n),
+ *   h = (1 - z) * n + z * h_prev.
+ *   bias_x, bias_h [3H] or NULL; h_out may alias h_prev.
+ */
+size_t amq_gru_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a);
+int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                 const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias_x,
+                 const float* bias_h, const float* x, const float* h_prev, int64_t B, int k_a, int T,
+                 float* h_out, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMQ_H_ */

@@ -28,7 +28,7 @@
  * Parity unpinned: nothing in this file.  (Trained-model accuracy tables are
  * outside what this oracle computes.)
  *
- * Build: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (see oracle/build.py).
+ * Build: gcc -O3 -ffp-contract=off -fopenmp -shared -fPIC (see oracle/build.py).
  */
 #include <math.h>
 #include <stdint.h>

@@ -11,7 +11,7 @@ SRC = os.path.join(HERE, "amq_oracle.c")
 LIB = os.path.join(HERE, "libamq_oracle.so")
 
 # -ffp-contract=off: single binary32 operations must stay single operations.
-FLAGS = ["-O2", "-std=gnu99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+FLAGS = ["-O3", "-std=gnu99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
          "-Wall", "-Wextra"]
 
 

@@ -1,0 +1,11 @@
+"""MI355X (gfx950) library for alternating multi-bit quantization and the quantized LSTM / GRU
+inference step (arXiv 1802.00150).
+
+`binding` wraps the C ABI of include/amq.h (libamq.so, built from csrc/ by `build`);
+`inputs` holds the seeded synthetic workloads.  Importing the package loads nothing; the
+shared library is loaded at the first call and a missing library is an error, never a fallback.
+"""
+from . import binding  # noqa: F401
+from .binding import (AmqError, binary_dots, binary_gemm, binary_gemv, binary_gemv_grouped, bst_assign,  # noqa: F401
+                      gru_step, gru_workspace, ls_update, lstm_sequence, lstm_step, lstm_workspace,
+                      quantize_activations, quantize_weights, version, wpr)

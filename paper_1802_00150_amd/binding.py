@@ -1,0 +1,243 @@
+"""Thin Python binding of the C ABI in include/amq.h.
+
+Argument marshalling only: every function takes torch tensors that already live on the GPU,
+passes their device pointers and the current HIP stream to the entry point of the same name,
+and raises on a non-zero status.  There is no CPU fallback: without the built library, or on
+tensors that are not on a GPU, every call fails loudly.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libamq.so")
+
+EXPORTS = [
+    "amq_wpr", "amq_version", "amq_status_string", "amq_last_hip_error",
+    "amq_quantize_weights", "amq_quantize_activations", "amq_ls_update", "amq_bst_assign",
+    "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
+    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_sequence",
+    "amq_gru_workspace_bytes", "amq_gru_step",
+]
+
+_lib = None
+_p, _i64, _int, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+
+
+class AmqError(RuntimeError):
+    pass
+
+
+def lib():
+    """Load libamq.so (built by paper_1802_00150_amd/build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise AmqError("libamq.so is not built: run `python -m paper_1802_00150_amd.build` "
+                           "(or __graft_entry__.build()) first")
+        L = C.CDLL(LIB_PATH)
+        L.amq_wpr.argtypes, L.amq_wpr.restype = [_i64], _i64
+        L.amq_version.restype = C.c_char_p
+        L.amq_status_string.argtypes, L.amq_status_string.restype = [_int], C.c_char_p
+        L.amq_last_hip_error.restype = _int
+        L.amq_quantize_weights.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p]
+        L.amq_quantize_activations.argtypes = [_p, _i64, _i64, _int, _int, _p, _p, _p]
+        L.amq_ls_update.argtypes = [_p, _i64, _i64, _int, _p, _p, _p]
+        L.amq_bst_assign.argtypes = [_p, _i64, _i64, _int, _p, _p, _p]
+        L.amq_binary_dots.argtypes = [_p, _i64, _i64, _int, _p, _i64, _int, _p, _p]
+        L.amq_binary_gemv.argtypes = [_p, _p, _i64, _i64, _int, _p, _p, _int, _p, _int, _p, _p]
+        L.amq_binary_gemm.argtypes = [_p, _p, _i64, _i64, _int, _p, _p, _i64, _int, _p, _int, _p, _p]
+        L.amq_binary_gemv_grouped.argtypes = [_i64, _p, _p, _i64, _i64, _int, _p, _p, _int, _p, _p, _p]
+        L.amq_lstm_workspace_bytes.argtypes, L.amq_lstm_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
+        L.amq_gru_workspace_bytes.argtypes, L.amq_gru_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
+        L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
+                                    _p, _sz, _p]
+        L.amq_lstm_sequence.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _i64, _p, _p, _i64, _int,
+                                        _int, _p, _p, _sz, _p]
+        L.amq_gru_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
+                                   _sz, _p]
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        L = lib()
+        msg = L.amq_status_string(status).decode()
+        if status == 3:
+            msg += " (hipError %d)" % L.amq_last_hip_error()
+        raise AmqError(msg)
+
+
+def _dev(t, dtype):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise AmqError("expected a GPU tensor")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise AmqError("expected a contiguous %s tensor, got %s" % (dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _opt(t):
+    return None if t is None else _dev(t, torch.float32)
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def wpr(n):
+    return int(lib().amq_wpr(int(n)))
+
+
+def version():
+    return lib().amq_version().decode()
+
+
+def _empty(shape, dtype, like):
+    return torch.empty(shape, dtype=dtype, device=like.device)
+
+
+def quantize_weights(W, k, T):
+    """W [rows, cols] float32 (rows may be strided) -> planes [k, rows, wpr] int32, alpha [rows, k]."""
+    if W.dim() != 2 or W.stride(1) != 1 or W.dtype != torch.float32 or not W.is_cuda:
+        raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
+    rows, cols = W.shape
+    planes = _empty((k, rows, wpr(cols)), torch.int32, W)
+    alpha = _empty((rows, k), torch.float32, W)
+    _check(lib().amq_quantize_weights(W.data_ptr(), rows, cols, W.stride(0), k, T, planes.data_ptr(),
+                                      alpha.data_ptr(), _stream()))
+    return planes, alpha
+
+
+def quantize_activations(X, k, T):
+    """X [batch, n] float32 -> planes [k, batch, wpr] int32, beta [batch, k]."""
+    batch, n = X.shape
+    planes = _empty((k, batch, wpr(n)), torch.int32, X)
+    beta = _empty((batch, k), torch.float32, X)
+    _check(lib().amq_quantize_activations(_dev(X, torch.float32), batch, n, k, T, planes.data_ptr(),
+                                          beta.data_ptr(), _stream()))
+    return planes, beta
+
+
+def ls_update(X, planes, coef):
+    """Eq. 5 with the codes given; returns the updated copy of coef."""
+    rows, n = X.shape
+    k = planes.shape[0]
+    out = coef.clone()
+    _check(lib().amq_ls_update(_dev(X, torch.float32), rows, n, k, _dev(planes, torch.int32),
+                               _dev(out, torch.float32), _stream()))
+    return out
+
+
+def bst_assign(X, coef):
+    """Alg. 1 with the coefficients given; returns planes [k, rows, wpr]."""
+    rows, n = X.shape
+    k = coef.shape[1]
+    planes = _empty((k, rows, wpr(n)), torch.int32, X)
+    _check(lib().amq_bst_assign(_dev(X, torch.float32), rows, n, k, _dev(coef, torch.float32),
+                                planes.data_ptr(), _stream()))
+    return planes
+
+
+def binary_dots(Wp, n, Xp):
+    k_w, m, _ = Wp.shape
+    k_a, batch, _ = Xp.shape
+    D = _empty((batch, m, k_w, k_a), torch.int32, Wp)
+    _check(lib().amq_binary_dots(_dev(Wp, torch.int32), m, n, k_w, _dev(Xp, torch.int32), batch, k_a,
+                                 D.data_ptr(), _stream()))
+    return D
+
+
+def binary_gemm(Wp, alpha, n, Xp, beta, bias=None, Y=None):
+    """Y [batch, m]; if Y is given the product is accumulated into it (in place)."""
+    k_w, m, _ = Wp.shape
+    k_a, batch, _ = Xp.shape
+    acc = Y is not None
+    if not acc:
+        Y = _empty((batch, m), torch.float32, Wp)
+    _check(lib().amq_binary_gemm(_dev(Wp, torch.int32), _dev(alpha, torch.float32), m, n, k_w,
+                                 _dev(Xp, torch.int32), _dev(beta, torch.float32), batch, k_a, _opt(bias),
+                                 1 if acc else 0, _dev(Y, torch.float32), _stream()))
+    return Y
+
+
+def binary_gemv(Wp, alpha, n, Xp, beta, bias=None, Y=None):
+    k_w, m, _ = Wp.shape
+    k_a = Xp.shape[0]
+    acc = Y is not None
+    if not acc:
+        Y = _empty((1, m), torch.float32, Wp)
+    _check(lib().amq_binary_gemv(_dev(Wp, torch.int32), _dev(alpha, torch.float32), m, n, k_w,
+                                 _dev(Xp, torch.int32), _dev(beta, torch.float32), k_a, _opt(bias),
+                                 1 if acc else 0, _dev(Y, torch.float32), _stream()))
+    return Y
+
+
+def binary_gemv_grouped(Wp, alpha, n, Xp, beta, bias=None, Y=None):
+    """Wp [G, k_w, m, wpr], alpha [G, m, k_w], Xp [G, k_a, wpr], beta [G, k_a] -> Y [G, m]."""
+    G, k_w, m, _ = Wp.shape
+    k_a = Xp.shape[1]
+    if Y is None:
+        Y = _empty((G, m), torch.float32, Wp)
+    _check(lib().amq_binary_gemv_grouped(G, _dev(Wp, torch.int32), _dev(alpha, torch.float32), m, n, k_w,
+                                         _dev(Xp, torch.int32), _dev(beta, torch.float32), k_a, _opt(bias),
+                                         _dev(Y, torch.float32), _stream()))
+    return Y
+
+
+def lstm_workspace(I, H, B, k_a, device):
+    nbytes = int(lib().amq_lstm_workspace_bytes(I, H, B, k_a))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def gru_workspace(I, H, B, k_a, device):
+    nbytes = int(lib().amq_gru_workspace_bytes(I, H, B, k_a))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def lstm_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias, x, h_prev, c_prev, k_a, T, ws=None, h_out=None,
+              c_out=None):
+    k_w = Wxp.shape[0]
+    B = x.shape[0]
+    if ws is None:
+        ws = lstm_workspace(I, H, B, k_a, x.device)
+    if h_out is None:
+        h_out = torch.empty_like(h_prev)
+    if c_out is None:
+        c_out = torch.empty_like(c_prev)
+    _check(lib().amq_lstm_step(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                               _dev(alpha_h, torch.float32), I, H, k_w, _opt(bias), _dev(x, torch.float32),
+                               _dev(h_prev, torch.float32), _dev(c_prev, torch.float32), B, k_a, T,
+                               _dev(h_out, torch.float32), _dev(c_out, torch.float32), ws.data_ptr(),
+                               ws.numel(), _stream()))
+    return h_out, c_out
+
+
+def lstm_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias, xs, h, c, k_a, T, ws=None, hs=None):
+    """xs [steps, B, I]; h, c [B, H] are updated in place; hs [steps, B, H] optional."""
+    k_w = Wxp.shape[0]
+    steps, B, _ = xs.shape
+    if ws is None:
+        ws = lstm_workspace(I, H, B, k_a, xs.device)
+    _check(lib().amq_lstm_sequence(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
+                                   _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, k_w,
+                                   _opt(bias), _dev(xs, torch.float32), steps, _dev(h, torch.float32),
+                                   _dev(c, torch.float32), B, k_a, T,
+                                   None if hs is None else _dev(hs, torch.float32), ws.data_ptr(),
+                                   ws.numel(), _stream()))
+    return h, c
+
+
+def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T, ws=None, h_out=None):
+    k_w = Wxp.shape[0]
+    B = x.shape[0]
+    if ws is None:
+        ws = gru_workspace(I, H, B, k_a, x.device)
+    if h_out is None:
+        h_out = torch.empty_like(h_prev)
+    _check(lib().amq_gru_step(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                              _dev(alpha_h, torch.float32), I, H, k_w, _opt(bias_x), _opt(bias_h),
+                              _dev(x, torch.float32), _dev(h_prev, torch.float32), B, k_a, T,
+                              _dev(h_out, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
+    return h_out

@@ -1,0 +1,277 @@
+// C ABI of the library (declared in include/amq.h): argument validation on the host, then
+// kernel launches on the caller's stream.  Nothing here allocates or synchronises.
+#include "../../include/amq.h"
+
+#include "amq_launch.h"
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+int hip_status(hipError_t e) {
+  if (e == hipSuccess) return AMQ_OK;
+  g_last_hip = (int)e;
+  return AMQ_ERR_HIP;
+}
+
+bool bits_ok(int k) { return k >= 1 && k <= AMQ_MAX_BITS; }
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+size_t up256(size_t b) { return (b + 255) & ~size_t(255); }
+
+// Workspace carving shared by the LSTM / GRU steps.
+struct StepWs {
+  uint32_t* xp;
+  uint32_t* hp;
+  float* beta_x;
+  float* beta_h;
+  float* pre0;
+  float* pre1;
+  size_t total;
+};
+
+StepWs carve(void* ws, int64_t I, int64_t H, int64_t B, int k_a, int gates, int n_pre) {
+  StepWs w;
+  size_t off = 0;
+  char* base = static_cast<char*>(ws);
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += up256(bytes);
+    return p;
+  };
+  w.xp = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(I)));
+  w.hp = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(H)));
+  w.beta_x = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * k_a));
+  w.beta_h = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * k_a));
+  w.pre0 = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H));
+  w.pre1 = n_pre > 1 ? reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H)) : nullptr;
+  w.total = off;
+  return w;
+}
+
+int check_step(const void* Wxp, const void* ax, const void* Whp, const void* ah, int64_t I, int64_t H,
+               int k_w, const void* x, const void* h_prev, int64_t B, int k_a, int T, const void* h_out,
+               const void* ws, size_t ws_bytes, size_t need) {
+  if (!Wxp || !ax || !Whp || !ah || !x || !h_prev || !h_out || !ws) return AMQ_ERR_INVALID;
+  if (!bits_ok(k_w) || !bits_ok(k_a) || T < 0 || I <= 0 || H <= 0 || B <= 0) return AMQ_ERR_INVALID;
+  if (!aligned(Wxp, 16) || !aligned(Whp, 16) || !aligned(ws, 256) || ws_bytes < need) return AMQ_ERR_INVALID;
+  if (I > AMQ_MAX_QUANT_N || H > AMQ_MAX_QUANT_N || B > (1 << 24)) return AMQ_ERR_UNSUPPORTED;
+  return AMQ_OK;
+}
+
+amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                        const uint32_t* Xp, const float* beta, int64_t batch, int k_a, const float* bias,
+                        int accumulate, float* Y) {
+  amq::GemmArgs g{};
+  g.op.Wp = Wp;
+  g.op.alpha = alpha;
+  g.op.Xp = Xp;
+  g.op.beta = beta;
+  g.op.n = (int)n;
+  g.m = m;
+  g.batch = (int)batch;
+  g.k_w = k_w;
+  g.k_a = k_a;
+  g.bias = bias;
+  g.accumulate = accumulate;
+  g.Y = Y;
+  g.D = nullptr;
+  g.groups = 1;
+  return g;
+}
+
+int check_product(const void* Wp, int64_t m, int64_t n, int k_w, const void* Xp, int64_t batch, int k_a) {
+  if (!Wp || !Xp) return AMQ_ERR_INVALID;
+  if (!bits_ok(k_w) || !bits_ok(k_a) || m <= 0 || n <= 0 || batch <= 0) return AMQ_ERR_INVALID;
+  if (!aligned(Wp, 16) || !aligned(Xp, 16)) return AMQ_ERR_INVALID;
+  if (n > AMQ_MAX_DOT_N || batch > (1 << 24) || m > (1LL << 40)) return AMQ_ERR_UNSUPPORTED;
+  return AMQ_OK;
+}
+
+int quantize_common(const float* X, int64_t rows, int64_t n, int64_t ld, int k, int T, uint32_t* planes,
+                    float* coef, int mode, void* stream) {
+  if (!X || !planes || !coef) return AMQ_ERR_INVALID;
+  if (!bits_ok(k) || T < 0 || rows <= 0 || n <= 0 || ld < n) return AMQ_ERR_INVALID;
+  if (!aligned(planes, 16)) return AMQ_ERR_INVALID;
+  if (n > AMQ_MAX_QUANT_N || rows > 0x7fffffffLL) return AMQ_ERR_UNSUPPORTED;
+  amq::QuantArgs a{};
+  a.seg[0] = amq::QuantSeg{X, ld, (int)n, (int)rows, planes, coef};
+  a.seg[1] = amq::QuantSeg{nullptr, 0, 0, 0, nullptr, nullptr};
+  a.T = T;
+  a.mode = mode;
+  return hip_status(amq::launch_quantize(a, k, static_cast<hipStream_t>(stream)));
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t amq_wpr(int64_t n) { return n <= 0 ? 0 : 4 * ((n + 127) / 128); }
+
+const char* amq_version(void) { return "amq 0.1 (gfx950)"; }
+
+const char* amq_status_string(int status) {
+  switch (status) {
+    case AMQ_OK: return "ok";
+    case AMQ_ERR_INVALID: return "invalid argument";
+    case AMQ_ERR_UNSUPPORTED: return "unsupported size";
+    case AMQ_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int amq_last_hip_error(void) { return g_last_hip; }
+
+int amq_quantize_weights(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T,
+                         uint32_t* planes, float* alpha, void* stream) {
+  return quantize_common(W, rows, cols, ld, k, T, planes, alpha, amq::kQuantFull, stream);
+}
+
+int amq_quantize_activations(const float* X, int64_t batch, int64_t n, int k, int T, uint32_t* planes,
+                             float* beta, void* stream) {
+  return quantize_common(X, batch, n, n, k, T, planes, beta, amq::kQuantFull, stream);
+}
+
+int amq_ls_update(const float* X, int64_t rows, int64_t n, int k, const uint32_t* planes, float* coef,
+                  void* stream) {
+  return quantize_common(X, rows, n, n, k, 1, const_cast<uint32_t*>(planes), coef, amq::kQuantLsOnly, stream);
+}
+
+int amq_bst_assign(const float* X, int64_t rows, int64_t n, int k, const float* coef, uint32_t* planes,
+                   void* stream) {
+  return quantize_common(X, rows, n, n, k, 1, planes, const_cast<float*>(coef), amq::kQuantBstOnly, stream);
+}
+
+int amq_binary_dots(const uint32_t* Wp, int64_t m, int64_t n, int k_w, const uint32_t* Xp, int64_t batch,
+                    int k_a, int32_t* D, void* stream) {
+  int st = check_product(Wp, m, n, k_w, Xp, batch, k_a);
+  if (st != AMQ_OK) return st;
+  if (!D) return AMQ_ERR_INVALID;
+  amq::GemmArgs g = gemm_args(Wp, nullptr, m, n, k_w, Xp, nullptr, batch, k_a, nullptr, 0, nullptr);
+  g.D = D;
+  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+}
+
+int amq_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                    const uint32_t* Xp, const float* beta, int64_t batch, int k_a, const float* bias,
+                    int accumulate, float* Y, void* stream) {
+  int st = check_product(Wp, m, n, k_w, Xp, batch, k_a);
+  if (st != AMQ_OK) return st;
+  if (!alpha || !beta || !Y) return AMQ_ERR_INVALID;
+  amq::GemmArgs g = gemm_args(Wp, alpha, m, n, k_w, Xp, beta, batch, k_a, bias, accumulate ? 1 : 0, Y);
+  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+}
+
+int amq_binary_gemv(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                    const uint32_t* Xp, const float* beta, int k_a, const float* bias, int accumulate,
+                    float* Y, void* stream) {
+  return amq_binary_gemm(Wp, alpha, m, n, k_w, Xp, beta, 1, k_a, bias, accumulate, Y, stream);
+}
+
+int amq_binary_gemv_grouped(int64_t groups, const uint32_t* Wp, const float* alpha, int64_t m, int64_t n,
+                            int k_w, const uint32_t* Xp, const float* beta, int k_a, const float* bias,
+                            float* Y, void* stream) {
+  int st = check_product(Wp, m, n, k_w, Xp, 1, k_a);
+  if (st != AMQ_OK) return st;
+  if (!alpha || !beta || !Y || groups <= 0) return AMQ_ERR_INVALID;
+  if (groups > 65535) return AMQ_ERR_UNSUPPORTED;
+  amq::GemmArgs g = gemm_args(Wp, alpha, m, n, k_w, Xp, beta, 1, k_a, bias, 0, Y);
+  const int64_t wpr = amq_wpr(n);
+  g.groups = (int)groups;
+  g.g_Wp = (long long)k_w * m * wpr;
+  g.g_alpha = (long long)m * k_w;
+  g.g_Xp = (long long)k_a * wpr;
+  g.g_beta = k_a;
+  g.g_Y = m;
+  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+}
+
+size_t amq_lstm_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve(nullptr, I, H, B, k_a, 4, 1).total;
+}
+
+size_t amq_gru_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve(nullptr, I, H, B, k_a, 3, 2).total;
+}
+
+static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                            const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                            const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
+                            int T, float* h_out, float* c_out, float* hs_out, const StepWs& w,
+                            hipStream_t s) {
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{x, I, (int)I, (int)B, w.xp, w.beta_x};
+  q.seg[1] = amq::QuantSeg{h_prev, H, (int)H, (int)B, w.hp, w.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  int st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
+  st = hip_status(amq::launch_gemm(gx, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
+  st = hip_status(amq::launch_gemm(gh, s));
+  if (st != AMQ_OK) return st;
+  return hip_status(amq::launch_lstm_pointwise(w.pre0, c_prev, h_out, c_out, hs_out, B, H, s));
+}
+
+int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                  int64_t I, int64_t H, int k_w, const float* bias, const float* x, const float* h_prev,
+                  const float* c_prev, int64_t B, int k_a, int T, float* h_out, float* c_out,
+                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (!c_prev || !c_out) return AMQ_ERR_INVALID;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out, workspace,
+                      workspace_bytes, need);
+  if (st != AMQ_OK) return st;
+  StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
+  return lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, x, h_prev, c_prev, B, k_a, T, h_out,
+                          c_out, nullptr, w, static_cast<hipStream_t>(stream));
+}
+
+int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                      int64_t I, int64_t H, int k_w, const float* bias, const float* xs, int64_t steps,
+                      float* h, float* c, int64_t B, int k_a, int T, float* hs, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  if (!c || steps <= 0) return AMQ_ERR_INVALID;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, xs, h, B, k_a, T, h, workspace, workspace_bytes,
+                      need);
+  if (st != AMQ_OK) return st;
+  StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
+  for (int64_t t = 0; t < steps; ++t) {
+    st = lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, xs + t * B * I, h, c, B, k_a, T, h, c,
+                          hs ? hs + t * B * H : nullptr, w, static_cast<hipStream_t>(stream));
+    if (st != AMQ_OK) return st;
+  }
+  return AMQ_OK;
+}
+
+int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                 int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h, const float* x,
+                 const float* h_prev, int64_t B, int k_a, int T, float* h_out, void* workspace,
+                 size_t workspace_bytes, void* stream) {
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 3, 2).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out, workspace,
+                      workspace_bytes, need);
+  if (st != AMQ_OK) return st;
+  StepWs w = carve(workspace, I, H, B, k_a, 3, 2);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{x, I, (int)I, (int)B, w.xp, w.beta_x};
+  q.seg[1] = amq::QuantSeg{h_prev, H, (int)H, (int)B, w.hp, w.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias_x, 0, w.pre0);
+  st = hip_status(amq::launch_gemm(gx, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gh = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.hp, w.beta_h, B, k_a, bias_h, 0, w.pre1);
+  st = hip_status(amq::launch_gemm(gh, s));
+  if (st != AMQ_OK) return st;
+  return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Pointwise parts of the recurrent cells: gate pre-activations -> new state.
+// LSTM: Eq. 6 with gate row blocks i, f, o, g (sigmoid, sigmoid, sigmoid, tanh).
+// GRU: textbook cell with the reset gate applied to the hidden-side product of the candidate.
+#include "amq_device.h"
+#include "amq_launch.h"
+
+namespace amq {
+
+namespace {
+
+__global__ __launch_bounds__(256) void lstm_pointwise_kernel(const float* __restrict__ pre,
+                                                             const float* c_prev, float* h_out, float* c_out,
+                                                             float* hs_out, long long B, long long H) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= B * H) return;
+  const long long b = t / H, u = t - b * H;
+  const float* p = pre + b * 4 * H;
+  const float gi = sigmoidf_dev(p[u]);
+  const float gf = sigmoidf_dev(p[H + u]);
+  const float go = sigmoidf_dev(p[2 * H + u]);
+  const float gg = tanhf_dev(p[3 * H + u]);
+  const float c = fmaf(gf, c_prev[t], gi * gg);
+  const float h = go * tanhf_dev(c);
+  c_out[t] = c;
+  h_out[t] = h;
+  if (hs_out) hs_out[t] = h;
+}
+
+__global__ __launch_bounds__(256) void gru_pointwise_kernel(const float* __restrict__ pre_x,
+                                                            const float* __restrict__ pre_h, const float* h_prev,
+                                                            float* h_out, long long B, long long H) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= B * H) return;
+  const long long b = t / H, u = t - b * H;
+  const float* px = pre_x + b * 3 * H;
+  const float* ph = pre_h + b * 3 * H;
+  const float r = sigmoidf_dev(px[u] + ph[u]);
+  const float z = sigmoidf_dev(px[H + u] + ph[H + u]);
+  const float nn = tanhf_dev(fmaf(r, ph[2 * H + u], px[2 * H + u]));
+  h_out[t] = fmaf(z, h_prev[t] - nn, nn);  // (1 - z) * n + z * h_prev
+}
+
+}  // namespace
+
+hipError_t launch_lstm_pointwise(const float* pre, const float* c_prev, float* h_out, float* c_out,
+                                 float* hs_out, long long B, long long H, hipStream_t s) {
+  const long long total = B * H;
+  hipLaunchKernelGGL(lstm_pointwise_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pre,
+                     c_prev, h_out, c_out, hs_out, B, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_gru_pointwise(const float* pre_x, const float* pre_h, const float* h_prev, float* h_out,
+                                long long B, long long H, hipStream_t s) {
+  const long long total = B * H;
+  hipLaunchKernelGGL(gru_pointwise_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pre_x,
+                     pre_h, h_prev, h_out, B, H);
+  return hipGetLastError();
+}
+
+}  // namespace amq

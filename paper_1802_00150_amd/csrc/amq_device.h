@@ -1,0 +1,51 @@
+// Device-side helpers shared by the gfx950 kernels: wavefront (64-lane) reductions,
+// workgroup reductions through LDS, and small utilities.  HIP for CDNA4 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amq {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Butterfly sums over the 64 lanes; every lane ends with the total.
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Sum over a workgroup of NW waves.  `scratch` holds NW elements of T in LDS and may be
+// reused right after the call returns (two barriers inside).  NW == 1 needs no LDS.
+template <int NW, typename T>
+__device__ __forceinline__ T block_sum(T v, T* scratch) {
+  v = wave_sum(v);
+  if constexpr (NW > 1) {
+    __syncthreads();
+    if (lane_id() == 0) scratch[wave_id()] = v;
+    __syncthreads();
+    T t = scratch[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) t += scratch[i];
+    v = t;
+  }
+  return v;
+}
+
+__device__ __forceinline__ int popc4(uint4 a, uint4 b) {
+  return __popc(a.x ^ b.x) + __popc(a.y ^ b.y) + __popc(a.z ^ b.z) + __popc(a.w ^ b.w);
+}
+
+// Cell nonlinearities: the accurate library routines (the pointwise part of a step is tiny).
+__device__ __forceinline__ float sigmoidf_dev(float a) { return 1.0f / (1.0f + expf(-a)); }
+__device__ __forceinline__ float tanhf_dev(float a) { return tanhf(a); }
+
+}  // namespace amq

@@ -1,0 +1,64 @@
+// Host-side launch interface between the C ABI (amq_api.hip) and the kernel files.
+// Everything here is plain data plus one launch function per kernel family; argument
+// checking happens in the C ABI layer before any of these are called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amq {
+
+// ---- quantizer -------------------------------------------------------------------------
+enum { kQuantFull = 0, kQuantLsOnly = 1, kQuantBstOnly = 2 };
+
+struct QuantSeg {
+  const float* X;    // [count][ld]
+  long long ld;      // row stride in elements
+  int n;             // vector length
+  int count;         // number of vectors (0 = segment unused)
+  uint32_t* planes;  // [k][count][wpr(n)]
+  float* coef;       // [count][k]
+};
+
+// Up to two groups of vectors in one launch (x_t and h_{t-1} of a recurrent step).
+struct QuantArgs {
+  QuantSeg seg[2];
+  int T;
+  int mode;
+};
+
+hipError_t launch_quantize(const QuantArgs& a, int k, hipStream_t s);
+
+// ---- binary products -------------------------------------------------------------------
+struct GemmOperand {
+  const uint32_t* Wp;   // [k_w][m][wpr]
+  const float* alpha;   // [m][k_w]
+  const uint32_t* Xp;   // [k_a][batch][wpr]
+  const float* beta;    // [batch][k_a]
+  int n;                // vector length of this block
+};
+
+struct GemmArgs {
+  GemmOperand op;
+  long long m;
+  int batch;
+  int k_w, k_a;
+  const float* bias;   // [m] or null
+  int accumulate;
+  float* Y;            // [batch][m] or null
+  int32_t* D;          // [batch][m][k_w][k_a] or null (test hook)
+  // grouped batch-1 products: strides in elements between consecutive groups (0 when groups == 1)
+  int groups;
+  long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
+};
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+// ---- cells -----------------------------------------------------------------------------
+// pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU
+hipError_t launch_lstm_pointwise(const float* pre /*[B][4H]*/, const float* c_prev, float* h_out,
+                                 float* c_out, float* hs_out /*nullable*/, long long B, long long H,
+                                 hipStream_t s);
+hipError_t launch_gru_pointwise(const float* pre_x /*[B][3H]*/, const float* pre_h, const float* h_prev,
+                                float* h_out, long long B, long long H, hipStream_t s);
+
+}  // namespace amq

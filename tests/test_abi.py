@@ -1,0 +1,78 @@
+"""The C-ABI library loads and exports every symbol that include/amq.h declares; host-only
+helpers and argument validation work without a GPU (validation precedes any launch)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_1802_00150_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1802_00150_amd import build
+        build.build()
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "amq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(amq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(L):
+    names = declared_symbols()
+    assert len(names) >= 15
+    for name in names:
+        assert hasattr(L, name), name
+    from paper_1802_00150_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_host_helpers(L):
+    assert [L.amq_wpr(n) for n in (1, 128, 129, 300, 1024, 4096)] == [4, 4, 8, 12, 32, 128]
+    assert L.amq_wpr(0) == 0
+    assert b"gfx950" in L.amq_version()
+    assert L.amq_status_string(0) == b"ok"
+    assert L.amq_status_string(1) == b"invalid argument"
+    assert L.amq_lstm_workspace_bytes(1024, 1024, 64, 3) % 256 == 0
+    assert L.amq_lstm_workspace_bytes(1024, 1024, 64, 3) >= 64 * 4096 * 4 + 2 * 3 * 64 * 32 * 4
+    assert L.amq_gru_workspace_bytes(1024, 1024, 0, 2) == 0
+
+
+def test_validation_rejects_before_touching_the_device(L):
+    # fake (never dereferenced) aligned addresses: validation must fail on the host
+    p = C.c_void_p(0x10000)
+    null = C.c_void_p(0)
+    INVALID, UNSUPPORTED = 1, 2
+    assert L.amq_quantize_weights(null, 4, 4, 4, 2, 2, p, p, None) == INVALID
+    assert L.amq_quantize_weights(p, 4, 4, 4, 0, 2, p, p, None) == INVALID
+    assert L.amq_quantize_weights(p, 4, 4, 4, 5, 2, p, p, None) == INVALID
+    assert L.amq_quantize_weights(p, 4, 4, 4, 2, -1, p, p, None) == INVALID
+    assert L.amq_quantize_weights(p, 4, 8, 4, 2, 2, p, p, None) == INVALID          # ld < cols
+    assert L.amq_quantize_weights(p, 4, 4, 4, 2, 2, C.c_void_p(0x10004), p, None) == INVALID  # misaligned
+    assert L.amq_quantize_weights(p, 4, 16385, 16385, 2, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_quantize_activations(p, 0, 4, 2, 2, p, p, None) == INVALID
+    assert L.amq_binary_dots(p, 4, 4, 2, p, 1, 2, null, None) == INVALID
+    assert L.amq_binary_gemm(p, p, 4, 4, 2, p, p, 1, 9, None, 0, p, None) == INVALID
+    assert L.amq_binary_gemm(p, p, 4, (1 << 20) + 1, 2, p, p, 1, 2, None, 0, p, None) == UNSUPPORTED
+    assert L.amq_binary_gemv_grouped(70000, p, p, 4, 4, 2, p, p, 2, None, p, None) == UNSUPPORTED
+    ws = C.c_void_p(0x20000)
+    need = L.amq_lstm_workspace_bytes(8, 8, 1, 2)
+    assert L.amq_lstm_step(p, p, p, p, 8, 8, 2, None, p, p, p, 1, 2, 2, p, p, ws, need - 1, None) == INVALID
+    assert L.amq_lstm_step(p, p, p, p, 8, 8, 2, None, p, p, p, 1, 2, 2, p, p, C.c_void_p(0x20010), need,
+                           None) == INVALID
+    assert L.amq_lstm_step(p, p, p, p, 8, 8, 2, None, p, p, null, 1, 2, 2, p, p, ws, need, None) == INVALID
+    assert L.amq_gru_step(p, p, p, p, 8, 8, 2, None, None, p, p, 1, 2, 2, p, null, 0, None) == INVALID
+    assert L.amq_lstm_sequence(p, p, p, p, 8, 8, 2, None, p, 0, p, p, 1, 2, 2, None, ws, need, None) == INVALID
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_1802_00150_amd as amq
+    with pytest.raises(amq.AmqError):
+        amq.quantize_activations(torch.zeros(2, 8), 2, 2)

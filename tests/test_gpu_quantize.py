@@ -1,0 +1,169 @@
+"""GPU parity: the quantizer entry points against the CPU oracle, through the C ABI.
+
+Staged protocol (the method is discontinuous at interval boundaries): greedy only (T = 0);
+Eq. 5 with the oracle's codes; Alg. 1 with the oracle's coefficients (bit-exact); then the
+whole of Alg. 2.  Flipped codes are accepted only as binary32 near-ties and are counted.
+"""
+import functools
+
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import assert_coef_close, compare_codes, host, planes_host, to_dev
+
+pytestmark = pytest.mark.gpu
+
+LENGTHS = [1, 5, 63, 64, 65, 127, 128, 129, 300, 600, 1000, 1024, 2048, 2049, 4096, 5000, 16384]
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def amq():
+    import paper_1802_00150_amd as m
+    m.binding.lib()
+    return m
+
+
+@functools.lru_cache(maxsize=1)
+def heavy():
+    from paper_1802_00150_amd import inputs
+    return inputs.heavy_tailed()
+
+
+def make_batch(n, batch, seed, scale=1.0):
+    g = np.random.default_rng(seed)
+    X = (g.standard_normal((batch, n)) * scale).astype(np.float32)
+    if batch > 2:
+        X[1] = np.abs(X[1])            # one-sided: coefficients leave the natural order
+        X[2] = X[2] ** 3               # heavy tails
+    return X
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_greedy_only(amq, k):
+    for n in LENGTHS:
+        say("greedy k=%d n=%d" % (k, n))
+        X = make_batch(n, 5, 100 + n)
+        pr, ar = oracle.quantize_rows(X, k, 0)
+        pg, ag = amq.quantize_activations(to_dev(X), k, 0)
+        assert_coef_close(host(ag), ar)
+        flips, _ = compare_codes(X, planes_host(pg), pr, ar)
+        assert flips == 0
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_ls_given_oracle_codes(amq, k):
+    for n in LENGTHS:
+        say("ls k=%d n=%d" % (k, n))
+        X = make_batch(n, 5, 200 + n)
+        pr, a0 = oracle.quantize_rows(X, k, 0)
+        ref = np.stack([oracle.ls(X[r], np.stack([np.unpackbits(pr[i, r].view(np.uint8), bitorder="little")[:n]
+                                                  for i in range(k)]), a0[r])[0] for r in range(X.shape[0])])
+        got = amq.ls_update(to_dev(X), to_dev(pr), to_dev(a0))
+        assert_coef_close(host(got), ref)
+
+
+def test_ls_singular_rows_keep_coefficients(amq):
+    n, k = 200, 3
+    g = np.random.default_rng(7)
+    X = g.standard_normal((4, n)).astype(np.float32)
+    b = (g.random((4, n)) < 0.5).astype(np.uint8)
+    c = (g.random((4, n)) < 0.5).astype(np.uint8)
+    codes = [b, c, 1 - b]                                       # plane 3 = -plane 1: singular
+    planes = np.stack([np.stack([oracle.pack(p[r]) for r in range(4)]) for p in codes])
+    keep = g.standard_normal((4, k)).astype(np.float32)
+    got = amq.ls_update(to_dev(X), to_dev(planes), to_dev(keep))
+    assert np.array_equal(host(got), keep)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_bst_given_oracle_coefficients_is_bit_exact(amq, k):
+    g = np.random.default_rng(300 + k)
+    for n in LENGTHS:
+        say("bst k=%d n=%d" % (k, n))
+        X = make_batch(n, 6, 300 + n)
+        coef = g.standard_normal((6, k)).astype(np.float32)
+        coef[1] = np.abs(coef[1])
+        coef[2] = -np.sort(-np.abs(coef[2]))
+        if k > 1:
+            coef[3, -1] = coef[3, 0]               # equal coefficients: tied code values
+        coef[4, 0] = 0.0                            # zero coefficient: duplicated codes
+        coef[5] = 0.0
+        X[0, : min(n, 8)] = 0.0                     # entries exactly on the middle boundary
+        ref = np.stack([np.stack([oracle.pack(p) for p in oracle.bst(X[r], coef[r])]) for r in range(6)], axis=1)
+        got = planes_host(amq.bst_assign(to_dev(X), to_dev(coef)))
+        assert np.array_equal(got, ref)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+@pytest.mark.parametrize("T", [1, 2, 3])
+def test_alternating_whole(amq, k, T):
+    total_flips = 0
+    for n in LENGTHS:
+        say("alt k=%d T=%d n=%d" % (k, T, n))
+        X = make_batch(n, 7, 400 + n, scale=0.3)
+        pr, ar = oracle.quantize_rows(X, k, T)
+        pg, ag = amq.quantize_activations(to_dev(X), k, T)
+        flips, rows = compare_codes(X, planes_host(pg), pr, ar)
+        total_flips += flips
+        ok = np.ones(X.shape[0], bool)
+        if rows:
+            ok = ~(planes_host(pg) != pr).any(axis=(0, 2))
+        assert_coef_close(host(ag)[ok], ar[ok])
+    say("near-tie flips: %d" % total_flips)
+    assert total_flips <= 2
+
+
+def test_degenerate_vectors(amq):
+    n = 300
+    X = np.zeros((4, n), np.float32)
+    X[1] = 0.5
+    X[2] = np.where(np.arange(n) % 2 == 0, 0.25, -0.25)
+    X[3, 0] = 1.0
+    for k in (1, 2, 3, 4):
+        say("degenerate k=%d" % k)
+        pr, ar = oracle.quantize_rows(X, k, 2)
+        pg, ag = amq.quantize_activations(to_dev(X), k, 2)
+        assert np.array_equal(planes_host(pg), pr)
+        assert_coef_close(host(ag), ar)
+    assert np.all(host(ag)[0] == 0)
+
+
+def test_quantize_weights_strided_rows(amq):
+    g = np.random.default_rng(9)
+    big = (g.standard_normal((33, 700)) * 0.05).astype(np.float32)
+    W = big[:, 100:400]                                # 300 columns, row stride 700
+    pr, ar = oracle.quantize_rows(np.ascontiguousarray(W), 2, 2)
+    pg, ag = amq.quantize_weights(to_dev(big)[:, 100:400], 2, 2)
+    assert np.array_equal(planes_host(pg), pr)
+    assert_coef_close(host(ag), ar)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_weight_quantizer_heavy_tailed_full_size_sampled(amq, k):
+    # Config 5 at full size (16384 x 4096, heavy tails) in the launch the benchmark times; the
+    # oracle recomputes a sample of rows (first, last, and a spread in between).
+    W = heavy()
+    say("weights 16384x4096 k=%d" % k)
+    pg, ag = amq.quantize_weights(to_dev(W), k, 2)
+    rows = np.unique(np.concatenate([[0, 1, 16383], np.random.default_rng(k).integers(0, 16384, 96)]))
+    pr, ar = oracle.quantize_rows(W[rows], k, 2)
+    pgh = planes_host(pg)[:, rows]
+    flips, nrows = compare_codes(W[rows], pgh, pr, ar)
+    ok = ~(pgh != pr).any(axis=(0, 2))
+    assert_coef_close(host(ag)[rows][ok], ar[ok])
+    say("flips %d in %d rows" % (flips, nrows))
+    assert flips <= 2
+    # property that holds at any size: reconstruction error per row never above the greedy one
+    sel = rows[:16]
+    Wd = W[sel].astype(np.float64)
+    bits = np.unpackbits(pgh[:, :16].view(np.uint8), axis=2, bitorder="little")[:, :, :4096].astype(np.float64) * 2 - 1
+    rec = np.einsum("irn,ri->rn", bits, host(ag)[sel].astype(np.float64))
+    err = ((Wd - rec) ** 2).sum(1)
+    for t, r in enumerate(sel):
+        c0, a0 = oracle.greedy(W[r], k)
+        assert err[t] <= oracle.error(W[r], c0, a0) * (1 + 1e-6)
