@@ -134,10 +134,10 @@ def bench_gemm_kernel(amq, dev, m, n, k_w, k_a, batch, iters=200):
     alpha = torch.rand((m, k_w), generator=g).to(dev)
     beta = torch.rand((batch, k_a), generator=g).to(dev)
     Y = torch.empty((batch, m), device=dev)
-    ms = event_time_ms(lambda: amq.binary_gemm(Wp, alpha, n, Xp, beta, Y=None if False else None) if False else
-                       amq.binding.lib().amq_binary_gemm(Wp.data_ptr(), alpha.data_ptr(), m, n, k_w, Xp.data_ptr(),
-                                                         beta.data_ptr(), batch, k_a, None, 0, Y.data_ptr(),
-                                                         torch.cuda.current_stream().cuda_stream), iters, 20)
+    L = amq.binding.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    ms = event_time_ms(lambda: L.amq_binary_gemm(Wp.data_ptr(), alpha.data_ptr(), m, n, k_w, Xp.data_ptr(),
+                                                 beta.data_ptr(), batch, k_a, None, 0, Y.data_ptr(), s), iters, 20)
     return ms
 
 
