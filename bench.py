@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized LSTM step (and the kernels it is made of) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lstm_b64] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--sections a,b,...] [--no-cpu]
 
 A step is one pass of the whole hot path -- on-line quantization of x_t and h_{t-1}, the
 binary products with both weight blocks, the coefficient epilogue and the cell -- over one
@@ -233,18 +233,34 @@ def cpu_baseline_lstm(cfg, budget_s=15.0):
                       % (n, B, H, k_w, k_a)}
 
 
+SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "quantizer", "cpu"]
+
+
+def copy_probe(dev, nbytes=512 << 20, iters=10):
+    """A plain device copy of known size: the yardstick that scales the HBM byte counters."""
+    import torch
+    src = torch.empty(nbytes // 4, dtype=torch.int32, device=dev).random_()
+    dst = torch.empty_like(src)
+    ms = event_time_ms(lambda: dst.copy_(src), iters, 2)
+    return {"bytes_read": nbytes, "bytes_written": nbytes, "ms": ms, "GBps": 2 * nbytes / (ms * 1e-3) / 1e9}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=700)
     ap.add_argument("--warmup", type=int, default=70)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--quick", action="store_true", help="primary workload only")
+    ap.add_argument("--sections", default=",".join(SECTIONS),
+                    help="comma list out of %s, plus copy_probe (for counter calibration)" % SECTIONS)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported "
               "(no sharding or collectives are part of it)" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    sections = set(args.sections.split(","))
+    if args.no_cpu:
+        sections.discard("cpu")
 
     import torch
     import paper_1802_00150_amd as amq
@@ -254,38 +270,44 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    # ---- primary: config 3, LSTM 1024/1024, batch 64, W3/A3, T=2
-    cfg = inputs.lstm_large()
-    ms_step, q = bench_lstm_steps(amq, cfg, dev, args.steps, args.warmup)
-    I, H, B, k_w, k_a = cfg["I"], cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"]
-
-    # dominant kernel of that step: the binary GEMM (two launches per step, x block and h block)
-    ms_gemm = bench_gemm_kernel(amq, dev, 4 * H, H, k_w, k_a, B)
-    macs, lane_ops, _ = gemm_algorithmic(4 * H, H, k_w, k_a, B)
-    achieved = lane_ops / (ms_gemm * 1e-3) / 1e12
-    roofline = {"kernel": "binary GEMM 4096x1024 W3/A3 B=64 (xor+popcount)", "bound": "alu",
-                "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "TOP/s (integer lane-ops)",
-                "frac": achieved / VALU_PEAK_TOPS, "traffic": None, "launch_ms": ms_gemm,
-                "bit_macs_per_launch": macs}
-
-    out = {"metric": "quantized LSTM steps/sec (batch 64)", "value": 1e3 / ms_step, "unit": "steps/s",
-           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+    out = {"metric": "quantized LSTM steps/sec (batch 64)", "value": None, "unit": "steps/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": None,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32 popcount + f32",
            "data": "synthetic",
            "config": {"workload": "config 3: LSTM input 1024 hidden 1024, batch 64, 35-step sequences, "
                                   "weights row-wise 3-bit, activations 3-bit on line, T=2",
-                      "global_batch": B, "seq_len": 35},
-           "roofline": roofline}
-
+                      "global_batch": 64, "seq_len": 35}}
     also = {}
-    if not args.quick:
-        # ---- batch-1 LSTM, config 1 (hidden 300): per-step launches and one call per sequence
+    cfg = inputs.lstm_large()
+
+    if "primary" in sections:
+        # config 3, LSTM 1024/1024, batch 64, W3/A3, T=2: whole steps, state carried on the GPU
+        ms_step, _ = bench_lstm_steps(amq, cfg, dev, args.steps, args.warmup)
+        H, B, k_w, k_a = cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"]
+        out["value"] = 1e3 / ms_step
+        out["ms_per_step"] = ms_step
+        # dominant kernel of that step: the binary GEMM (x block and h block, same shape)
+        ms_gemm = bench_gemm_kernel(amq, dev, 4 * H, H, k_w, k_a, B)
+        macs, lane_ops, _ = gemm_algorithmic(4 * H, H, k_w, k_a, B)
+        achieved = lane_ops / (ms_gemm * 1e-3) / 1e12
+        out["roofline"] = {"kernel": "binary GEMM 4096x1024 W3/A3 B=64 (xor+popcount)", "bound": "alu",
+                           "achieved": achieved, "peak": VALU_PEAK_TOPS, "unit": "TOP/s (integer lane-ops)",
+                           "frac": achieved / VALU_PEAK_TOPS, "traffic": None, "launch_ms": ms_gemm,
+                           "bit_macs_per_launch": macs}
+
+    if "lstm_b1" in sections:
+        # batch-1 LSTM, config 1 (hidden 300): per-step launches and one call per sequence
         c1 = inputs.lstm_small()
         ms1, _ = bench_lstm_steps(amq, c1, dev, 700, 70)
         ms1_seq = bench_lstm_sequence(amq, c1, dev, 20, 2)
         also["lstm_b1_hidden300_steps_per_s"] = 1e3 / ms1
         also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 / ms1_seq
-        # ---- batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency
+        cb = inputs.lstm_large(B=1)
+        msb, _ = bench_lstm_steps(amq, cb, dev, 700, 70)
+        also["lstm_b1_hidden1024_w3a3_steps_per_s"] = 1e3 / msb
+
+    if "gemv" in sections:
+        # batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency
         for k in (2, 3):
             ms, G, nbytes = bench_gemv_stream(amq, dev, 4096, 1024, k, k)
             gbps = nbytes / (ms * 1e-3) / 1e9
@@ -296,19 +318,26 @@ def main():
                                         "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launch_ms": ms,
                                         "bytes_per_launch": nbytes}
             also["gemv_b1_w%da%d_warm_call_us" % (k, k)] = bench_gemv_warm(amq, dev, 4096, 1024, k) * 1e3
+
+    if "gemm" in sections:
         for b in (8, 64):
             for k in (2, 3):
                 ms = bench_gemm_kernel(amq, dev, 4096, 1024, k, k, b)
                 also["gemm_b%d_w%da%d_us" % (b, k, k)] = ms * 1e3
-        # ---- config 4: GRU step + projection
+
+    if "gru" in sections:
         also["gru_b256_with_projection_steps_per_s"] = 1e3 / bench_gru(amq, dev, 100, 10)
-        # ---- config 5: offline weight quantizer
+
+    if "quantizer" in sections:
         for k in (1, 2, 3, 4):
             ms, nbytes = bench_quantizer(amq, dev, k)
             also["quantize_weights_16384x4096_k%d_GBps" % k] = nbytes / (ms * 1e-3) / 1e9
-    out["also"] = also
 
-    if not args.no_cpu:
+    if "copy_probe" in sections:
+        also["copy_probe"] = copy_probe(dev)
+
+    out["also"] = also
+    if "cpu" in sections:
         out["cpu_baseline"] = cpu_baseline_lstm(cfg)
     print(json.dumps(out))
 

@@ -79,6 +79,24 @@ amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64
   return g;
 }
 
+// One quantized product: the register-resident kernel for small batches, the general one otherwise.
+int run_product(const amq::GemmArgs& g, hipStream_t s) {
+  if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch)) {
+    amq::BmvArgs b{};
+    b.blk[0] = amq::BmvBlock{g.op.Wp, g.op.alpha, g.op.Xp, g.op.beta, g.op.n};
+    b.m = g.m;
+    b.H = 0;
+    b.batch = g.batch;
+    b.bias0 = g.bias;
+    b.accumulate = g.accumulate;
+    b.Y = g.Y;
+    b.groups = g.groups;
+    b.g_Wp = g.g_Wp; b.g_alpha = g.g_alpha; b.g_Xp = g.g_Xp; b.g_beta = g.g_beta; b.g_Y = g.g_Y;
+    return hip_status(amq::launch_bmv(b, g.k_w, g.k_a, amq::kEpiStore, s));
+  }
+  return hip_status(amq::launch_gemm(g, s));
+}
+
 int check_product(const void* Wp, int64_t m, int64_t n, int k_w, const void* Xp, int64_t batch, int k_a) {
   if (!Wp || !Xp) return AMQ_ERR_INVALID;
   if (!bits_ok(k_w) || !bits_ok(k_a) || m <= 0 || n <= 0 || batch <= 0) return AMQ_ERR_INVALID;
@@ -158,7 +176,7 @@ int amq_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n
   if (st != AMQ_OK) return st;
   if (!alpha || !beta || !Y) return AMQ_ERR_INVALID;
   amq::GemmArgs g = gemm_args(Wp, alpha, m, n, k_w, Xp, beta, batch, k_a, bias, accumulate ? 1 : 0, Y);
-  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+  return run_product(g, static_cast<hipStream_t>(stream));
 }
 
 int amq_binary_gemv(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
@@ -182,7 +200,7 @@ int amq_binary_gemv_grouped(int64_t groups, const uint32_t* Wp, const float* alp
   g.g_Xp = (long long)k_a * wpr;
   g.g_beta = k_a;
   g.g_Y = m;
-  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+  return run_product(g, static_cast<hipStream_t>(stream));
 }
 
 size_t amq_lstm_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
@@ -207,11 +225,26 @@ static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uin
   q.mode = amq::kQuantFull;
   int st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
+  if (amq::bmv_supported((int)I, (int)H, k_a, B)) {
+    amq::BmvArgs b{};
+    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
+    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
+    b.m = 4 * H;
+    b.H = H;
+    b.batch = (int)B;
+    b.bias0 = bias;
+    b.c_prev = c_prev;
+    b.h_out = h_out;
+    b.c_out = c_out;
+    b.hs_out = hs_out;
+    b.groups = 1;
+    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
+  }
   amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
-  st = hip_status(amq::launch_gemm(gx, s));
+  st = run_product(gx, s);
   if (st != AMQ_OK) return st;
   amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
-  st = hip_status(amq::launch_gemm(gh, s));
+  st = run_product(gh, s);
   if (st != AMQ_OK) return st;
   return hip_status(amq::launch_lstm_pointwise(w.pre0, c_prev, h_out, c_out, hs_out, B, H, s));
 }
@@ -265,11 +298,25 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   q.mode = amq::kQuantFull;
   st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
+  if (amq::bmv_supported((int)I, (int)H, k_a, B)) {
+    amq::BmvArgs b{};
+    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
+    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
+    b.m = 3 * H;
+    b.H = H;
+    b.batch = (int)B;
+    b.bias0 = bias_x;
+    b.bias1 = bias_h;
+    b.h_prev = h_prev;
+    b.h_out = h_out;
+    b.groups = 1;
+    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiGru, s));
+  }
   amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias_x, 0, w.pre0);
-  st = hip_status(amq::launch_gemm(gx, s));
+  st = run_product(gx, s);
   if (st != AMQ_OK) return st;
   amq::GemmArgs gh = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.hp, w.beta_h, B, k_a, bias_h, 0, w.pre1);
-  st = hip_status(amq::launch_gemm(gh, s));
+  st = run_product(gh, s);
   if (st != AMQ_OK) return st;
   return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
 }

@@ -1,0 +1,248 @@
+// Small-batch binary matrix-vector products with the weight planes held in registers and the
+// epilogue fused: plain output (streaming GEMV), LSTM cell (Eq. 6) or GRU cell.
+//
+// Mapping (gfx950, wave64): a weight row of one plane is cpr = wpr/4 16-byte chunks.  A wave
+// is split into groups of G = 2^lg lanes (G >= cpr, at most 64); a group owns R = 64/G
+// consecutive rows (or hidden units), a lane one chunk.  One wave-wide dwordx4 load therefore
+// reads up to 1 KiB of contiguous plane memory.  A wave loads, up front, NSEG row segments
+// (gate blocks, or consecutive row groups when streaming) x NBLK operand blocks (x and h) x
+// KW planes -- all loads in flight before the first use -- and then loops over the batch with
+// the activation planes staged in LDS.  Per batch entry a lane forms the float partial
+//   sum_i alpha_i * sum_j beta_j * (bits_in_chunk - 2 * popcount(w_i xor x_j))
+// and the G lanes of a group are summed with DPP butterflies (one value per segment instead of
+// KW*KA integers).  Lane 0 of the group applies bias / cell nonlinearity and stores.
+#include "amq_device.h"
+#include "amq_launch.h"
+
+namespace amq {
+
+namespace {
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+  return v + __int_as_float(t);
+}
+
+// Sum over aligned groups of 2^lg lanes; every lane of a group ends with the group's total.
+__device__ __forceinline__ float group_sum(float v, int lg) {
+  if (lg >= 1) v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+  if (lg >= 2) v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+  if (lg >= 3) v = dpp_add<0x141>(v);  // row_half_mirror
+  if (lg >= 4) v = dpp_add<0x140>(v);  // row_mirror
+  if (lg >= 5) v += __shfl_xor(v, 16, kWave);
+  if (lg >= 6) v += __shfl_xor(v, 32, kWave);
+  return v;
+}
+
+template <int KW, int KA, int NSEG, int NBLK, int EPI>
+__global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
+  extern __shared__ uint4 xs[];
+  const int lane = lane_id(), wv = wave_id();
+  const int lg = a.lg;
+  const int G = 1 << lg, R = 64 >> lg;
+  const int sub = lane & (G - 1), rloc = lane >> lg;
+  const long long wave_global = (long long)blockIdx.x * 4 + wv;
+  const long long grp = blockIdx.y;
+  const int batch = a.batch;
+
+  int cpr[NBLK], xoff[NBLK], bits[NBLK];
+  {
+    int off = 0;
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+      const int n = a.blk[k].n;
+      cpr[k] = (n + 127) >> 7;
+      xoff[k] = off;
+      const int total = KA * batch * cpr[k];
+      const uint4* src = reinterpret_cast<const uint4*>(a.blk[k].Xp + grp * a.g_Xp);
+      for (int t = threadIdx.x; t < total; t += 256) xs[off + t] = src[t];
+      off += total;
+      const int left = n - 128 * sub;
+      bits[k] = left < 0 ? 0 : (left > 128 ? 128 : left);
+    }
+  }
+  __syncthreads();
+
+  // rows of this lane: segment s covers rows seg_base(s) + [0, R)
+  const long long nrow = (EPI == kEpiStore) ? a.m : a.H;  // rows per segment space
+  long long row[NSEG];
+  bool ok[NSEG];
+#pragma unroll
+  for (int s = 0; s < NSEG; ++s) {
+    long long r;
+    if (EPI == kEpiStore) {
+      r = (wave_global * NSEG + s) * R + rloc;
+      ok[s] = r < a.m;
+    } else {
+      const long long u = wave_global * R + rloc;
+      ok[s] = u < a.H;
+      r = (long long)s * a.H + u;
+    }
+    row[s] = ok[s] ? r : 0;
+  }
+  {
+    const long long first = (EPI == kEpiStore) ? wave_global * NSEG * R : wave_global * R;
+    if (first >= nrow) return;  // whole wave past the end (after the barrier)
+  }
+
+  uint4 wq[NBLK][NSEG][KW];
+  float al[NBLK][NSEG][KW];
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) {
+    const int wpr = cpr[k] * 4;
+    const uint32_t* Wp = a.blk[k].Wp + grp * a.g_Wp;
+    const float* alpha = a.blk[k].alpha + grp * a.g_alpha;
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s)
+#pragma unroll
+      for (int i = 0; i < KW; ++i) {
+        wq[k][s][i] = (sub < cpr[k]) ? reinterpret_cast<const uint4*>(Wp + ((long long)i * a.m + row[s]) * wpr)[sub]
+                                     : make_uint4(0, 0, 0, 0);
+        al[k][s][i] = alpha[row[s] * KW + i];
+      }
+  }
+
+  for (int b = 0; b < batch; ++b) {
+    float part[NBLK][NSEG];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+      uint4 xq[KA];
+      float bt[KA];
+      const float* beta = a.blk[k].beta + grp * a.g_beta;
+#pragma unroll
+      for (int j = 0; j < KA; ++j) {
+        xq[j] = (sub < cpr[k]) ? xs[xoff[k] + (j * batch + b) * cpr[k] + sub] : make_uint4(0, 0, 0, 0);
+        bt[j] = beta[b * KA + j];
+      }
+#pragma unroll
+      for (int s = 0; s < NSEG; ++s) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          float inner = 0.0f;
+#pragma unroll
+          for (int j = 0; j < KA; ++j)
+            inner = fmaf(bt[j], (float)(bits[k] - 2 * popc4(wq[k][s][i], xq[j])), inner);
+          acc = fmaf(al[k][s][i], inner, acc);
+        }
+        part[k][s] = acc;
+      }
+    }
+
+    if constexpr (EPI == kEpiStore) {
+#pragma unroll
+      for (int s = 0; s < NSEG; ++s) {
+        const float v = group_sum(part[0][s], lg);
+        if (sub == 0 && ok[s]) {
+          float* yp = a.Y + grp * a.g_Y + (long long)b * a.m + row[s];
+          float y = v + (a.bias0 ? a.bias0[row[s]] : 0.0f);
+          if (a.accumulate) y += *yp;
+          *yp = y;
+        }
+      }
+    } else if constexpr (EPI == kEpiLstm) {
+      float pre[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) pre[s] = group_sum(part[0][s] + part[1][s], lg);
+      if (sub == 0 && ok[0]) {
+        const long long u = row[0];
+        if (a.bias0) {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) pre[s] += a.bias0[s * a.H + u];
+        }
+        const long long t = (long long)b * a.H + u;
+        const float gi = sigmoidf_dev(pre[0]);
+        const float gf = sigmoidf_dev(pre[1]);
+        const float go = sigmoidf_dev(pre[2]);
+        const float gg = tanhf_dev(pre[3]);
+        const float c = fmaf(gf, a.c_prev[t], gi * gg);
+        const float h = go * tanhf_dev(c);
+        a.c_out[t] = c;
+        a.h_out[t] = h;
+        if (a.hs_out) a.hs_out[t] = h;
+      }
+    } else {  // GRU: segments r, z, n; the candidate keeps its x-side and h-side sums apart
+      const float sr = group_sum(part[0][0] + part[1][0], lg);
+      const float sz = group_sum(part[0][1] + part[1][1], lg);
+      const float nx = group_sum(part[0][2], lg);
+      const float nh = group_sum(part[1][2], lg);
+      if (sub == 0 && ok[0]) {
+        const long long u = row[0];
+        float bxr = 0.f, bxz = 0.f, bxn = 0.f, bhr = 0.f, bhz = 0.f, bhn = 0.f;
+        if (a.bias0) { bxr = a.bias0[u]; bxz = a.bias0[a.H + u]; bxn = a.bias0[2 * a.H + u]; }
+        if (a.bias1) { bhr = a.bias1[u]; bhz = a.bias1[a.H + u]; bhn = a.bias1[2 * a.H + u]; }
+        const long long t = (long long)b * a.H + u;
+        const float r = sigmoidf_dev(sr + bxr + bhr);
+        const float z = sigmoidf_dev(sz + bxz + bhz);
+        const float nn = tanhf_dev(fmaf(r, nh + bhn, nx + bxn));
+        a.h_out[t] = fmaf(z, a.h_prev[t] - nn, nn);
+      }
+    }
+  }
+}
+
+template <int KW, int KA, int NSEG, int NBLK, int EPI>
+hipError_t launch_one(const BmvArgs& a, long long waves, size_t lds, hipStream_t s) {
+  const long long blocks = (waves + 3) / 4;
+  hipLaunchKernelGGL((bmv_kernel<KW, KA, NSEG, NBLK, EPI>), dim3((unsigned)blocks, (unsigned)a.groups),
+                     dim3(256), lds, s, a);
+  return hipGetLastError();
+}
+
+template <int KW, int KA>
+hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s) {
+  const int R = 64 >> a.lg;
+  size_t lds = 0;
+  const int nblk = (epi == kEpiStore) ? 1 : 2;
+  for (int k = 0; k < nblk; ++k) lds += (size_t)KA * a.batch * ((a.blk[k].n + 127) / 128) * 16;
+  switch (epi) {
+    case kEpiStore: {
+      // four row groups per wave (all loads in flight) when there are enough rows to fill the
+      // chip that way; one row group per wave for small products, where parallelism matters more
+      const long long waves4 = (a.m + 4LL * R - 1) / (4LL * R);
+      if (waves4 * a.groups >= 2048) return launch_one<KW, KA, 4, 1, kEpiStore>(a, waves4, lds, s);
+      return launch_one<KW, KA, 1, 1, kEpiStore>(a, (a.m + R - 1) / R, lds, s);
+    }
+    case kEpiLstm: return launch_one<KW, KA, 4, 2, kEpiLstm>(a, (a.H + R - 1) / R, lds, s);
+    case kEpiGru: return launch_one<KW, KA, 3, 2, kEpiGru>(a, (a.H + R - 1) / R, lds, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int KW>
+hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s) {
+  switch (k_a) {
+    case 1: return launch_epi<KW, 1>(a, epi, s);
+    case 2: return launch_epi<KW, 2>(a, epi, s);
+    case 3: return launch_epi<KW, 3>(a, epi, s);
+    case 4: return launch_epi<KW, 4>(a, epi, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool bmv_supported(int n0, int n1, int k_a, long long batch) {
+  const int c0 = (n0 + 127) / 128, c1 = (n1 + 127) / 128;
+  if (c0 > 64 || c1 > 64 || batch > kBmvMaxBatch) return false;
+  return (size_t)k_a * batch * (c0 + c1) * 16 <= 48 * 1024;
+}
+
+hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s) {
+  int nmax = a.blk[0].n;
+  if (epi != kEpiStore && a.blk[1].n > nmax) nmax = a.blk[1].n;
+  const int cpr = (nmax + 127) / 128;
+  int lg = 0;
+  while ((1 << lg) < cpr) ++lg;
+  a.lg = lg;
+  switch (k_w) {
+    case 1: return launch_ka<1>(a, k_a, epi, s);
+    case 2: return launch_ka<2>(a, k_a, epi, s);
+    case 3: return launch_ka<3>(a, k_a, epi, s);
+    case 4: return launch_ka<4>(a, k_a, epi, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace amq

@@ -53,6 +53,41 @@ struct GemmArgs {
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
+// ---- small-batch products with weights in registers and fused epilogues --------------------
+enum { kEpiStore = 0, kEpiLstm = 1, kEpiGru = 2 };
+constexpr int kBmvMaxBatch = 16;
+
+struct BmvBlock {
+  const uint32_t* Wp;   // [k_w][m][wpr(n)]
+  const float* alpha;   // [m][k_w]
+  const uint32_t* Xp;   // [k_a][batch][wpr(n)]
+  const float* beta;    // [batch][k_a]
+  int n;
+};
+
+struct BmvArgs {
+  BmvBlock blk[2];      // x block, h block (store mode uses blk[0] only)
+  long long m;          // rows per plane (4H for the LSTM, 3H for the GRU)
+  long long H;          // hidden units (cell modes)
+  int batch;
+  const float* bias0;   // store: [m]; LSTM: [4H]; GRU: bias_x [3H]   (nullable)
+  const float* bias1;   // GRU: bias_h [3H] (nullable)
+  int accumulate;       // store mode
+  float* Y;             // store mode: [batch][m]
+  const float* c_prev;  // LSTM
+  const float* h_prev;  // GRU
+  float* h_out;
+  float* c_out;
+  float* hs_out;        // LSTM, nullable
+  int lg;               // filled by launch_bmv
+  int groups;           // store mode: independent products in one launch (1 otherwise)
+  long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
+};
+
+// true if the register-resident kernel can take these vector lengths / batch
+bool bmv_supported(int n0, int n1, int k_a, long long batch);
+hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s);
+
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU
 hipError_t launch_lstm_pointwise(const float* pre /*[B][4H]*/, const float* c_prev, float* h_out,
