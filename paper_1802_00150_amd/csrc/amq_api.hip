@@ -79,21 +79,35 @@ amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64
   return g;
 }
 
-// One quantized product: the register-resident kernel for small batches, the general one otherwise.
+// Matrix-core product: fp4 kernel when the vectors fit one 1024-entry chunk, int8 kernel otherwise.
+hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, hipStream_t s) {
+  if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s);
+  return amq::launch_mfma(b, k_w, k_a, epi, s);
+}
+
+amq::BmvArgs store_args(const amq::GemmArgs& g) {
+  amq::BmvArgs b{};
+  b.blk[0] = amq::BmvBlock{g.op.Wp, g.op.alpha, g.op.Xp, g.op.beta, g.op.n};
+  b.m = g.m;
+  b.H = 0;
+  b.batch = g.batch;
+  b.bias0 = g.bias;
+  b.accumulate = g.accumulate;
+  b.Y = g.Y;
+  b.D = g.D;
+  b.groups = g.groups;
+  b.g_Wp = g.g_Wp; b.g_alpha = g.g_alpha; b.g_Xp = g.g_Xp; b.g_beta = g.g_beta; b.g_Y = g.g_Y;
+  return b;
+}
+
+// One quantized product.  Batch <= 16: weights-in-registers popcount kernel (memory-bound
+// regime).  Larger batches: the int8 matrix-core kernel (dense contraction).  The general
+// popcount kernel covers what is left (very long vectors at small batch, small-batch integer dots).
 int run_product(const amq::GemmArgs& g, hipStream_t s) {
-  if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch)) {
-    amq::BmvArgs b{};
-    b.blk[0] = amq::BmvBlock{g.op.Wp, g.op.alpha, g.op.Xp, g.op.beta, g.op.n};
-    b.m = g.m;
-    b.H = 0;
-    b.batch = g.batch;
-    b.bias0 = g.bias;
-    b.accumulate = g.accumulate;
-    b.Y = g.Y;
-    b.groups = g.groups;
-    b.g_Wp = g.g_Wp; b.g_alpha = g.g_alpha; b.g_Xp = g.g_Xp; b.g_beta = g.g_beta; b.g_Y = g.g_Y;
-    return hip_status(amq::launch_bmv(b, g.k_w, g.k_a, amq::kEpiStore, s));
-  }
+  if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch))
+    return hip_status(amq::launch_bmv(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s));
+  if (g.groups == 1 && g.batch > amq::kBmvMaxBatch && amq::mfma_supported(g.batch))
+    return hip_status(launch_matrix_core(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s));
   return hip_status(amq::launch_gemm(g, s));
 }
 
@@ -164,9 +178,12 @@ int amq_binary_dots(const uint32_t* Wp, int64_t m, int64_t n, int k_w, const uin
   int st = check_product(Wp, m, n, k_w, Xp, batch, k_a);
   if (st != AMQ_OK) return st;
   if (!D) return AMQ_ERR_INVALID;
-  amq::GemmArgs g = gemm_args(Wp, nullptr, m, n, k_w, Xp, nullptr, batch, k_a, nullptr, 0, nullptr);
+  // the kernels read coefficients unconditionally; in this integer-only mode they point at any
+  // readable memory of sufficient size (the weight planes) and their values are never used
+  const float* dummy = reinterpret_cast<const float*>(Wp);
+  amq::GemmArgs g = gemm_args(Wp, dummy, m, n, k_w, Xp, dummy, batch, k_a, nullptr, 0, nullptr);
   g.D = D;
-  return hip_status(amq::launch_gemm(g, static_cast<hipStream_t>(stream)));
+  return run_product(g, static_cast<hipStream_t>(stream));
 }
 
 int amq_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
@@ -240,6 +257,21 @@ static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uin
     b.groups = 1;
     return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
   }
+  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B)) {
+    amq::BmvArgs b{};
+    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
+    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
+    b.m = 4 * H;
+    b.H = H;
+    b.batch = (int)B;
+    b.bias0 = bias;
+    b.c_prev = c_prev;
+    b.h_out = h_out;
+    b.c_out = c_out;
+    b.hs_out = hs_out;
+    b.groups = 1;
+    return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiLstm, s));
+  }
   amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
   st = run_product(gx, s);
   if (st != AMQ_OK) return st;
@@ -311,6 +343,20 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
     b.h_out = h_out;
     b.groups = 1;
     return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiGru, s));
+  }
+  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B)) {
+    amq::BmvArgs b{};
+    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
+    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
+    b.m = 3 * H;
+    b.H = H;
+    b.batch = (int)B;
+    b.bias0 = bias_x;
+    b.bias1 = bias_h;
+    b.h_prev = h_prev;
+    b.h_out = h_out;
+    b.groups = 1;
+    return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiGru, s));
   }
   amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias_x, 0, w.pre0);
   st = run_product(gx, s);

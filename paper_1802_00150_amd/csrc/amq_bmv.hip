@@ -54,15 +54,11 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
       const int n = a.blk[k].n;
       cpr[k] = (n + 127) >> 7;
       xoff[k] = off;
-      const int total = KA * batch * cpr[k];
-      const uint4* src = reinterpret_cast<const uint4*>(a.blk[k].Xp + grp * a.g_Xp);
-      for (int t = threadIdx.x; t < total; t += 256) xs[off + t] = src[t];
-      off += total;
+      off += KA * batch * cpr[k];
       const int left = n - 128 * sub;
       bits[k] = left < 0 ? 0 : (left > 128 ? 128 : left);
     }
   }
-  __syncthreads();
 
   // rows of this lane: segment s covers rows seg_base(s) + [0, R)
   const long long nrow = (EPI == kEpiStore) ? a.m : a.H;  // rows per segment space
@@ -81,11 +77,8 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
     }
     row[s] = ok[s] ? r : 0;
   }
-  {
-    const long long first = (EPI == kEpiStore) ? wave_global * NSEG * R : wave_global * R;
-    if (first >= nrow) return;  // whole wave past the end (after the barrier)
-  }
 
+  // weight planes and coefficients first: the longest loads go out before anything waits
   uint4 wq[NBLK][NSEG][KW];
   float al[NBLK][NSEG][KW];
 #pragma unroll
@@ -102,8 +95,43 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
         al[k][s][i] = alpha[row[s] * KW + i];
       }
   }
+  // biases of this lane's rows (loop-invariant over the batch)
+  float bs0[NSEG], bs1[NSEG];
+#pragma unroll
+  for (int s = 0; s < NSEG; ++s) {
+    bs0[s] = a.bias0 ? a.bias0[row[s]] : 0.0f;
+    bs1[s] = (EPI == kEpiGru && a.bias1) ? a.bias1[row[s]] : 0.0f;
+  }
+
+  // activation planes of every batch entry into LDS
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) {
+    const int total = KA * batch * cpr[k];
+    const uint4* src = reinterpret_cast<const uint4*>(a.blk[k].Xp + grp * a.g_Xp);
+    for (int t = threadIdx.x; t < total; t += 256) xs[xoff[k] + t] = src[t];
+  }
+  __syncthreads();
+  {
+    const long long first = (EPI == kEpiStore) ? wave_global * NSEG * R : wave_global * R;
+    if (first >= nrow) return;  // whole wave past the end (after the barrier)
+  }
 
   for (int b = 0; b < batch; ++b) {
+    // previous state / old output of this batch entry, requested before the popcount work
+    float prev[NSEG];
+#pragma unroll
+    for (int s = 0; s < NSEG; ++s) prev[s] = 0.0f;
+    if (sub == 0) {
+      if constexpr (EPI == kEpiStore) {
+        if (a.accumulate) {
+#pragma unroll
+          for (int s = 0; s < NSEG; ++s)
+            if (ok[s]) prev[s] = a.Y[grp * a.g_Y + (long long)b * a.m + row[s]];
+        }
+      } else if (ok[0]) {
+        prev[0] = (EPI == kEpiLstm) ? a.c_prev[(long long)b * a.H + row[0]] : a.h_prev[(long long)b * a.H + row[0]];
+      }
+    }
     float part[NBLK][NSEG];
 #pragma unroll
     for (int k = 0; k < NBLK; ++k) {
@@ -135,10 +163,7 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
       for (int s = 0; s < NSEG; ++s) {
         const float v = group_sum(part[0][s], lg);
         if (sub == 0 && ok[s]) {
-          float* yp = a.Y + grp * a.g_Y + (long long)b * a.m + row[s];
-          float y = v + (a.bias0 ? a.bias0[row[s]] : 0.0f);
-          if (a.accumulate) y += *yp;
-          *yp = y;
+          a.Y[grp * a.g_Y + (long long)b * a.m + row[s]] = v + bs0[s] + prev[s];
         }
       }
     } else if constexpr (EPI == kEpiLstm) {
@@ -147,16 +172,14 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
       for (int s = 0; s < 4; ++s) pre[s] = group_sum(part[0][s] + part[1][s], lg);
       if (sub == 0 && ok[0]) {
         const long long u = row[0];
-        if (a.bias0) {
 #pragma unroll
-          for (int s = 0; s < 4; ++s) pre[s] += a.bias0[s * a.H + u];
-        }
+        for (int s = 0; s < 4; ++s) pre[s] += bs0[s];
         const long long t = (long long)b * a.H + u;
         const float gi = sigmoidf_dev(pre[0]);
         const float gf = sigmoidf_dev(pre[1]);
         const float go = sigmoidf_dev(pre[2]);
         const float gg = tanhf_dev(pre[3]);
-        const float c = fmaf(gf, a.c_prev[t], gi * gg);
+        const float c = fmaf(gf, prev[0], gi * gg);
         const float h = go * tanhf_dev(c);
         a.c_out[t] = c;
         a.h_out[t] = h;
@@ -168,15 +191,11 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
       const float nx = group_sum(part[0][2], lg);
       const float nh = group_sum(part[1][2], lg);
       if (sub == 0 && ok[0]) {
-        const long long u = row[0];
-        float bxr = 0.f, bxz = 0.f, bxn = 0.f, bhr = 0.f, bhz = 0.f, bhn = 0.f;
-        if (a.bias0) { bxr = a.bias0[u]; bxz = a.bias0[a.H + u]; bxn = a.bias0[2 * a.H + u]; }
-        if (a.bias1) { bhr = a.bias1[u]; bhz = a.bias1[a.H + u]; bhn = a.bias1[2 * a.H + u]; }
-        const long long t = (long long)b * a.H + u;
-        const float r = sigmoidf_dev(sr + bxr + bhr);
-        const float z = sigmoidf_dev(sz + bxz + bhz);
-        const float nn = tanhf_dev(fmaf(r, nh + bhn, nx + bxn));
-        a.h_out[t] = fmaf(z, a.h_prev[t] - nn, nn);
+        const long long t = (long long)b * a.H + row[0];
+        const float r = sigmoidf_dev(sr + bs0[0] + bs1[0]);
+        const float z = sigmoidf_dev(sz + bs0[1] + bs1[1]);
+        const float nn = tanhf_dev(fmaf(r, nh + bs1[2], nx + bs0[2]));
+        a.h_out[t] = fmaf(z, prev[0] - nn, nn);
       }
     }
   }

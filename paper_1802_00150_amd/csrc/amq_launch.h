@@ -74,6 +74,7 @@ struct BmvArgs {
   const float* bias1;   // GRU: bias_h [3H] (nullable)
   int accumulate;       // store mode
   float* Y;             // store mode: [batch][m]
+  int32_t* D;           // store mode, matrix-core kernel only: [batch][m][k_w][k_a] integer dots (nullable)
   const float* c_prev;  // LSTM
   const float* h_prev;  // GRU
   float* h_out;
@@ -87,6 +88,13 @@ struct BmvArgs {
 // true if the register-resident kernel can take these vector lengths / batch
 bool bmv_supported(int n0, int n1, int k_a, long long batch);
 hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s);
+
+// ---- batched products on the matrix cores (int8 MFMA on expanded codes), same epilogues ------
+bool mfma_supported(long long batch);
+hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
+// fp4 matrix-core kernel for vectors of at most 1024 entries (the fast path)
+bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
+hipError_t launch_mfma4(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU

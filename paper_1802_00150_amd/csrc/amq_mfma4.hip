@@ -1,0 +1,384 @@
+// Batched binary matrix products on the fp4 matrix cores of gfx950 (Fig. 3 right: the
+// concatenated form), for vectors of at most 1024 entries per operand block.
+//
+// Why fp4: the contraction only ever multiplies codes, and with both operands written as
+// {0, 1} every product and every partial sum (< 2^24) is exact in the E2M1 x E2M1 -> fp32
+// MFMA.  v_mfma_scale_f32_16x16x128_f8f6f4 in fp4 mode takes 128 entries of K per instruction
+// from 16-byte operands and issues every ~19 cycles on this chip, against ~32 cycles for the
+// int8 instruction with 64 entries of K (both measured), i.e. 3.3x the rate per entry.  The
+// +-1 inner product is recovered from popcounts:
+//   sum_l (2a_l - 1)(2x_l - 1) = 4 * sum_l a_l x_l - 2 * popc(a) - 2 * popc(x) + n.
+//
+// Expansion: bit p of a packed word becomes nibble 0b0010 (= 1.0 in E2M1) or 0.  One word
+// yields the four operand dwords (w << 1, w, w >> 1, w >> 2) & 0x22222222: nibble q of dword s
+// is bit 4q + s -- a fixed permutation of K applied to both operands.
+//
+// Work split: a wave owns 16 tile rows x KW planes x 16 batch entries x KA planes (KW * KA
+// accumulators of 4 registers).  A workgroup expands the activation tile (16 batch entries, all
+// planes, both operand blocks) into LDS once and its waves walk over row blocks, loading each
+// row block's packed weight words straight into the operand layout (lane = row l % 16, words
+// 8 * (l / 16) .. + 7).  In the cell modes the 16 tile rows are 4 hidden units x 4 gates, so
+// that in the 16x16 C layout (lane: column l % 16, rows 4 * (l / 16) + 0..3) one lane holds all
+// gates of one unit for one batch entry and the LSTM / GRU cell is applied in registers.
+#include "amq_device.h"
+#include "amq_launch.h"
+
+namespace amq {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kTileB = 16;   // batch entries per tile
+constexpr int kSteps = 8;    // 1024 entries / 128 per MFMA
+constexpr unsigned kNib = 0x22222222u;
+constexpr int kScaleOne = 0x7f7f7f7f;  // E8M0 exponent 127 = 2^0 in every byte
+
+__device__ __forceinline__ uint4 expand4(uint32_t w) {
+  return make_uint4((w << 1) & kNib, w & kNib, (w >> 1) & kNib, (w >> 2) & kNib);
+}
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// fp4 operands occupy the first four of the eight operand registers; the rest is left undefined
+// so that no registers are spent on it.
+__device__ __forceinline__ v8i as_operand(uint4 e) {
+  const v4i lo = {(int)e.x, (int)e.y, (int)e.z, (int)e.w};
+  return __builtin_shufflevector(lo, lo, 0, 1, 2, 3, -1, -1, -1, -1);
+}
+
+__device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
+  const uint4 v = q[t >> 2];
+  return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
+}
+
+template <int KW, int KA, int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_wg, int rowblocks) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
+  constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
+  constexpr int kPlaneBytes = kSteps * kTileB * 64;   // 8 KiB: [step][batch entry][k-block][16 B]
+  constexpr int kTileBytes = KA * kPlaneBytes;
+  constexpr int kItems = KA * kTileB * 8;             // 16-byte groups of packed words per operand block
+  constexpr int kIter = (kItems + 64 * NWV - 1) / (64 * NWV);
+  unsigned char* btile = smem;
+  int* pops = reinterpret_cast<int*>(smem + NBLK * kTileBytes);  // [NBLK][KA][kTileB]
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int l16 = lane & 15, l4 = lane >> 4;
+  const int b0 = blockIdx.y * kTileB;
+  const int batch = a.batch;
+  const int m = (int)a.m, H = (int)a.H;
+  const uint4* Wp4[NBLK];
+  const float* alpha[NBLK];
+  int nlen[NBLK], wq[NBLK];
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) {
+    Wp4[k] = reinterpret_cast<const uint4*>(a.blk[k].Wp);
+    alpha[k] = a.blk[k].alpha;
+    nlen[k] = a.blk[k].n;
+    wq[k] = (nlen[k] + 127) >> 7;  // 16-byte groups per row
+  }
+
+  // ---- prologue: packed activation words of every operand block, 16 bytes per thread, coalesced
+  uint4 xw[NBLK][kIter];
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) {
+    const uint4* Xp4 = reinterpret_cast<const uint4*>(a.blk[k].Xp);
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+      const int e = tid + it * 64 * NWV;
+      const int q = e & 7, nn = (e >> 3) & (kTileB - 1), j = e >> 7;
+      const bool valid = e < kItems && b0 + nn < batch && q < wq[k];
+      const int bb = b0 + nn < batch ? b0 + nn : batch - 1;
+      const uint4 v = Xp4[((e < kItems ? j : 0) * batch + bb) * wq[k] + (q < wq[k] ? q : 0)];
+      xw[k][it] = valid ? v : make_uint4(0, 0, 0, 0);
+    }
+  }
+  if (tid < NBLK * KA * kTileB) pops[tid] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) {
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+      const int e = tid + it * 64 * NWV;
+      if (e < kItems) {
+        const int q = e & 7, nn = (e >> 3) & (kTileB - 1), j = e >> 7;
+        const uint4 w4 = xw[k][it];
+        const int pc = __popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w);
+        if (pc) atomicAdd(&pops[(k * KA + j) * kTileB + nn], pc);
+        // words 4q .. 4q+3 of the row: k-block q >> 1, steps 4 * (q & 1) + 0..3
+        uint4* dst = reinterpret_cast<uint4*>(btile + k * kTileBytes + j * kPlaneBytes +
+                                              ((4 * (q & 1)) * kTileB + nn) * 64 + (q >> 1) * 16);
+        dst[0 * kTileB * 4] = expand4(w4.x);
+        dst[1 * kTileB * 4] = expand4(w4.y);
+        dst[2 * kTileB * 4] = expand4(w4.z);
+        dst[3 * kTileB * 4] = expand4(w4.w);
+      }
+    }
+  }
+  __syncthreads();
+
+  const int b = b0 + l16;
+  const bool bok = b < batch;
+  const int bc = bok ? b : batch - 1;
+  float btv[NBLK][KA];
+  float cx[NBLK][KA];  // n - 2 * popc(activation plane): the column-only part of the dot product
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k)
+#pragma unroll
+    for (int j = 0; j < KA; ++j) {
+      btv[k][j] = a.blk[k].beta[bc * KA + j];
+      cx[k][j] = (float)(nlen[k] - 2 * pops[(k * KA + j) * kTileB + l16]);
+    }
+
+  int rb_end = (blockIdx.x + 1) * rb_per_wg;
+  if (rb_end > rowblocks) rb_end = rowblocks;
+  for (int rb = blockIdx.x * rb_per_wg + wv; rb < rb_end; rb += NWV) {
+    // A-operand view: lane = (tile row l16, k-block l4)
+    int wrow;
+    bool wok;
+    if constexpr (EPI == kEpiStore) {
+      wrow = rb * 16 + l16;
+      wok = wrow < m;
+    } else {
+      const int unit = rb * 4 + (l16 >> 2);
+      const int gate = l16 & 3;
+      wok = unit < H && gate < NG;
+      wrow = gate * H + unit;
+    }
+    if (!wok) wrow = 0;
+    uint4 araw[NBLK][KW][2];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+      const int base = wrow * wq[k];
+      const int plane = m * wq[k];
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+          const int g = 2 * l4 + v;
+          const uint4 t4 = Wp4[k][base + i * plane + (g < wq[k] ? g : 0)];
+          araw[k][i][v] = (wok && g < wq[k]) ? t4 : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // C view: rows 4 * l4 + r.  Everything the epilogue reads from memory is requested now.
+    int crow[4];
+    bool cok[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if constexpr (EPI == kEpiStore) {
+        crow[r] = rb * 16 + 4 * l4 + r;
+        cok[r] = crow[r] < m;
+      } else {
+        const int unit = rb * 4 + l4;
+        cok[r] = unit < H && r < NG;
+        crow[r] = r * H + unit;
+      }
+      if (!cok[r]) crow[r] = 0;
+    }
+    float alr[NBLK][4][KW];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < KW; ++i) alr[k][r][i] = alpha[k][crow[r] * KW + i];
+    float bias0[4], bias1[4], yold[4], prev = 0.0f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      bias0[r] = a.bias0 ? a.bias0[crow[r]] : 0.0f;
+      bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[crow[r]] : 0.0f;
+      yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
+    }
+    if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
+    if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
+
+    float ysum[NBLK][4];
+#pragma unroll
+    for (int k = 0; k < NBLK; ++k) {
+      // popcount of every weight row plane: this lane's 8 words, then the four k-blocks of the
+      // row (lanes 16 apart), then fetched for the rows of the C view
+      float pw2[KW][4];
+#pragma unroll
+      for (int i = 0; i < KW; ++i) {
+        int pc = 0;
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+          pc += __popc(araw[k][i][v].x) + __popc(araw[k][i][v].y) + __popc(araw[k][i][v].z) + __popc(araw[k][i][v].w);
+        pc += __shfl_xor(pc, 16, kWave);
+        pc += __shfl_xor(pc, 32, kWave);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pw2[i][r] = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
+      }
+
+      v4f acc[KW][KA];
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+      const unsigned char* tile = btile + k * kTileBytes + l16 * 64 + l4 * 16;
+      uint4 bop[KA], bnx[KA], aop[KW], anx[KW];
+#pragma unroll
+      for (int j = 0; j < KA; ++j) bop[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes);
+#pragma unroll
+      for (int i = 0; i < KW; ++i) aop[i] = expand4(word_of(araw[k][i], 0));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int t = 0; t < kSteps; ++t) {
+        if (t + 1 < kSteps) {
+#pragma unroll
+          for (int j = 0; j < KA; ++j)
+            bnx[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes + (t + 1) * kTileB * 64);
+#pragma unroll
+          for (int i = 0; i < KW; ++i) anx[i] = expand4(word_of(araw[k][i], t + 1));
+        }
+#pragma unroll
+        for (int i = 0; i < KW; ++i)
+#pragma unroll
+          for (int j = 0; j < KA; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(aop[i]), as_operand(bop[j]), acc[i][j],
+                                                                         4, 4, 0, kScaleOne, 0, kScaleOne);
+        // issue order inside a step: the LDS reads of the next step first, then every MFMA
+        // followed by up to three of the VALU instructions that expand the next step's weights
+        __builtin_amdgcn_sched_group_barrier(0x100, KA, 0);
+#pragma unroll
+        for (int g = 0; g < KW * KA; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < KA; ++j) bop[j] = bnx[j];
+#pragma unroll
+        for (int i = 0; i < KW; ++i) aop[i] = anx[i];
+      }
+      // block epilogue in the C view: lane = (batch column l16, row quad l4); all integers
+      // involved are below 2^24, so the float arithmetic here is exact up to the final fmas
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float y = 0.0f;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          float inner = 0.0f;
+#pragma unroll
+          for (int j = 0; j < KA; ++j) {
+            const float d = 4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j];
+            if constexpr (EPI == kEpiStore) {
+              if (a.D && bok && cok[r]) a.D[(((long long)b * m + crow[r]) * KW + i) * KA + j] = (int)d;
+            }
+            inner = fmaf(btv[k][j], d, inner);
+          }
+          y = fmaf(alr[k][r][i], inner, y);
+        }
+        ysum[k][r] = y;
+      }
+    }
+
+    if (!bok) continue;
+    if constexpr (EPI == kEpiStore) {
+      if (a.Y) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (cok[r]) a.Y[(long long)b * m + crow[r]] = ysum[0][r] + bias0[r] + yold[r];
+      }
+    } else if constexpr (EPI == kEpiLstm) {
+      if (cok[0]) {
+        const int t = b * H + crow[0];
+        const float gi = sigmoidf_dev(ysum[0][0] + ysum[1][0] + bias0[0]);
+        const float gf = sigmoidf_dev(ysum[0][1] + ysum[1][1] + bias0[1]);
+        const float go = sigmoidf_dev(ysum[0][2] + ysum[1][2] + bias0[2]);
+        const float gg = tanhf_dev(ysum[0][3] + ysum[1][3] + bias0[3]);
+        const float c = fmaf(gf, prev, gi * gg);
+        const float h = go * tanhf_dev(c);
+        a.c_out[t] = c;
+        a.h_out[t] = h;
+        if (a.hs_out) a.hs_out[t] = h;
+      }
+    } else {
+      if (cok[0]) {
+        const int t = b * H + crow[0];
+        const float rg = sigmoidf_dev(ysum[0][0] + ysum[1][0] + bias0[0] + bias1[0]);
+        const float z = sigmoidf_dev(ysum[0][1] + ysum[1][1] + bias0[1] + bias1[1]);
+        const float nn = tanhf_dev(fmaf(rg, ysum[1][2] + bias1[2], ysum[0][2] + bias0[2]));
+        a.h_out[t] = fmaf(z, prev - nn, nn);
+      }
+    }
+  }
+}
+
+template <int KW, int KA, int EPI, int NWV>
+hipError_t launch_one(const BmvArgs& a, int rowblocks, int rb_per_wg, hipStream_t s) {
+  constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
+  const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + sizeof(int) * NBLK * KA * kTileB;
+  static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  dim3 grid((unsigned)((rowblocks + rb_per_wg - 1) / rb_per_wg), (unsigned)((a.batch + kTileB - 1) / kTileB));
+  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
+  return hipGetLastError();
+}
+
+template <int KW, int KA, int EPI>
+hipError_t launch_mode(const BmvArgs& a, hipStream_t s) {
+  const int rowblocks = (int)((EPI == kEpiStore) ? (a.m + 15) / 16 : (a.H + 3) / 4);
+  const int btiles = (a.batch + kTileB - 1) / kTileB;
+  // about two workgroups per CU; each expands its activation tile once and then walks row blocks
+  int splits = (512 + btiles - 1) / btiles;
+  int per = (rowblocks + splits - 1) / splits;
+  if (per < 4) per = 4;
+  // 8 waves (two per SIMD) when there is work for them and 256 registers per wave suffice
+  if (per >= 16 && KW * KA <= (EPI == kEpiStore ? 9 : 4)) return launch_one<KW, KA, EPI, 8>(a, rowblocks, per, s);
+  return launch_one<KW, KA, EPI, 4>(a, rowblocks, per, s);
+}
+
+template <int KW, int KA>
+hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s) {
+  switch (epi) {
+    case kEpiStore: return launch_mode<KW, KA, kEpiStore>(a, s);
+    case kEpiLstm: return launch_mode<KW, KA, kEpiLstm>(a, s);
+    case kEpiGru: return launch_mode<KW, KA, kEpiGru>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int KW>
+hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s) {
+  switch (k_a) {
+    case 1: return launch_epi<KW, 1>(a, epi, s);
+    case 2: return launch_epi<KW, 2>(a, epi, s);
+    case 3: return launch_epi<KW, 3>(a, epi, s);
+    case 4: return launch_epi<KW, 4>(a, epi, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// Vectors of at most 1024 entries, and sizes whose element offsets fit 32 bits.
+bool mfma4_supported(const BmvArgs& a, int k_w, int epi) {
+  const int nblk = (epi == kEpiStore) ? 1 : 2;
+  for (int k = 0; k < nblk; ++k)
+    if (a.blk[k].n > 1024) return false;
+  if (a.batch > 65535 * kTileB) return false;
+  if (a.m * 8 * k_w >= (1LL << 31)) return false;       // weight offsets in 16-byte units
+  if ((long long)a.batch * (a.m > a.H ? a.m : a.H) >= (1LL << 31)) return false;
+  return true;
+}
+
+hipError_t launch_mfma4(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s) {
+  switch (k_w) {
+    case 1: return launch_ka<1>(a, k_a, epi, s);
+    case 2: return launch_ka<2>(a, k_a, epi, s);
+    case 3: return launch_ka<3>(a, k_a, epi, s);
+    case 4: return launch_ka<4>(a, k_a, epi, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace amq

@@ -1,6 +1,6 @@
-// Alternating multi-bit quantization (Alg. 2) on gfx950: one wavefront (or one workgroup of
-// NW wavefronts) per vector, the vector held in registers, every stage of the algorithm in
-// this one kernel.
+// Alternating multi-bit quantization (Alg. 2) on gfx950: one wavefront (throughput regime,
+// many vectors) or one workgroup of NW = 4 / 16 wavefronts (latency regime, few vectors) per
+// vector, the vector held in registers, every stage of the algorithm in this one kernel.
 //
 // Element layout in a wave: "slot" j of a lane holds entry (slot_base + j) * 64 + lane, so a
 // wave-wide comparison yields, through the 64-bit ballot, exactly two packed code words of
@@ -102,11 +102,68 @@ __device__ __forceinline__ float readlane_f(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_d(double v) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+
+// Totals of NV doubles over the 64 lanes through DPP (no LDS traffic); the results are
+// wave-uniform (read from lane 63).  The NV chains are independent and interleave.
+template <int NV>
+__device__ __forceinline__ void wave_totals(double (&v)[NV]) {
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0xB1, 0xf>(v[i]);   // quad_perm [1,0,3,2]
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0x4E, 0xf>(v[i]);   // quad_perm [2,3,0,1]
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0x141, 0xf>(v[i]);  // row_half_mirror
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0x140, 0xf>(v[i]);  // row_mirror: every lane holds its row's sum
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0x142, 0xa>(v[i]);  // row_bcast15 into rows 1 and 3
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] += dpp_d<0x143, 0xc>(v[i]);  // row_bcast31 into rows 2 and 3
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v[i]), 63);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v[i]), 63);
+    v[i] = __hiloint2double(hi, lo);
+  }
+}
+
+constexpr int kMaxRed = 10;  // K coefficients + K(K-1)/2 plane pairs at K = 4
+
+// Totals over the whole workgroup; one barrier per call, two LDS buffers used alternately.
+template <int NW, int NV>
+__device__ __forceinline__ void block_totals(double (&v)[NV], double (*sh)[16 * kMaxRed], int& phase) {
+  wave_totals<NV>(v);
+  if constexpr (NW > 1) {
+    const int wv = wave_id();
+    if (lane_id() == 0) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) sh[phase][wv * NV + i] = v[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      double t = sh[phase][i];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += sh[phase][w * NV + i];
+      v[i] = t;
+    }
+    phase ^= 1;
+  }
+}
+
 template <int K, int NJ, int NW>
 __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
-  __shared__ double sh_d[NW];
-  __shared__ int sh_i[NW];
+  __shared__ double sh[2][16 * kMaxRed];
+  int phase = 0;
   constexpr int M = 1 << K;
+  constexpr int NP = K * (K - 1) / 2;
   const int lane = lane_id(), wv = wave_id();
   int vec = blockIdx.x;
   const int which = (vec >= a.seg[0].count) ? 1 : 0;
@@ -139,20 +196,26 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
   for (int i = 0; i < K; ++i) { alpha[i] = 0.0f; mym[i] = 0ull; q[i] = 0.0; }
 
   if (a.mode == kQuantFull) {
-    // ---- greedy initialisation, Eq. 4
+    // ---- greedy initialisation, Eq. 4.  One pass per stage: it assigns the signs, updates the
+    // residual and accumulates the l1 norm of the new residual for the next stage.
     float r[NJ];
+    double s[1];
+    {
+      double s0 = 0.0, s1 = 0.0;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) r[j] = w[j];
+      for (int j = 0; j < NJ; ++j) {
+        r[j] = w[j];
+        if (j & 1) s1 += (double)fabsf(w[j]); else s0 += (double)fabsf(w[j]);
+      }
+      s[0] = s0 + s1;
+    }
+    block_totals<NW, 1>(s, sh, phase);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      double s = 0.0;
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) s += (double)fabsf(r[j]);
-      s = block_sum<NW>(s, sh_d);
-      const float al = (float)(s / dn);
+      const float al = (float)(s[0] / dn);
       alpha[i] = al;
       unsigned long long mine = 0ull;
-      double qi = 0.0;
+      double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         if (j < nj) {
@@ -160,12 +223,18 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
           const bool bit = valid && (r[j] >= 0.0f);
           const unsigned long long mk = __ballot(bit);
           if (lane == j) mine = mk;
-          qi += bit ? (double)w[j] : -(double)w[j];
-          r[j] = valid ? r[j] - (bit ? al : -al) : 0.0f;
+          const double sw = bit ? (double)w[j] : -(double)w[j];
+          const float rn = valid ? r[j] - (bit ? al : -al) : 0.0f;
+          r[j] = rn;
+          if (j & 1) { q1 += sw; s1 += (double)fabsf(rn); } else { q0 += sw; s0 += (double)fabsf(rn); }
         }
       }
       mym[i] = mine;
-      q[i] = qi;
+      q[i] = q0 + q1;
+      if (i + 1 < K) {
+        s[0] = s0 + s1;
+        block_totals<NW, 1>(s, sh, phase);
+      }
     }
   } else if (a.mode == kQuantLsOnly) {
     // codes given: read the masks, rebuild B^T w from them
@@ -198,22 +267,35 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
   const int iters = (a.mode == kQuantFull) ? a.T : 1;
   for (int it = 0; it < iters; ++it) {
     if (a.mode != kQuantBstOnly) {
-      // ---- coefficients with the codes fixed, Eq. 5
+      // ---- coefficients with the codes fixed, Eq. 5: B^T w and the disagreement counts of
+      // every plane pair go through one workgroup reduction (counts are exact in binary64)
+      double red[K + NP];
+#pragma unroll
+      for (int i = 0; i < K; ++i) red[i] = q[i];
+      {
+        int t = K;
+#pragma unroll
+        for (int i = 0; i < K; ++i)
+#pragma unroll
+          for (int j = i + 1; j < K; ++j) red[t++] = (double)__popcll(mym[i] ^ mym[j]);
+      }
+      block_totals<NW, K + NP>(red, sh, phase);
       int G[K][K];
+      double qq[K];
+      {
+        int t = K;
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        G[i][i] = n;
+        for (int i = 0; i < K; ++i) {
+          qq[i] = red[i];
+          G[i][i] = n;
 #pragma unroll
-        for (int j = i + 1; j < K; ++j) {
-          int d = __popcll(mym[i] ^ mym[j]);
-          d = block_sum<NW>(d, sh_i);
-          G[i][j] = n - 2 * d;
-          G[j][i] = G[i][j];
+          for (int j = i + 1; j < K; ++j) {
+            const int d = __builtin_amdgcn_readfirstlane((int)red[t++]);  // wave-uniform: integer math on the scalar unit
+            G[i][j] = n - 2 * d;
+            G[j][i] = G[i][j];
+          }
         }
       }
-      double qq[K];
-#pragma unroll
-      for (int i = 0; i < K; ++i) qq[i] = block_sum<NW>(q[i], sh_d);
       ls_solve<K>(G, qq, alpha);
       if (a.mode == kQuantLsOnly) break;
     }
@@ -237,21 +319,20 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
     if (lane >= M) rank = lane;
     const float sv = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(v)));
     const int sp = __builtin_amdgcn_ds_permute(rank << 2, p);
-    const float nxt = __shfl_down(sv, 1, kWave);
-    const float tmid = 0.5f * (sv + nxt);  // midpoint of adjacent codes (lanes < M-1)
-    float thr[M - 1];
+    float thr[M - 1];  // midpoints of adjacent codes, wave-uniform
 #pragma unroll
-    for (int j = 0; j < M - 1; ++j) thr[j] = readlane_f(tmid, j);
+    for (int j = 0; j < M - 1; ++j) thr[j] = 0.5f * (readlane_f(sv, j) + readlane_f(sv, j + 1));
     unsigned bm[K];  // bit `pos` of bm[i]: plane i is +1 for the code at sorted position pos
 #pragma unroll
     for (int i = 0; i < K; ++i) bm[i] = (unsigned)__ballot(lane < M && ((sp >> (K - 1 - i)) & 1));
 
     // ---- codes with the coefficients fixed (Alg. 1); the position in the sorted table is the
     // number of midpoints <= w, which is where the k-comparison tree walk ends.
+    const bool more = (a.mode == kQuantFull) && (it + 1 < iters);  // B^T w is needed by another cycle
     unsigned long long mine[K];
-    double qi[K];
+    double qa[K], qb[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) { mine[i] = 0ull; qi[i] = 0.0; }
+    for (int i = 0; i < K; ++i) { mine[i] = 0ull; qa[i] = 0.0; qb[i] = 0.0; }
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       if (j < nj) {
@@ -259,17 +340,20 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
         int pos = 0;
 #pragma unroll
         for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
+        const double wd = (double)w[j];
 #pragma unroll
         for (int i = 0; i < K; ++i) {
           const bool bit = valid && ((bm[i] >> pos) & 1u);
           const unsigned long long mk = __ballot(bit);
           if (lane == j) mine[i] = mk;
-          qi[i] += bit ? (double)w[j] : -(double)w[j];
+          if (more) {
+            if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
+          }
         }
       }
     }
 #pragma unroll
-    for (int i = 0; i < K; ++i) { mym[i] = mine[i]; q[i] = qi[i]; }
+    for (int i = 0; i < K; ++i) { mym[i] = mine[i]; q[i] = qa[i] + qb[i]; }
   }
 
   if (a.mode != kQuantLsOnly) {
@@ -284,17 +368,38 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
   }
 }
 
+template <int K, int NJ, int NW>
+void launch_one(const QuantArgs& a, int total, hipStream_t s) {
+  hipLaunchKernelGGL((quantize_kernel<K, NJ, NW>), dim3(total), dim3(64 * NW), 0, s, a);
+}
+
+// Waves per vector: one when there are enough vectors to fill the chip (throughput regime),
+// 4 or 16 when there are few (latency regime); then the smallest register bucket that holds
+// the vector's share.
 template <int K>
 hipError_t launch_k(const QuantArgs& a, int max_n, hipStream_t s) {
   const int total = a.seg[0].count + a.seg[1].count;
   if (total == 0) return hipSuccess;
   const int nslots = 2 * ((max_n + 127) / 128);
-  if (nslots <= 16)
-    hipLaunchKernelGGL((quantize_kernel<K, 16, 1>), dim3(total), dim3(64), 0, s, a);
-  else if (nslots <= 64)
-    hipLaunchKernelGGL((quantize_kernel<K, 64, 1>), dim3(total), dim3(64), 0, s, a);
-  else
-    hipLaunchKernelGGL((quantize_kernel<K, 64, 4>), dim3(total), dim3(256), 0, s, a);
+  int nw = total >= 1024 ? 1 : (total >= 96 ? 4 : 16);
+  while (nw > 1 && nw > nslots) nw /= 4;
+  if (nw == 1 && nslots > 64) nw = 4;
+  if (nw == 4 && nslots > 256) return hipErrorInvalidValue;
+  const int nj = (nslots + nw - 1) / nw;
+  if (nw == 1) {
+    if (nj <= 4) launch_one<K, 4, 1>(a, total, s);
+    else if (nj <= 16) launch_one<K, 16, 1>(a, total, s);
+    else launch_one<K, 64, 1>(a, total, s);
+  } else if (nw == 4) {
+    if (nj <= 1) launch_one<K, 1, 4>(a, total, s);
+    else if (nj <= 4) launch_one<K, 4, 4>(a, total, s);
+    else if (nj <= 16) launch_one<K, 16, 4>(a, total, s);
+    else launch_one<K, 64, 4>(a, total, s);
+  } else {
+    if (nj <= 1) launch_one<K, 1, 16>(a, total, s);
+    else if (nj <= 4) launch_one<K, 4, 16>(a, total, s);
+    else launch_one<K, 16, 16>(a, total, s);
+  }
   return hipGetLastError();
 }
 
