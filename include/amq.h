@@ -7,7 +7,7 @@
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
  *   - The caller owns every buffer, including workspaces.  The library
  *     allocates nothing and keeps no state between calls (except the entry
- *     point marked "static scratch").  Inputs are never modified.  Outputs must
+ *     point whose comment says it keeps static scratch).  Inputs are never modified.  Outputs must
  *     not alias inputs unless stated.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise the host.
@@ -50,8 +50,8 @@ const char* amq_status_string(int status);
 int amq_last_hip_error(void);             /* hipError_t of the last AMQ_ERR_HIP on this thread */
 
 /*
- * Row-wise alternating multi-bit quantization of a weight matrix (Sec. 4,
- * "row by row"; Alg. 2 on every row): greedy initialisation (Eq. 4), then T
+ * Row-wise alternating multi-bit quantization of a weight matrix (Sec. 4: every
+ * row gets its own coefficients; Alg. 2 on every row): greedy initialisation (Eq. 4), then T
  * times { least-squares coefficients (Eq. 5); sorted code table; binary-search
  * code assignment (Alg. 1) }.  No trailing least-squares step.  T = 0 returns
  * the greedy result.  If the k x k Gram matrix of the codes is singular the
@@ -65,8 +65,8 @@ int amq_quantize_weights(const float* W, int64_t rows, int64_t cols, int64_t ld,
                          uint32_t* planes, float* alpha, void* stream);
 
 /*
- * On-line quantization of a batch of activation vectors (Sec. 4: h_t "needs to
- * be quantized on-line"); the same mathematics as amq_quantize_weights on the
+ * On-line quantization of a batch of activation vectors (Sec. 4: h_t depends on
+ * the input and has to be quantized at inference time); the same mathematics as amq_quantize_weights on the
  * rows of X, X dense [batch][n].
  *   planes [k][batch][wpr(n)] uint32 out,  beta [batch][k] float out
  */
@@ -136,6 +136,19 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
                   const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
                   int T, float* h_out, float* c_out, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/*
+ * The same LSTM step on operands that are already quantized: x_t as packed planes Xp
+ * [k_a][B][wpr(I)] with beta_x [B][k_a] (Sec. 4: with one-hot inputs x_t is a row of the
+ * quantized embedding matrix, so it arrives already quantized), h_{t-1} as Hp / beta_h.
+ * Products, coefficient epilogue and cell only; no workspace.  Returns AMQ_ERR_UNSUPPORTED for
+ * B <= 16 with I or H above 8192 (that shape needs the workspace path of amq_lstm_step).
+ */
+int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                         const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                         const uint32_t* Xp, const float* beta_x, const uint32_t* Hp,
+                         const float* beta_h, const float* c_prev, int64_t B, int k_a, float* h_out,
+                         float* c_out, void* stream);
 
 /*
  * `steps` consecutive LSTM steps in one call (the recurrence of Eq. 6 over a

@@ -260,7 +260,7 @@ void amq_oracle_pack(const uint8_t* code, int64_t n, uint32_t* words) {
 static int unpack_bit(const uint32_t* words, int64_t l) { return (int)((words[l / 32] >> (l % 32)) & 1u); }
 
 /* ------------------------------------------------------------------ *
- * Row-wise quantization of a matrix (Sec. 4: "row by row"), also used for a
+ * Row-wise quantization of a matrix (Sec. 4: one coefficient set per row), also used for a
  * batch of activation vectors.  W is rows x cols with leading dimension ld.
  * planes: [k][rows][wpr] words, alpha: [rows][k].
  * ------------------------------------------------------------------ */

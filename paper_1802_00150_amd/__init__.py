@@ -7,5 +7,5 @@ shared library is loaded at the first call and a missing library is an error, ne
 """
 from . import binding  # noqa: F401
 from .binding import (AmqError, binary_dots, binary_gemm, binary_gemv, binary_gemv_grouped, bst_assign,  # noqa: F401
-                      gru_step, gru_workspace, ls_update, lstm_sequence, lstm_step, lstm_workspace,
+                      gru_step, gru_workspace, ls_update, lstm_sequence, lstm_step, lstm_step_packed, lstm_workspace,
                       quantize_activations, quantize_weights, version, wpr)

@@ -17,7 +17,7 @@ EXPORTS = [
     "amq_wpr", "amq_version", "amq_status_string", "amq_last_hip_error",
     "amq_quantize_weights", "amq_quantize_activations", "amq_ls_update", "amq_bst_assign",
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
-    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_sequence",
+    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_packed", "amq_lstm_sequence",
     "amq_gru_workspace_bytes", "amq_gru_step",
 ]
 
@@ -53,6 +53,8 @@ def lib():
         L.amq_gru_workspace_bytes.argtypes, L.amq_gru_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
                                     _p, _sz, _p]
+        L.amq_lstm_step_packed.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _i64, _int,
+                                           _p, _p, _p]
         L.amq_lstm_sequence.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _i64, _p, _p, _i64, _int,
                                         _int, _p, _p, _sz, _p]
         L.amq_gru_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
@@ -211,6 +213,24 @@ def lstm_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias, x, h_prev, c_prev, k_a, T,
                                _dev(h_prev, torch.float32), _dev(c_prev, torch.float32), B, k_a, T,
                                _dev(h_out, torch.float32), _dev(c_out, torch.float32), ws.data_ptr(),
                                ws.numel(), _stream()))
+    return h_out, c_out
+
+
+def lstm_step_packed(Wxp, alpha_x, Whp, alpha_h, I, H, bias, Xp, beta_x, Hp, beta_h, c_prev, h_out=None,
+                     c_out=None):
+    """LSTM step on operands that are already quantized (Xp [k_a, B, wpr(I)], Hp [k_a, B, wpr(H)])."""
+    k_w = Wxp.shape[0]
+    k_a, B, _ = Xp.shape
+    if h_out is None:
+        h_out = torch.empty_like(c_prev)
+    if c_out is None:
+        c_out = torch.empty_like(c_prev)
+    _check(lib().amq_lstm_step_packed(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
+                                      _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, k_w,
+                                      _opt(bias), _dev(Xp, torch.int32), _dev(beta_x, torch.float32),
+                                      _dev(Hp, torch.int32), _dev(beta_h, torch.float32),
+                                      _dev(c_prev, torch.float32), B, k_a, _dev(h_out, torch.float32),
+                                      _dev(c_out, torch.float32), _stream()))
     return h_out, c_out
 
 

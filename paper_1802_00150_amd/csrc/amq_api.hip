@@ -230,6 +230,32 @@ size_t amq_gru_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
   return carve(nullptr, I, H, B, k_a, 3, 2).total;
 }
 
+// Products + epilogue + cell in one launch, given quantized operands.  Returns -1 if no fused
+// kernel takes this shape (the caller then uses the unfused path, which needs a workspace).
+static int lstm_fused_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                             const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                             const uint32_t* Xp, const float* beta_x, const uint32_t* Hp, const float* beta_h,
+                             const float* c_prev, int64_t B, int k_a, float* h_out, float* c_out,
+                             float* hs_out, hipStream_t s) {
+  amq::BmvArgs b{};
+  b.blk[0] = amq::BmvBlock{Wxp, alpha_x, Xp, beta_x, (int)I};
+  b.blk[1] = amq::BmvBlock{Whp, alpha_h, Hp, beta_h, (int)H};
+  b.m = 4 * H;
+  b.H = H;
+  b.batch = (int)B;
+  b.bias0 = bias;
+  b.c_prev = c_prev;
+  b.h_out = h_out;
+  b.c_out = c_out;
+  b.hs_out = hs_out;
+  b.groups = 1;
+  if (amq::bmv_supported((int)I, (int)H, k_a, B))
+    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
+  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B))
+    return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiLstm, s));
+  return -1;
+}
+
 static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                             const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
                             const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
@@ -242,36 +268,9 @@ static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uin
   q.mode = amq::kQuantFull;
   int st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
-  if (amq::bmv_supported((int)I, (int)H, k_a, B)) {
-    amq::BmvArgs b{};
-    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
-    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
-    b.m = 4 * H;
-    b.H = H;
-    b.batch = (int)B;
-    b.bias0 = bias;
-    b.c_prev = c_prev;
-    b.h_out = h_out;
-    b.c_out = c_out;
-    b.hs_out = hs_out;
-    b.groups = 1;
-    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
-  }
-  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B)) {
-    amq::BmvArgs b{};
-    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
-    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
-    b.m = 4 * H;
-    b.H = H;
-    b.batch = (int)B;
-    b.bias0 = bias;
-    b.c_prev = c_prev;
-    b.h_out = h_out;
-    b.c_out = c_out;
-    b.hs_out = hs_out;
-    b.groups = 1;
-    return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiLstm, s));
-  }
+  st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, w.xp, w.beta_x, w.hp, w.beta_h, c_prev,
+                         B, k_a, h_out, c_out, hs_out, s);
+  if (st >= 0) return st;
   amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
   st = run_product(gx, s);
   if (st != AMQ_OK) return st;
@@ -279,6 +278,20 @@ static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uin
   st = run_product(gh, s);
   if (st != AMQ_OK) return st;
   return hip_status(amq::launch_lstm_pointwise(w.pre0, c_prev, h_out, c_out, hs_out, B, H, s));
+}
+
+int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                         int64_t I, int64_t H, int k_w, const float* bias, const uint32_t* Xp,
+                         const float* beta_x, const uint32_t* Hp, const float* beta_h, const float* c_prev,
+                         int64_t B, int k_a, float* h_out, float* c_out, void* stream) {
+  if (!Wxp || !alpha_x || !Whp || !alpha_h || !Xp || !beta_x || !Hp || !beta_h || !c_prev || !h_out || !c_out)
+    return AMQ_ERR_INVALID;
+  if (!bits_ok(k_w) || !bits_ok(k_a) || I <= 0 || H <= 0 || B <= 0) return AMQ_ERR_INVALID;
+  if (!aligned(Wxp, 16) || !aligned(Whp, 16) || !aligned(Xp, 16) || !aligned(Hp, 16)) return AMQ_ERR_INVALID;
+  if (I > AMQ_MAX_QUANT_N || H > AMQ_MAX_QUANT_N || B > (1 << 24)) return AMQ_ERR_UNSUPPORTED;
+  int st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, Xp, beta_x, Hp, beta_h, c_prev, B, k_a,
+                             h_out, c_out, nullptr, static_cast<hipStream_t>(stream));
+  return st >= 0 ? st : AMQ_ERR_UNSUPPORTED;
 }
 
 int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
