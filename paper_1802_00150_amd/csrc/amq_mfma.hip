@@ -221,6 +221,12 @@ __global__ __launch_bounds__(256) void mfma_kernel(BmvArgs a) {
       }
     }
 
+    // MFMAs read all 64 lanes; keep them (and the code feeding them) out of the divergent
+    // branches of the epilogue by pinning the accumulators in uniform control flow.
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
     // block epilogue in the C view: lane = (batch column l16, row quad l4)
     const int b = b0 + l16;
     const bool bok = b < batch;

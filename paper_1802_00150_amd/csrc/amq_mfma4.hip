@@ -254,6 +254,14 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
 #pragma unroll
         for (int i = 0; i < KW; ++i) aop[i] = anx[i];
       }
+      // An MFMA reads its operands from all 64 lanes, but the compiler treats it as lane-local
+      // and would sink it (and the VALU code producing its operands) into the divergent branch
+      // that guards the final stores, where lanes of padded batch columns -- which still supply
+      // weight rows -- are masked off.  Pin the accumulators here, in uniform control flow.
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
       // block epilogue in the C view: lane = (batch column l16, row quad l4); all integers
       // involved are below 2^24, so the float arithmetic here is exact up to the final fmas
 #pragma unroll
@@ -276,15 +284,16 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       }
     }
 
-    if (!bok) continue;
+    // (no early exit for padded batch columns: every lane stays active through the loop, the
+    // stores below are predicated instead)
     if constexpr (EPI == kEpiStore) {
-      if (a.Y) {
+      if (a.Y && bok) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           if (cok[r]) a.Y[(long long)b * m + crow[r]] = ysum[0][r] + bias0[r] + yold[r];
       }
     } else if constexpr (EPI == kEpiLstm) {
-      if (cok[0]) {
+      if (bok && cok[0]) {
         const int t = b * H + crow[0];
         const float gi = sigmoidf_dev(ysum[0][0] + ysum[1][0] + bias0[0]);
         const float gf = sigmoidf_dev(ysum[0][1] + ysum[1][1] + bias0[1]);
@@ -297,7 +306,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
         if (a.hs_out) a.hs_out[t] = h;
       }
     } else {
-      if (cok[0]) {
+      if (bok && cok[0]) {
         const int t = b * H + crow[0];
         const float rg = sigmoidf_dev(ysum[0][0] + ysum[1][0] + bias0[0] + bias1[0]);
         const float z = sigmoidf_dev(ysum[0][1] + ysum[1][1] + bias0[1] + bias1[1]);

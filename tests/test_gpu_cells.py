@@ -30,9 +30,12 @@ def quantized(W, k):
     return oracle.quantize_rows(W, k, 2)
 
 
+# batches above 16 take the matrix-core kernels (fp4 up to 1024 entries, int8 beyond); sizes are
+# chosen so that batch tiles, row blocks and K chunks are all ragged
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (300, 300, 1, 2, 2),
                                            (64, 200, 5, 2, 3), (1024, 512, 9, 3, 3), (17, 129, 4, 4, 4),
-                                           (256, 256, 6, 1, 1)])
+                                           (256, 256, 6, 1, 1), (200, 136, 21, 2, 3), (1024, 130, 37, 3, 3),
+                                           (300, 301, 17, 4, 4), (1500, 1100, 19, 2, 2), (2100, 70, 33, 3, 2)])
 def test_lstm_step_random(amq, I, H, B, k_w, k_a):
     g = np.random.default_rng(I + H + B)
     Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
@@ -59,7 +62,8 @@ def test_lstm_step_random(amq, I, H, B, k_w, k_a):
 
 
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (1024, 512, 9, 2, 2),
-                                           (300, 257, 4, 4, 3)])
+                                           (300, 257, 4, 4, 3), (200, 136, 21, 2, 3), (1024, 130, 37, 3, 3),
+                                           (1500, 1100, 19, 2, 2)])
 def test_gru_step_random(amq, I, H, B, k_w, k_a):
     g = np.random.default_rng(I + H + B + 1)
     Wx = (g.standard_normal((3 * H, I)) * 0.08).astype(np.float32)
@@ -80,6 +84,29 @@ def test_gru_step_random(amq, I, H, B, k_w, k_a):
     dh = to_dev(h)
     amq.gru_step(*d, I, H, to_dev(bx), to_dev(bh), to_dev(x), dh, k_a, 2, h_out=dh)
     assert_vec_close(host(dh), h_ref, "h in place")
+
+
+@pytest.mark.parametrize("I,H,B,k_w,k_a", [(300, 300, 1, 2, 2), (1024, 512, 9, 3, 3), (1024, 1024, 64, 3, 3),
+                                           (200, 136, 21, 2, 3)])
+def test_lstm_step_packed(amq, I, H, B, k_w, k_a):
+    # operands quantized by the oracle (x_t as a row of a quantized table needs no on-line quantization)
+    g = np.random.default_rng(I + 3 * H + B)
+    Wx = (g.standard_normal((4 * H, I)) * 0.05).astype(np.float32)
+    Wh = (g.standard_normal((4 * H, H)) * 0.05).astype(np.float32)
+    bias = (g.standard_normal(4 * H) * 0.1).astype(np.float32)
+    x = g.standard_normal((B, I)).astype(np.float32)
+    h = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    c = g.standard_normal((B, H)).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    Xp, bx = oracle.quantize_rows(x, k_a, 2)
+    Hp, bh = oracle.quantize_rows(h, k_a, 2)
+    say("lstm packed I=%d H=%d B=%d" % (I, H, B))
+    h_ref, c_ref = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, x, h, c, k_a, 2)
+    h_g, c_g = amq.lstm_step_packed(to_dev(Wxp), to_dev(ax), to_dev(Whp), to_dev(ah), I, H, to_dev(bias),
+                                    to_dev(Xp), to_dev(bx), to_dev(Hp), to_dev(bh), to_dev(c))
+    assert_vec_close(host(c_g), c_ref, "c")
+    assert_vec_close(host(h_g), h_ref, "h")
 
 
 def run_lstm_config(amq, c, steps, teacher_forced_steps):
