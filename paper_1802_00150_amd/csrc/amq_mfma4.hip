@@ -262,25 +262,64 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       for (int i = 0; i < KW; ++i)
 #pragma unroll
         for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
-      // block epilogue in the C view: lane = (batch column l16, row quad l4); all integers
-      // involved are below 2^24, so the float arithmetic here is exact up to the final fmas
+      // block epilogue in the C view: lane = (batch column l16, row quad l4), with
+      //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j))   (integers below 2^24: exact in binary32)
+      //   y = sum_i alpha_i sum_j beta_j d_ij.
+      if constexpr (EPI == kEpiStore) {
+        // plain products (logits): the factored form
+        //   4 sum_i alpha_i (sum_j beta_j acc_ij) - (sum_i alpha_i 2 popc(w_i)) (sum_j beta_j)
+        //     + (sum_i alpha_i) (sum_j beta_j (n - 2 popc(x_j)))
+        // halves the arithmetic; its cancellation costs about one decimal digit (error ~1e-6
+        // relative), irrelevant for an output that nothing feeds back into the quantizer
+        float sb = 0.0f, sbcx = 0.0f;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float y = 0.0f;
-#pragma unroll
-        for (int i = 0; i < KW; ++i) {
-          float inner = 0.0f;
-#pragma unroll
-          for (int j = 0; j < KA; ++j) {
-            const float d = 4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j];
-            if constexpr (EPI == kEpiStore) {
-              if (a.D && bok && cok[r]) a.D[(((long long)b * m + crow[r]) * KW + i) * KA + j] = (int)d;
-            }
-            inner = fmaf(btv[k][j], d, inner);
-          }
-          y = fmaf(alr[k][r][i], inner, y);
+        for (int j = 0; j < KA; ++j) {
+          sb += btv[k][j];
+          sbcx = fmaf(btv[k][j], cx[k][j], sbcx);
         }
-        ysum[k][r] = y;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float y = 0.0f, pa = 0.0f, sa = 0.0f;
+#pragma unroll
+          for (int i = 0; i < KW; ++i) {
+            float inner = 0.0f;
+#pragma unroll
+            for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], acc[i][j][r], inner);
+            y = fmaf(alr[k][r][i], inner, y);
+            pa = fmaf(alr[k][r][i], pw2[i][r], pa);
+            sa += alr[k][r][i];
+          }
+          ysum[k][r] = fmaf(4.0f, y, fmaf(sa, sbcx, -pa * sb));
+        }
+      } else {
+        // recurrent cells: h_t goes back into the on-line quantizer, where a difference in the
+        // last digits can move an entry across an interval boundary; form the exact integer
+        // dot products first, as the reference arithmetic does
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float y = 0.0f;
+#pragma unroll
+          for (int i = 0; i < KW; ++i) {
+            float inner = 0.0f;
+#pragma unroll
+            for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], 4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j], inner);
+            y = fmaf(alr[k][r][i], inner, y);
+          }
+          ysum[k][r] = y;
+        }
+      }
+      if constexpr (EPI == kEpiStore) {
+        if (a.D && bok) {  // integer test hook: the dot products themselves
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (cok[r]) {
+#pragma unroll
+              for (int i = 0; i < KW; ++i)
+#pragma unroll
+                for (int j = 0; j < KA; ++j)
+                  a.D[(((long long)b * m + crow[r]) * KW + i) * KA + j] = (int)(4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j]);
+            }
+        }
       }
     }
 
@@ -288,9 +327,16 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     // stores below are predicated instead)
     if constexpr (EPI == kEpiStore) {
       if (a.Y && bok) {
+        float* yp = a.Y + (long long)b * m + crow[0];
+        if ((m & 3) == 0 && cok[3]) {
+          // the four rows of this lane are consecutive in Y[b][.]: one aligned 16-byte store
+          *reinterpret_cast<float4*>(yp) = make_float4(ysum[0][0] + bias0[0] + yold[0], ysum[0][1] + bias0[1] + yold[1],
+                                                       ysum[0][2] + bias0[2] + yold[2], ysum[0][3] + bias0[3] + yold[3]);
+        } else {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (cok[r]) a.Y[(long long)b * m + crow[r]] = ysum[0][r] + bias0[r] + yold[r];
+          for (int r = 0; r < 4; ++r)
+            if (cok[r]) yp[r] = ysum[0][r] + bias0[r] + yold[r];
+        }
       }
     } else if constexpr (EPI == kEpiLstm) {
       if (bok && cok[0]) {

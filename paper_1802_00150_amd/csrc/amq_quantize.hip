@@ -1,5 +1,5 @@
 // Alternating multi-bit quantization (Alg. 2) on gfx950: one wavefront (throughput regime,
-// many vectors) or one workgroup of NW = 4 / 16 wavefronts (latency regime, few vectors) per
+// many vectors) or one workgroup of NW = 4 wavefronts (latency regime, few vectors) per
 // vector, the vector held in registers, every stage of the algorithm in this one kernel.
 //
 // Element layout in a wave: "slot" j of a lane holds entry (slot_base + j) * 64 + lane, so a
@@ -101,31 +101,29 @@ void launch_one(const QuantArgs& a, int total, hipStream_t s) {
 }
 
 // Waves per vector: one when there are enough vectors to fill the chip (throughput regime),
-// 4 or 16 when there are few (latency regime); then the smallest register bucket that holds
-// the vector's share.
+// four when there are few (latency regime: a quarter of the per-entry work per wave, one wave
+// per SIMD so that the wave-uniform parts of the algorithm are not replicated on a SIMD); then
+// the smallest register bucket that holds the vector's share.  Vectors above 4096 entries
+// always take four waves.
 template <int K>
 hipError_t launch_k(const QuantArgs& a, int max_n, hipStream_t s) {
   const int total = a.seg[0].count + a.seg[1].count;
   if (total == 0) return hipSuccess;
   const int nslots = 2 * ((max_n + 127) / 128);
-  int nw = total >= 1024 ? 1 : (total >= 96 ? 4 : 16);
-  while (nw > 1 && nw > nslots) nw /= 4;
+  int nw = total >= 1024 ? 1 : 4;
+  if (nw > nslots) nw = 1;
   if (nw == 1 && nslots > 64) nw = 4;
-  if (nw == 4 && nslots > 256) return hipErrorInvalidValue;
+  if (nslots > 256) return hipErrorInvalidValue;
   const int nj = (nslots + nw - 1) / nw;
   if (nw == 1) {
     if (nj <= 4) launch_one<K, 4, 1>(a, total, s);
     else if (nj <= 16) launch_one<K, 16, 1>(a, total, s);
     else launch_one<K, 64, 1>(a, total, s);
-  } else if (nw == 4) {
+  } else {
     if (nj <= 1) launch_one<K, 1, 4>(a, total, s);
     else if (nj <= 4) launch_one<K, 4, 4>(a, total, s);
     else if (nj <= 16) launch_one<K, 16, 4>(a, total, s);
     else launch_one<K, 64, 4>(a, total, s);
-  } else {
-    if (nj <= 1) launch_one<K, 1, 16>(a, total, s);
-    else if (nj <= 4) launch_one<K, 4, 16>(a, total, s);
-    else launch_one<K, 16, 16>(a, total, s);
   }
   return hipGetLastError();
 }

@@ -159,6 +159,38 @@ def test_config1_lstm_300_sequence(amq):
     assert_vec_close(host(cc), c_ref, "sequence c")
 
 
+@pytest.mark.parametrize("I,H,k_w,k_a,steps", [(300, 300, 2, 2, 7), (100, 64, 3, 3, 5), (512, 200, 2, 3, 4),
+                                               (130, 256, 3, 2, 3), (64, 1, 2, 2, 3)])
+def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
+    # small models at batch 1 run the whole sequence in one persistent launch; every h_t of the
+    # series is compared with the oracle's step-by-step recurrence (with bias, non-zero start)
+    import torch
+    g = np.random.default_rng(I * 7 + H)
+    Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((4 * H, H)) * 0.08).astype(np.float32)
+    bias = (g.standard_normal(4 * H) * 0.1).astype(np.float32)
+    xs = g.standard_normal((steps, 1, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((1, H))).astype(np.float32)
+    c0 = g.standard_normal((1, H)).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    say("sequence I=%d H=%d kw=%d ka=%d" % (I, H, k_w, k_a))
+    h, c = h0.copy(), c0.copy()
+    hs_ref = []
+    for t in range(steps):
+        h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, xs[t], h, c, k_a, 2)
+        hs_ref.append(h.copy())
+    dh, dc = to_dev(h0), to_dev(c0)
+    hs = torch.empty((steps, 1, H), dtype=torch.float32, device=dh.device)
+    amq.lstm_sequence(to_dev(Wxp), to_dev(ax), to_dev(Whp), to_dev(ah), I, H, to_dev(bias), to_dev(xs), dh, dc,
+                      k_a, 2, hs=hs)
+    hs_g = host(hs)
+    for t in range(steps):
+        assert_vec_close(hs_g[t], hs_ref[t], "h_%d" % t)
+    assert_vec_close(host(dh), h, "h final")
+    assert_vec_close(host(dc), c, "c final")
+
+
 def test_config3_lstm_1024_batch64(amq):
     from paper_1802_00150_amd import inputs
     c = inputs.lstm_large(steps=6)
