@@ -363,6 +363,10 @@ def main():
             for k in (2, 3):
                 ms = bench_gemm_kernel(amq, dev, 4096, 1024, k, k, b)
                 also["gemm_b%d_w%da%d_us" % (b, k, k)] = ms * 1e3
+        # config 4's output projection: 10000 x 1024, W2 / A3, batch 256 -> fp32 logits
+        ms = bench_gemm_kernel(amq, dev, 10000, 1024, 2, 3, 256)
+        also["projection_10000x1024_w2a3_b256_us"] = ms * 1e3
+        also["projection_10000x1024_w2a3_b256_TFLOPs"] = 2.0 * 10000 * 1024 * 6 * 256 / (ms * 1e-3) / 1e12
 
     if "gru" in sections:
         also["gru_b256_with_projection_steps_per_s"] = 1e3 / bench_gru(amq, dev, 100, 10)
