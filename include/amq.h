@@ -6,9 +6,8 @@
  * Conventions (all entry points):
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
  *   - The caller owns every buffer, including workspaces.  The library
- *     allocates nothing and keeps no state between calls (except the entry
- *     point whose comment says it keeps static scratch).  Inputs are never modified.  Outputs must
- *     not alias inputs unless stated.
+ *     allocates nothing and keeps no state between calls.  Inputs are never
+ *     modified.  Outputs must not alias inputs unless stated.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise the host.
  *   - Return value: AMQ_OK, or an error code.  Arguments are validated on the
