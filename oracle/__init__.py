@@ -20,6 +20,7 @@ _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
 _u32p = np.ctypeslib.ndpointer(dtype=np.uint32, flags="C_CONTIGUOUS")
 _i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
 _f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_i64p = np.ctypeslib.ndpointer(dtype=np.int64, flags="C_CONTIGUOUS")
 _i64 = C.c_int64
 _int = C.c_int
 
@@ -50,6 +51,12 @@ def lib():
                                            _f32p, _f32p, _f32p, _i64, _int, _int, _f32p, _f32p]
         L.amq_oracle_gru_step.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
                                           C.c_void_p, _f32p, _f32p, _i64, _int, _int, _f32p]
+        L.amq_oracle_embedding_lookup.argtypes = [_u32p, _f32p, _i64, _i64, _int, _i64p, _i64, _u32p, _f32p]
+        L.amq_oracle_lstm_step_xq.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
+                                              _u32p, _f32p, _f32p, _f32p, _i64, _int, _int, _f32p, _f32p]
+        L.amq_oracle_log_softmax.argtypes = [_f32p, _i64, _i64, _f32p]
+        L.amq_oracle_softmax_layer.argtypes = [_u32p, _f32p, _i64, _i64, _int, C.c_void_p, _f32p, _i64,
+                                               _int, _int, _f32p, _f32p]
         L.amq_oracle_gamma.argtypes = [C.c_double] * 4
         L.amq_oracle_gamma.restype = C.c_double
         _lib = L
@@ -208,6 +215,57 @@ def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T
     lib().amq_oracle_gru_step(Wxp, _f32(alpha_x), Whp, _f32(alpha_h), I, H, k_w, bx_p, bh_p, x, h_prev,
                               B, k_a, T, h)
     return h
+
+
+def embedding_lookup(Ep, alpha_e, n, ids):
+    """Ep [k, vocab, wpr], alpha_e [vocab, k], ids [B] -> Xp [k, B, wpr], beta [B, k]."""
+    Ep = np.ascontiguousarray(Ep, np.uint32)
+    ids = np.ascontiguousarray(ids, np.int64)
+    k, vocab, w = Ep.shape
+    B = ids.shape[0]
+    if ids.min() < 0 or ids.max() >= vocab:
+        raise ValueError("id out of range")
+    Xp = np.zeros((k, B, w), np.uint32)
+    beta = np.zeros((B, k), np.float32)
+    lib().amq_oracle_embedding_lookup(Ep, _f32(alpha_e), vocab, n, k, ids, B, Xp, beta)
+    return Xp, beta
+
+
+def lstm_step_xq(Wxp, alpha_x, Whp, alpha_h, I, H, bias, Xp, beta_x, h_prev, c_prev, T):
+    """LSTM step with x_t given as packed planes Xp [k_a, B, wpr(I)] + beta_x [B, k_a]."""
+    Wxp = np.ascontiguousarray(Wxp, np.uint32)
+    Whp = np.ascontiguousarray(Whp, np.uint32)
+    Xp = np.ascontiguousarray(Xp, np.uint32)
+    k_w = Wxp.shape[0]
+    k_a, B, _ = Xp.shape
+    h_prev, c_prev = _f32(h_prev), _f32(c_prev)
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    bias_a, bias_p = _opt(bias)
+    lib().amq_oracle_lstm_step_xq(Wxp, _f32(alpha_x), Whp, _f32(alpha_h), I, H, k_w, bias_p, Xp,
+                                  _f32(beta_x), h_prev, c_prev, B, k_a, T, h, c)
+    return h, c
+
+
+def log_softmax(Y):
+    Y = _f32(Y)
+    B, V = Y.shape
+    out = np.zeros((B, V), np.float32)
+    lib().amq_oracle_log_softmax(Y, B, V, out)
+    return out
+
+
+def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T):
+    """Returns (logits, logprob), each [B, V] float32."""
+    Wsp = np.ascontiguousarray(Wsp, np.uint32)
+    k_w, V, _ = Wsp.shape
+    h = _f32(h)
+    B = h.shape[0]
+    logits = np.zeros((B, V), np.float32)
+    logprob = np.zeros((B, V), np.float32)
+    bias_a, bias_p = _opt(bias)
+    lib().amq_oracle_softmax_layer(Wsp, _f32(alpha_s), V, H, k_w, bias_p, h, B, k_a, T, logits, logprob)
+    return logits, logprob
 
 
 def gamma(m, n, k_w, k_h):

@@ -24,6 +24,9 @@
  * routine; non-increasing error over the half-steps of Alg. 2; binary dots
  * against an integer matrix product on unpacked +-1 codes; GEMM and the two
  * cells against dense fp64 products of the de-quantized operands; the
+ * embedding lookup against quantizing the looked-up row; the log-softmax
+ * against a library routine, the two-class closed form and normalisation;
+ * the output layer against a dense fp64 layer on de-quantized operands; the
  * operation-count model of Sec. 4.
  * Parity unpinned: nothing in this file.  (Trained-model accuracy tables are
  * outside what this oracle computes.)
@@ -346,14 +349,12 @@ void amq_oracle_binary_gemm(const uint32_t* Wp, const float* alpha, int64_t m, i
   free(D);
 }
 
-/* Pre-activations a[b][r] = bias[r] + quantized product, kept in binary64. */
-static void preact(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
-                   const float* X, int64_t batch, int k_a, int T, const float* bias, double* a) {
-  int64_t wpr = amq_oracle_wpr(n);
-  uint32_t* Xp = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)k_a * (size_t)batch * (size_t)wpr);
-  float* beta = (float*)malloc(sizeof(float) * (size_t)batch * (size_t)k_a);
+/* Pre-activations a[b][r] = bias[r] + quantized product on operands that are
+ * already quantized, kept in binary64. */
+static void preact_packed(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                          const uint32_t* Xp, const float* beta, int64_t batch, int k_a,
+                          const float* bias, double* a) {
   int32_t* D = (int32_t*)malloc(sizeof(int32_t) * (size_t)batch * (size_t)m * (size_t)(k_w * k_a));
-  amq_oracle_quantize_rows(X, batch, n, n, k_a, T, Xp, beta);
   amq_oracle_binary_dots(Wp, m, n, k_w, Xp, batch, k_a, D);
   for (int64_t b = 0; b < batch; ++b)
     for (int64_t r = 0; r < m; ++r) {
@@ -367,11 +368,38 @@ static void preact(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n,
       a[b * m + r] = y;
     }
   free(D);
+}
+
+/* The same with the dense operand X quantized on line first (k_a bits, T cycles). */
+static void preact(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
+                   const float* X, int64_t batch, int k_a, int T, const float* bias, double* a) {
+  int64_t wpr = amq_oracle_wpr(n);
+  uint32_t* Xp = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)k_a * (size_t)batch * (size_t)wpr);
+  float* beta = (float*)malloc(sizeof(float) * (size_t)batch * (size_t)k_a);
+  amq_oracle_quantize_rows(X, batch, n, n, k_a, T, Xp, beta);
+  preact_packed(Wp, alpha, m, n, k_w, Xp, beta, batch, k_a, bias, a);
   free(beta);
   free(Xp);
 }
 
 static double sigmoid(double a) { return 1.0 / (1.0 + exp(-a)); }
+
+/* The pointwise part of Eq. 6 on binary64 pre-activations ax + ah. */
+static void lstm_cell(const double* ax, const double* ah, int64_t H, int64_t B, const float* c_prev,
+                      float* h_out, float* c_out) {
+  int64_t m = 4 * H;
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t u = 0; u < H; ++u) {
+      double gi = sigmoid(ax[b * m + u] + ah[b * m + u]);
+      double gf = sigmoid(ax[b * m + H + u] + ah[b * m + H + u]);
+      double go = sigmoid(ax[b * m + 2 * H + u] + ah[b * m + 2 * H + u]);
+      double gg = tanh(ax[b * m + 3 * H + u] + ah[b * m + 3 * H + u]);
+      double c = gf * (double)c_prev[b * H + u] + gi * gg;
+      double h = go * tanh(c);
+      c_out[b * H + u] = (float)c;
+      h_out[b * H + u] = (float)h;
+    }
+}
 
 /* ------------------------------------------------------------------ *
  * One quantized LSTM step, Eq. 6.  Wx is 4H x I, Wh is 4H x H, each row-wise
@@ -389,19 +417,86 @@ void amq_oracle_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint3
   double* ah = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
   preact(Wxp, alpha_x, m, I, k_w, x, B, k_a, T, bias, ax);
   preact(Whp, alpha_h, m, H, k_w, h_prev, B, k_a, T, NULL, ah);
-  for (int64_t b = 0; b < B; ++b)
-    for (int64_t u = 0; u < H; ++u) {
-      double gi = sigmoid(ax[b * m + u] + ah[b * m + u]);
-      double gf = sigmoid(ax[b * m + H + u] + ah[b * m + H + u]);
-      double go = sigmoid(ax[b * m + 2 * H + u] + ah[b * m + 2 * H + u]);
-      double gg = tanh(ax[b * m + 3 * H + u] + ah[b * m + 3 * H + u]);
-      double c = gf * (double)c_prev[b * H + u] + gi * gg;
-      double h = go * tanh(c);
-      c_out[b * H + u] = (float)c;
-      h_out[b * H + u] = (float)h;
-    }
+  lstm_cell(ax, ah, H, B, c_prev, h_out, c_out);
   free(ax);
   free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * Embedding lookup (Eq. 6, first line, with the one-hot input of a language
+ * model; Sec. 4): W_e x_t is row id of the embedding matrix, and with every
+ * row of W_e quantized on its own off line that row is a finished k-bit
+ * quantization.
+ * Ep: [k][vocab][wpr(n)], alpha_e: [vocab][k]  ->  Xp: [k][B][wpr], beta: [B][k].
+ * ------------------------------------------------------------------ */
+void amq_oracle_embedding_lookup(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t n,
+                                 int k, const int64_t* ids, int64_t B, uint32_t* Xp, float* beta) {
+  int64_t wpr = amq_oracle_wpr(n);
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t id = ids[b];
+    for (int i = 0; i < k; ++i) {
+      for (int64_t w = 0; w < wpr; ++w)
+        Xp[((size_t)i * B + b) * wpr + w] = Ep[((size_t)i * vocab + id) * wpr + w];
+      beta[b * k + i] = alpha_e[id * k + i];
+    }
+  }
+}
+
+/* ------------------------------------------------------------------ *
+ * The LSTM step of Eq. 6 with x_t arriving already quantized (packed planes
+ * Xp [k_a][B][wpr(I)] and coefficients beta_x [B][k_a], e.g. looked up in a
+ * quantized embedding); h_{t-1} is quantized on line as before.
+ * ------------------------------------------------------------------ */
+void amq_oracle_lstm_step_xq(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                             const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                             const uint32_t* Xp, const float* beta_x, const float* h_prev,
+                             const float* c_prev, int64_t B, int k_a, int T, float* h_out,
+                             float* c_out) {
+  int64_t m = 4 * H;
+  double* ax = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  double* ah = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  preact_packed(Wxp, alpha_x, m, I, k_w, Xp, beta_x, B, k_a, bias, ax);
+  preact(Whp, alpha_h, m, H, k_w, h_prev, B, k_a, T, NULL, ah);
+  lstm_cell(ax, ah, H, B, c_prev, h_out, c_out);
+  free(ax);
+  free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * Logarithm of the softmax of Eq. 6 (last line), row by row:
+ *   out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])),
+ * evaluated in binary64 with the row maximum taken out of the exponent, and
+ * rounded once.
+ * ------------------------------------------------------------------ */
+void amq_oracle_log_softmax(const float* Y, int64_t B, int64_t V, float* out) {
+  for (int64_t b = 0; b < B; ++b) {
+    const float* y = Y + (size_t)b * V;
+    double mx = (double)y[0];
+    for (int64_t v = 1; v < V; ++v)
+      if ((double)y[v] > mx) mx = (double)y[v];
+    double s = 0.0;
+    for (int64_t v = 0; v < V; ++v) s += exp((double)y[v] - mx);
+    double lse = mx + log(s);
+    for (int64_t v = 0; v < V; ++v) out[(size_t)b * V + v] = (float)((double)y[v] - lse);
+  }
+}
+
+/* ------------------------------------------------------------------ *
+ * Output layer of Eq. 6: y_t = softmax(W_s h_t + b_s) with W_s (V x H)
+ * row-wise k_w-bit and h_t quantized on line to k_a bits (T cycles).  The
+ * logits are stored values (binary32); the log-probabilities are formed from
+ * the stored logits.  logits may be NULL.
+ * ------------------------------------------------------------------ */
+void amq_oracle_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H,
+                              int k_w, const float* bias, const float* h, int64_t B, int k_a, int T,
+                              float* logits, float* logprob) {
+  double* a = (double*)malloc(sizeof(double) * (size_t)B * (size_t)V);
+  float* y = logits ? logits : (float*)malloc(sizeof(float) * (size_t)B * (size_t)V);
+  preact(Wsp, alpha_s, V, H, k_w, h, B, k_a, T, bias, a);
+  for (size_t e = 0; e < (size_t)B * (size_t)V; ++e) y[e] = (float)a[e];
+  amq_oracle_log_softmax(y, B, V, logprob);
+  if (!logits) free(y);
+  free(a);
 }
 
 /* ------------------------------------------------------------------ *

@@ -67,3 +67,18 @@ def heavy_tailed(trial: int = 0, rows: int = 16384, cols: int = 4096):
     mask = g.random((rows, cols), dtype=np.float32) < np.float32(0.01)
     W[mask] *= np.float32(10.0)
     return W
+
+
+def language_model(trial: int = 0, steps: int = STEPS, B: int = 1, H: int = 1024, E: int = 1024,
+                   vocab: int = 42000, k: int = 2):
+    """Full language-model step at the paper's large shape (hidden 1024, vocabulary 42000, whose
+    output layer is 42000 x 1024): embedding table ~ N(0, 0.1^2), LSTM weights and output layer
+    ~ N(0, 0.02^2), uniform token ids.  Config index 6 in the seed scheme."""
+    g = rng(6, trial)
+    W = normal(g, (4 * H, E + H), 0.02)
+    emb = normal(g, (vocab, E), 0.1)
+    Ws = normal(g, (vocab, H), 0.02)
+    bs = normal(g, (vocab,), 0.1)
+    ids = g.integers(0, vocab, size=(steps, B)).astype(np.int64)
+    return dict(E=E, H=H, B=B, V=vocab, k_w=k, k_a=k, T=2, Wx=np.ascontiguousarray(W[:, :E]),
+                Wh=np.ascontiguousarray(W[:, E:]), emb=emb, Ws=Ws, bs=bs, ids=ids)
