@@ -176,6 +176,49 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                  const float* bias_h, const float* x, const float* h_prev, int64_t B, int k_a, int T,
                  float* h_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Embedding lookup (Eq. 6, first line; Sec. 4): with one-hot inputs W_e x_t is a row of the
+ * embedding matrix, and a table quantized off line by amq_quantize_weights (Ep [k][vocab][wpr(n)],
+ * alpha_e [vocab][k]) holds that row as a finished k-bit quantization.  Copies rows ids[0..B)
+ * into operand form:
+ *   ids [B] int64 (device);  Xp [k][B][wpr(n)] out;  beta [B][k] out.
+ * An id outside [0, vocab) gives the zero vector (plane bits 0, coefficients 0); it is never
+ * dereferenced.
+ */
+int amq_embedding_lookup(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t n, int k,
+                         const int64_t* ids, int64_t B, uint32_t* Xp, float* beta, void* stream);
+
+/*
+ * Logarithm of the softmax of Eq. 6 (last line), for every row of Y [B][V]:
+ *   out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])).
+ * out may be Y itself.
+ */
+int amq_log_softmax(const float* Y, int64_t B, int64_t V, float* out, void* stream);
+
+/*
+ * Output layer of Eq. 6: log softmax(W_s h_t + b_s), W_s (V x H) row-wise k_w-bit, h_t quantized
+ * on line to k_a bits (T cycles).  logprob [B][V] receives the logits first and is then normalised
+ * in place.  workspace: at least amq_softmax_layer_workspace_bytes(H, B, k_a) bytes, 256-byte aligned.
+ */
+size_t amq_softmax_layer_workspace_bytes(int64_t H, int64_t B, int k_a);
+int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_w,
+                      const float* bias, const float* h, int64_t B, int k_a, int T, float* logprob,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One whole language-model step, Eq. 6 from token to distribution: x_t = row ids[b] of the quantized
+ * embedding (k_a planes: the table must be quantized with k = k_a), h_{t-1} quantized on line (k_a),
+ * LSTM cell (h and c [B][H] are read and overwritten), h_t quantized again (k_as) and the output
+ * layer W_s (V x H, k_ws-bit) with log-softmax -> logprob [B][V].
+ *   workspace: at least amq_lm_workspace_bytes(E, H, B, k_a, k_as) bytes, 256-byte aligned.
+ */
+size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t B, int k_a, int k_as);
+int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as,
+                int T, float* logprob, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -463,7 +463,7 @@ void amq_oracle_lstm_step_xq(const uint32_t* Wxp, const float* alpha_x, const ui
 }
 
 /* ------------------------------------------------------------------ *
- * Logarithm of the softmax of Eq. 6 (last line), row by row:
+ * Logarithm of the softmax of Eq. 6 (last line), for every row:
  *   out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])),
  * evaluated in binary64 with the row maximum taken out of the exponent, and
  * rounded once.

@@ -19,6 +19,8 @@ EXPORTS = [
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_packed", "amq_lstm_sequence",
     "amq_gru_workspace_bytes", "amq_gru_step",
+    "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
+    "amq_lm_workspace_bytes", "amq_lm_step",
 ]
 
 _lib = None
@@ -59,6 +61,14 @@ def lib():
                                         _int, _p, _p, _sz, _p]
         L.amq_gru_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
                                    _sz, _p]
+        L.amq_embedding_lookup.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p, _p, _p]
+        L.amq_log_softmax.argtypes = [_p, _i64, _i64, _p, _p]
+        L.amq_softmax_layer_workspace_bytes.argtypes = [_i64, _i64, _int]
+        L.amq_softmax_layer_workspace_bytes.restype = _sz
+        L.amq_softmax_layer.argtypes = [_p, _p, _i64, _i64, _int, _p, _p, _i64, _int, _int, _p, _p, _sz, _p]
+        L.amq_lm_workspace_bytes.argtypes, L.amq_lm_workspace_bytes.restype = [_i64, _i64, _i64, _int, _int], _sz
+        L.amq_lm_step.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
+                                  _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         _lib = L
     return _lib
 
@@ -261,3 +271,69 @@ def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T
                               _dev(x, torch.float32), _dev(h_prev, torch.float32), B, k_a, T,
                               _dev(h_out, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
     return h_out
+
+
+def embedding_lookup(Ep, alpha_e, n, ids):
+    """Rows ids [B] (int64) of a quantized table Ep [k, vocab, wpr(n)], alpha_e [vocab, k] ->
+    Xp [k, B, wpr(n)], beta [B, k]."""
+    k, vocab, w = Ep.shape
+    B = ids.shape[0]
+    Xp = _empty((k, B, w), torch.int32, Ep)
+    beta = _empty((B, k), torch.float32, Ep)
+    _check(lib().amq_embedding_lookup(_dev(Ep, torch.int32), _dev(alpha_e, torch.float32), vocab, n, k,
+                                      _dev(ids, torch.int64), B, Xp.data_ptr(), beta.data_ptr(), _stream()))
+    return Xp, beta
+
+
+def log_softmax(Y, out=None):
+    """Row-wise log-softmax of Y [B, V]; out may be Y itself."""
+    B, V = Y.shape
+    if out is None:
+        out = torch.empty_like(Y)
+    _check(lib().amq_log_softmax(_dev(Y, torch.float32), B, V, _dev(out, torch.float32), _stream()))
+    return out
+
+
+def softmax_layer_workspace(H, B, k_a, device):
+    nbytes = int(lib().amq_softmax_layer_workspace_bytes(H, B, k_a))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T, ws=None, logprob=None):
+    """log softmax(W_s h + b_s) with W_s quantized (Wsp [k_w, V, wpr(H)]) and h [B, H] quantized on line."""
+    k_w, V, _ = Wsp.shape
+    B = h.shape[0]
+    if ws is None:
+        ws = softmax_layer_workspace(H, B, k_a, h.device)
+    if logprob is None:
+        logprob = _empty((B, V), torch.float32, h)
+    _check(lib().amq_softmax_layer(_dev(Wsp, torch.int32), _dev(alpha_s, torch.float32), V, H, k_w, _opt(bias),
+                                   _dev(h, torch.float32), B, k_a, T, _dev(logprob, torch.float32),
+                                   ws.data_ptr(), ws.numel(), _stream()))
+    return logprob
+
+
+def lm_workspace(E, H, B, k_a, k_as, device):
+    nbytes = int(lib().amq_lm_workspace_bytes(E, H, B, k_a, k_as))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def lm_step(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, bias_s, ids, h, c, k_a, k_as, T,
+            ws=None, logprob=None):
+    """One language-model step: ids [B] -> embedding rows -> LSTM (h, c updated in place) -> log-probabilities
+    [B, V]."""
+    vocab = Ep.shape[1]
+    k_w = Wxp.shape[0]
+    k_ws, V, _ = Wsp.shape
+    B = ids.shape[0]
+    if ws is None:
+        ws = lm_workspace(E, H, B, k_a, k_as, h.device)
+    if logprob is None:
+        logprob = _empty((B, V), torch.float32, h)
+    _check(lib().amq_lm_step(_dev(Ep, torch.int32), _dev(alpha_e, torch.float32), vocab, E,
+                             _dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                             _dev(alpha_h, torch.float32), H, k_w, _opt(bias), _dev(Wsp, torch.int32),
+                             _dev(alpha_s, torch.float32), V, k_ws, _opt(bias_s), _dev(ids, torch.int64),
+                             _dev(h, torch.float32), _dev(c, torch.float32), B, k_a, k_as, T,
+                             _dev(logprob, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
+    return logprob

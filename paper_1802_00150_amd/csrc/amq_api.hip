@@ -385,4 +385,120 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
 }
 
+int amq_embedding_lookup(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t n, int k,
+                         const int64_t* ids, int64_t B, uint32_t* Xp, float* beta, void* stream) {
+  if (!Ep || !alpha_e || !ids || !Xp || !beta) return AMQ_ERR_INVALID;
+  if (!bits_ok(k) || vocab <= 0 || n <= 0 || B <= 0) return AMQ_ERR_INVALID;
+  if (n > AMQ_MAX_QUANT_N || B > 0x7fffffffLL) return AMQ_ERR_UNSUPPORTED;
+  amq::QuantArgs q{};
+  q.mode = amq::kQuantFull;
+  q.gather = amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids), (int)n, (int)B, Xp, beta};
+  return hip_status(amq::launch_quantize(q, k, static_cast<hipStream_t>(stream)));
+}
+
+int amq_log_softmax(const float* Y, int64_t B, int64_t V, float* out, void* stream) {
+  if (!Y || !out || B <= 0 || V <= 0) return AMQ_ERR_INVALID;
+  if (B > 0x7fffffffLL || V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_log_softmax(Y, B, V, out, static_cast<hipStream_t>(stream)));
+}
+
+// Workspace of the output layer: the quantized h_t.
+struct SoftmaxWs {
+  uint32_t* hp;
+  float* beta;
+  size_t total;
+};
+static SoftmaxWs carve_softmax(void* ws, int64_t H, int64_t B, int k_a) {
+  SoftmaxWs w;
+  char* base = static_cast<char*>(ws);
+  size_t off = 0;
+  w.hp = reinterpret_cast<uint32_t*>(base ? base + off : nullptr);
+  off += up256(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(H));
+  w.beta = reinterpret_cast<float*>(base ? base + off : nullptr);
+  off += up256(sizeof(float) * (size_t)B * k_a);
+  w.total = off;
+  return w;
+}
+
+size_t amq_softmax_layer_workspace_bytes(int64_t H, int64_t B, int k_a) {
+  if (H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve_softmax(nullptr, H, B, k_a).total;
+}
+
+static int softmax_layer_launch(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_w,
+                                const float* bias, const float* h, int64_t B, int k_a, int T, float* logprob,
+                                const SoftmaxWs& w, hipStream_t s) {
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  int st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs g = gemm_args(Wsp, alpha_s, V, H, k_w, w.hp, w.beta, B, k_a, bias, 0, logprob);
+  st = run_product(g, s);
+  if (st != AMQ_OK) return st;
+  return hip_status(amq::launch_log_softmax(logprob, B, V, logprob, s));
+}
+
+int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_w,
+                      const float* bias, const float* h, int64_t B, int k_a, int T, float* logprob,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Wsp || !alpha_s || !h || !logprob || !workspace) return AMQ_ERR_INVALID;
+  if (!bits_ok(k_w) || !bits_ok(k_a) || T < 0 || V <= 0 || H <= 0 || B <= 0) return AMQ_ERR_INVALID;
+  if (!aligned(Wsp, 16) || !aligned(workspace, 256)) return AMQ_ERR_INVALID;
+  if (workspace_bytes < carve_softmax(nullptr, H, B, k_a).total) return AMQ_ERR_INVALID;
+  if (H > AMQ_MAX_QUANT_N || B > (1 << 24) || V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
+  SoftmaxWs w = carve_softmax(workspace, H, B, k_a);
+  return softmax_layer_launch(Wsp, alpha_s, V, H, k_w, bias, h, B, k_a, T, logprob, w,
+                              static_cast<hipStream_t>(stream));
+}
+
+size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t B, int k_a, int k_as) {
+  if (E <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
+  return carve(nullptr, E, H, B, k_a, 4, 1).total + carve_softmax(nullptr, H, B, k_as).total;
+}
+
+int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as, int T,
+                float* logprob, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !c || !logprob) return AMQ_ERR_INVALID;
+  if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
+  const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
+  const size_t need_step = sizes_ok ? carve(nullptr, E, H, B, k_a, 4, 1).total : 0;
+  const size_t need = sizes_ok ? need_step + carve_softmax(nullptr, H, B, k_as).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, ids, h, B, k_a, T, h, workspace, workspace_bytes,
+                      need);
+  if (st != AMQ_OK) return st;
+  if (!aligned(Wsp, 16) || !aligned(Ep, 16)) return AMQ_ERR_INVALID;
+  if (V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
+  SoftmaxWs sw = carve_softmax(static_cast<char*>(workspace) + need_step, H, B, k_as);
+
+  // h_{t-1} quantized on line and x_t looked up in the quantized embedding, one launch
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  q.gather = amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids), (int)E, (int)B, w.xp,
+                            w.beta_x};
+  st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, bias, w.xp, w.beta_x, w.hp, w.beta_h, c, B, k_a,
+                         h, c, nullptr, s);
+  if (st < 0) {
+    amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, E, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
+    st = run_product(gx, s);
+    if (st != AMQ_OK) return st;
+    amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
+    st = run_product(gh, s);
+    if (st != AMQ_OK) return st;
+    st = hip_status(amq::launch_lstm_pointwise(w.pre0, c, h, c, nullptr, B, H, s));
+  }
+  if (st != AMQ_OK) return st;
+  return softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, h, B, k_as, T, logprob, sw, s);
+}
+
 }  // extern "C"

@@ -19,11 +19,27 @@ struct QuantSeg {
   float* coef;       // [count][k]
 };
 
-// Up to two groups of vectors in one launch (x_t and h_{t-1} of a recurrent step).
+// Rows of a quantized table copied out by index in the same launch (the embedding lookup of a
+// language-model step): table planes [k][vocab][wpr(n)], coefficients [vocab][k].  An index
+// outside [0, vocab) yields the zero vector (all plane bits 0, coefficients 0).
+struct GatherSeg {
+  const uint32_t* table;   // [k][vocab][wpr(n)]
+  const float* table_coef; // [vocab][k]
+  long long vocab;
+  const long long* ids;    // [count]
+  int n;
+  int count;               // 0 = unused
+  uint32_t* planes;        // [k][count][wpr(n)]
+  float* coef;             // [count][k]
+};
+
+// Up to two groups of vectors in one launch (x_t and h_{t-1} of a recurrent step), plus an
+// optional gather of already quantized rows.
 struct QuantArgs {
   QuantSeg seg[2];
   int T;
   int mode;
+  GatherSeg gather;
 };
 
 hipError_t launch_quantize(const QuantArgs& a, int k, hipStream_t s);
@@ -115,6 +131,10 @@ struct Seq1Args {
 };
 bool lstm_seq1_supported(long long I, long long H, long long B, int k_w, int k_a);
 hipError_t launch_lstm_seq1(Seq1Args a, int k_w, int k_a, hipStream_t s);
+
+// ---- output layer -----------------------------------------------------------------------
+// out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])); out may alias Y.
+hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* out, hipStream_t s);
 
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU

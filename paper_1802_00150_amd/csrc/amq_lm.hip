@@ -1,0 +1,105 @@
+// Logarithm of the softmax that closes Eq. 6 (y_t = softmax(W_s h_t + b_s)), one workgroup of
+// 16 wavefronts per row of logits.  The row is read once into registers (NV values per lane,
+// lane-interleaved so that every load is a coalesced 256-byte wave access), the maximum and the
+// sum of exponentials are reduced across the workgroup, and the shifted row is written back.
+// Rows longer than 64 * 1024 values take the re-reading variant (three passes, same arithmetic).
+//
+// Precision: binary32 throughout; exp through v_exp_f32, the sum of V <= 2^16 positive terms as
+// per-lane partial sums + a tree, log through logf.  Absolute error of a result is a few 1e-6.
+#include "amq_device.h"
+#include "amq_launch.h"
+
+namespace amq {
+
+namespace {
+
+constexpr int kLsmThreads = 1024;
+constexpr int kLsmWaves = kLsmThreads / kWave;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sumf(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Workgroup-wide maximum / sum through LDS; `sh` holds kLsmWaves floats and is free again on return.
+template <bool IS_MAX>
+__device__ __forceinline__ float block_reduce(float v, float* sh) {
+  v = IS_MAX ? wave_max(v) : wave_sumf(v);
+  __syncthreads();
+  if (lane_id() == 0) sh[wave_id()] = v;
+  __syncthreads();
+  float t = sh[0];
+#pragma unroll
+  for (int i = 1; i < kLsmWaves; ++i) t = IS_MAX ? fmaxf(t, sh[i]) : t + sh[i];
+  return t;
+}
+
+// NV > 0: the row lives in registers.  NV == 0: re-reading variant for any V.
+template <int NV>
+__global__ __launch_bounds__(kLsmThreads) void log_softmax_kernel(const float* Y, long long V, float* out) {
+  __shared__ float sh[kLsmWaves];
+  const float* y = Y + (long long)blockIdx.x * V;
+  float* o = out + (long long)blockIdx.x * V;
+  const int t = threadIdx.x;
+  const float kLow = -3.0e38f;
+  if constexpr (NV > 0) {
+    float v[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const long long e = (long long)j * kLsmThreads + t;
+      v[j] = e < V ? y[e] : kLow;
+    }
+    float mx = kLow;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) mx = fmaxf(mx, v[j]);
+    mx = block_reduce<true>(mx, sh);
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const long long e = (long long)j * kLsmThreads + t;
+      s += e < V ? __expf(v[j] - mx) : 0.0f;
+    }
+    s = block_reduce<false>(s, sh);
+    const float lse = mx + logf(s);
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const long long e = (long long)j * kLsmThreads + t;
+      if (e < V) o[e] = v[j] - lse;
+    }
+  } else {
+    float mx = kLow;
+    for (long long e = t; e < V; e += kLsmThreads) mx = fmaxf(mx, y[e]);
+    mx = block_reduce<true>(mx, sh);
+    float s = 0.0f;
+    for (long long e = t; e < V; e += kLsmThreads) s += __expf(y[e] - mx);
+    s = block_reduce<false>(s, sh);
+    const float lse = mx + logf(s);
+    for (long long e = t; e < V; e += kLsmThreads) o[e] = y[e] - lse;
+  }
+}
+
+template <int NV>
+void launch_lsm(const float* Y, long long B, long long V, float* out, hipStream_t s) {
+  hipLaunchKernelGGL((log_softmax_kernel<NV>), dim3((unsigned)B), dim3(kLsmThreads), 0, s, Y, V, out);
+}
+
+}  // namespace
+
+hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* out, hipStream_t s) {
+  const long long nv = (V + kLsmThreads - 1) / kLsmThreads;
+  if (nv <= 4) launch_lsm<4>(Y, B, V, out, s);
+  else if (nv <= 12) launch_lsm<12>(Y, B, V, out, s);
+  else if (nv <= 24) launch_lsm<24>(Y, B, V, out, s);
+  else if (nv <= 44) launch_lsm<44>(Y, B, V, out, s);
+  else if (nv <= 64) launch_lsm<64>(Y, B, V, out, s);
+  else launch_lsm<0>(Y, B, V, out, s);
+  return hipGetLastError();
+}
+
+}  // namespace amq

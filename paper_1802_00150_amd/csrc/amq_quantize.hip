@@ -18,12 +18,34 @@ namespace amq {
 
 namespace {
 
+// One workgroup copies row ids[g] of a quantized table (all K planes and coefficients) to
+// position g of the output operand; an index outside the table gives the zero vector.
+template <int K>
+__device__ __forceinline__ void gather_row(const GatherSeg& t, int g, int nthreads) {
+  const int wpr = 4 * ((t.n + 127) >> 7);
+  const long long id = t.ids[g];
+  const bool ok = id >= 0 && id < t.vocab;
+  const long long row = ok ? id : 0;
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    const uint32_t* src = t.table + ((long long)i * t.vocab + row) * wpr;
+    uint32_t* dst = t.planes + ((long long)i * t.count + g) * wpr;
+    for (int w = threadIdx.x; w < wpr; w += nthreads) dst[w] = ok ? src[w] : 0u;
+  }
+  if (threadIdx.x < K) t.coef[(long long)g * K + threadIdx.x] = ok ? t.table_coef[row * K + threadIdx.x] : 0.0f;
+}
+
 template <int K, int NJ, int NW>
 __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
   __shared__ double sh[2][16 * kMaxRed];
   int phase = 0;
   const int lane = lane_id(), wv = wave_id();
   int vec = blockIdx.x;
+  if (vec >= a.seg[0].count + a.seg[1].count) {
+    // workgroups past the vectors to quantize copy table rows by index
+    gather_row<K>(a.gather, vec - a.seg[0].count - a.seg[1].count, 64 * NW);
+    return;
+  }
   const int which = (vec >= a.seg[0].count) ? 1 : 0;
   if (which) vec -= a.seg[0].count;
   const float* X = which ? a.seg[1].X : a.seg[0].X;
@@ -107,14 +129,15 @@ void launch_one(const QuantArgs& a, int total, hipStream_t s) {
 // always take four waves.
 template <int K>
 hipError_t launch_k(const QuantArgs& a, int max_n, hipStream_t s) {
-  const int total = a.seg[0].count + a.seg[1].count;
+  const int nvec = a.seg[0].count + a.seg[1].count;
+  const int total = nvec + a.gather.count;  // one workgroup per vector, one per gathered row
   if (total == 0) return hipSuccess;
-  const int nslots = 2 * ((max_n + 127) / 128);
-  int nw = total >= 1024 ? 1 : 4;
+  const int nslots = nvec ? 2 * ((max_n + 127) / 128) : 1;
+  int nw = nvec >= 1024 ? 1 : 4;
   // long rows in the throughput regime: four waves of 16 entries per lane keep ~90 registers and
   // five waves per SIMD, against ~230 registers and two waves for one wave of 64 entries per
   // lane (measured +35 / +18 / +9 % at k = 1 / 2 / 3 on 16384 x 4096, -6 % at k = 4)
-  if (total >= 1024 && nslots >= 32 && K <= 3) nw = 4;
+  if (nvec >= 1024 && nslots >= 32 && K <= 3) nw = 4;
   if (nw > nslots) nw = 1;
   if (nw == 1 && nslots > 64) nw = 4;
   if (nslots > 256) return hipErrorInvalidValue;

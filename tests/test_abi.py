@@ -72,6 +72,30 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 16000, 16000, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
+    # language-model entry points
+    assert L.amq_embedding_lookup(p, p, 10, 8, 2, null, 1, p, p, None) == INVALID
+    assert L.amq_embedding_lookup(p, p, 0, 8, 2, p, 1, p, p, None) == INVALID
+    assert L.amq_embedding_lookup(p, p, 10, 8, 5, p, 1, p, p, None) == INVALID
+    assert L.amq_embedding_lookup(p, p, 10, 1 << 15, 2, p, 1, p, p, None) == UNSUPPORTED
+    assert L.amq_log_softmax(p, 0, 8, p, None) == INVALID
+    assert L.amq_log_softmax(null, 1, 8, p, None) == INVALID
+    assert L.amq_log_softmax(p, 1, (1 << 31) + 1, p, None) == UNSUPPORTED
+    need_s = L.amq_softmax_layer_workspace_bytes(8, 1, 2)
+    assert need_s > 0 and need_s % 256 == 0
+    assert L.amq_softmax_layer_workspace_bytes(8, 1, 0) == 0
+    assert L.amq_softmax_layer(p, p, 16, 8, 2, None, p, 1, 2, 2, p, ws, need_s - 1, None) == INVALID
+    assert L.amq_softmax_layer(p, p, 16, 8, 2, None, p, 1, 2, -1, p, ws, need_s, None) == INVALID
+    assert L.amq_softmax_layer(p, p, 16, 8, 2, None, null, 1, 2, 2, p, ws, need_s, None) == INVALID
+    need_l = L.amq_lm_workspace_bytes(8, 8, 1, 2, 3)
+    assert need_l == need + L.amq_softmax_layer_workspace_bytes(8, 1, 3)
+    lm = lambda **kw: L.amq_lm_step(p, p, kw.get("vocab", 10), 8, p, p, p, p, 8, 2, None, p, p, 16, kw.get("k_ws", 2),
+                                    None, kw.get("ids", p), p, p, 1, 2, kw.get("k_as", 3), 2, p, ws,
+                                    kw.get("bytes", need_l), None)
+    assert lm(bytes=need_l - 1) == INVALID
+    assert lm(ids=null) == INVALID
+    assert lm(vocab=0) == INVALID
+    assert lm(k_ws=5) == INVALID
+    assert lm(k_as=0) == INVALID
 
 
 def test_binding_refuses_cpu_tensors():

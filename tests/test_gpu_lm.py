@@ -1,0 +1,162 @@
+"""GPU parity: embedding lookup, log-softmax, output layer and the whole language-model step
+(Eq. 6 from token to distribution) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from gpu_util import assert_vec_close, host, planes_host, to_dev
+from paper_1802_00150_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def amq():
+    import paper_1802_00150_amd as m
+    m.binding.lib()
+    return m
+
+
+@pytest.fixture(autouse=True)
+def threads():
+    oracle.set_threads(oracle.host_threads())
+    yield
+    oracle.set_threads(1)
+
+
+@pytest.mark.parametrize("vocab,n,k,B", [(50, 70, 2, 5), (1000, 300, 2, 1), (333, 1024, 3, 64), (17, 129, 4, 3),
+                                         (64, 5000, 1, 2)])
+def test_embedding_lookup(amq, vocab, n, k, B):
+    import torch
+    g = np.random.default_rng(vocab + n + k)
+    emb = (g.standard_normal((vocab, n)) * 0.1).astype(np.float32)
+    Ep, ae = oracle.quantize_rows(emb, k, 2)
+    ids = g.integers(0, vocab, size=B).astype(np.int64)
+    ids[-1] = ids[0]                      # a repeated id
+    say("embedding vocab=%d n=%d k=%d B=%d" % (vocab, n, k, B))
+    Xr, br = oracle.embedding_lookup(Ep, ae, n, ids)
+    Xg, bg = amq.embedding_lookup(to_dev(Ep), to_dev(ae), n, torch.from_numpy(ids).to("cuda:0"))
+    assert np.array_equal(planes_host(Xg), Xr)
+    assert np.array_equal(host(bg), br)
+
+
+def test_embedding_lookup_out_of_range_id_gives_zero_vector(amq):
+    import torch
+    g = np.random.default_rng(5)
+    emb = (g.standard_normal((20, 200)) * 0.1).astype(np.float32)
+    Ep, ae = oracle.quantize_rows(emb, 2, 2)
+    ids = np.array([3, 20, -1, 19, 1 << 40], np.int64)
+    Xg, bg = amq.embedding_lookup(to_dev(Ep), to_dev(ae), 200, torch.from_numpy(ids).to("cuda:0"))
+    Xg, bg = planes_host(Xg), host(bg)
+    Xr, br = oracle.embedding_lookup(Ep, ae, 200, np.array([3, 19], np.int64))
+    assert np.array_equal(Xg[:, [0, 3]], Xr) and np.array_equal(bg[[0, 3]], br)
+    assert not Xg[:, [1, 2, 4]].any() and not bg[[1, 2, 4]].any()
+
+
+@pytest.mark.parametrize("B,V", [(1, 1), (3, 7), (2, 1000), (5, 4097), (4, 10000), (1, 42000), (64, 42000),
+                                 (2, 65536), (3, 70001)])
+def test_log_softmax(amq, B, V):
+    g = np.random.default_rng(B * 100003 + V)
+    Y = (g.standard_normal((B, V)) * 3.0 + g.standard_normal((B, 1)) * 20.0).astype(np.float32)
+    say("log_softmax B=%d V=%d" % (B, V))
+    ref = oracle.log_softmax(Y)
+    d = to_dev(Y)
+    out = amq.log_softmax(d)
+    assert_vec_close(host(out), ref, "logprob")
+    assert np.array_equal(host(d), Y)            # input untouched
+    amq.log_softmax(d, out=d)                    # in place
+    assert np.array_equal(host(d), host(out))
+    assert np.allclose(np.exp(host(out).astype(np.float64)).sum(axis=1), 1.0, atol=1e-4)
+
+
+@pytest.mark.parametrize("V,H,B,k_w,k_a", [(130, 72, 3, 2, 2), (1000, 300, 1, 2, 3), (777, 256, 20, 3, 3),
+                                           (10000, 1024, 37, 2, 3), (4100, 1500, 18, 2, 2), (300, 2100, 5, 4, 4)])
+def test_softmax_layer(amq, V, H, B, k_w, k_a):
+    g = np.random.default_rng(V + H + B)
+    Ws = (g.standard_normal((V, H)) * 0.05).astype(np.float32)
+    bs = (g.standard_normal(V) * 0.3).astype(np.float32)
+    h = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    Wsp, als = oracle.quantize_rows(Ws, k_w, 2)
+    dW, dA = to_dev(Wsp), to_dev(als)
+    for bias in (None, bs):
+        say("softmax layer V=%d H=%d B=%d W%d/A%d bias=%s" % (V, H, B, k_w, k_a, bias is not None))
+        logits, ref = oracle.softmax_layer(Wsp, als, H, bias, h, k_a, 2)
+        got = amq.softmax_layer(dW, dA, H, None if bias is None else to_dev(bias), to_dev(h), k_a, 2)
+        assert_vec_close(host(got), ref, "logprob")
+
+
+def lm_oracle_step(q, ids, h, c, k_as):
+    Xp, bx = oracle.embedding_lookup(q["Ep"], q["ae"], q["E"], ids)
+    h1, c1 = oracle.lstm_step_xq(q["Wxp"], q["ax"], q["Whp"], q["ah"], q["E"], q["H"], q["bias"], Xp, bx, h, c, 2)
+    _, lp = oracle.softmax_layer(q["Wsp"], q["as"], q["H"], q["bs"], h1, k_as, 2)
+    return h1, c1, lp
+
+
+def lm_setup(cfg, k_ws):
+    k = cfg["k_w"]
+    q = dict(E=cfg["E"], H=cfg["H"], bs=cfg["bs"])
+    q["Ep"], q["ae"] = oracle.quantize_rows(cfg["emb"], k, 2)
+    q["Wxp"], q["ax"] = oracle.quantize_rows(cfg["Wx"], k, 2)
+    q["Whp"], q["ah"] = oracle.quantize_rows(cfg["Wh"], k, 2)
+    q["Wsp"], q["as"] = oracle.quantize_rows(cfg["Ws"], k_ws, 2)
+    g = np.random.default_rng(cfg["H"])
+    q["bias"] = (g.standard_normal(4 * cfg["H"]) * 0.1).astype(np.float32)
+    return q
+
+
+def lm_gpu_step(amq, q, dq, ids, dh, dc, k_a, k_as):
+    import torch
+    return amq.lm_step(dq["Ep"], dq["ae"], q["E"], dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], q["H"], dq["bias"],
+                       dq["Wsp"], dq["as"], dq["bs"], torch.from_numpy(np.ascontiguousarray(ids)).to("cuda:0"),
+                       dh, dc, k_a, k_as, 2)
+
+
+# small and ragged shapes: batch 3 and 1 take the register-resident kernel, 20 the matrix cores
+@pytest.mark.parametrize("E,H,V,B,k,k_ws,k_as", [(40, 24, 130, 3, 2, 2, 2), (300, 300, 10000, 1, 2, 2, 3),
+                                                 (128, 256, 1000, 20, 3, 3, 3), (200, 136, 555, 33, 2, 3, 2)])
+def test_lm_step_teacher_forced_and_free_running(amq, E, H, V, B, k, k_ws, k_as):
+    steps = 4
+    cfg = inputs.language_model(trial=E + B, steps=steps, B=B, H=H, E=E, vocab=V, k=k)
+    q = lm_setup(cfg, k_ws)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    fh, fc = to_dev(h), to_dev(c)                 # free-running GPU state
+    for t in range(steps):
+        say("lm step E=%d H=%d V=%d B=%d t=%d" % (E, H, V, B, t))
+        ids = cfg["ids"][t]
+        h1, c1, lp = lm_oracle_step(q, ids, h, c, k_as)
+        dh, dc = to_dev(h), to_dev(c)             # teacher-forced: the oracle's previous state
+        got = lm_gpu_step(amq, q, dq, ids, dh, dc, k, k_as)
+        assert_vec_close(host(dc), c1, "c")
+        assert_vec_close(host(dh), h1, "h")
+        assert_vec_close(host(got), lp, "logprob")
+        got_free = lm_gpu_step(amq, q, dq, ids, fh, fc, k, k_as)
+        assert_vec_close(host(fh), h1, "h free-running")
+        assert_vec_close(host(got_free), lp, "logprob free-running")
+        h, c = h1, c1
+
+
+@pytest.mark.parametrize("B", [1, 64])
+def test_lm_step_full_size(amq, B):
+    """Hidden 1024, vocabulary 42000 (the output layer is 42000 x 1024), W2/A2."""
+    cfg = inputs.language_model(trial=0, steps=2, B=B)
+    q = lm_setup(cfg, 2)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    g = np.random.default_rng(B)
+    h = np.tanh(g.standard_normal((B, 1024))).astype(np.float32) * np.float32(0.5)
+    c = g.standard_normal((B, 1024)).astype(np.float32)
+    for t in range(2):
+        say("lm full size B=%d t=%d" % (B, t))
+        ids = cfg["ids"][t]
+        h1, c1, lp = lm_oracle_step(q, ids, h, c, 2)
+        dh, dc = to_dev(h), to_dev(c)
+        got = lm_gpu_step(amq, q, dq, ids, dh, dc, 2, 2)
+        assert_vec_close(host(dc), c1, "c")
+        assert_vec_close(host(dh), h1, "h")
+        assert_vec_close(host(got), lp, "logprob")
+        h, c = h1, c1
