@@ -240,6 +240,37 @@ def bench_gru(amq, dev, steps, warmup):
     return wall_time_ms(step, steps, warmup)
 
 
+def bench_lm(amq, dev, B, steps, warmup):
+    """Whole language-model steps (token ids -> log-probabilities), hidden 1024, vocabulary 42000, W2/A2."""
+    import torch
+    from paper_1802_00150_amd import inputs
+    cfg = inputs.language_model(steps=8, B=B)
+    E, H, V, k, T = cfg["E"], cfg["H"], cfg["V"], cfg["k_w"], cfg["T"]
+    Ep, ae = amq.quantize_weights(dv(cfg["emb"], dev), k, T)
+    Wxp, ax = amq.quantize_weights(dv(cfg["Wx"], dev), k, T)
+    Whp, ah = amq.quantize_weights(dv(cfg["Wh"], dev), k, T)
+    Wsp, as_ = amq.quantize_weights(dv(cfg["Ws"], dev), k, T)
+    bs = dv(cfg["bs"], dev)
+    ids = torch.from_numpy(cfg["ids"]).to(dev)
+    h = torch.zeros((B, H), device=dev)
+    c = torch.zeros((B, H), device=dev)
+    ws = amq.lm_workspace(E, H, V, B, k, k, dev)
+    logprob = torch.empty((B, V), device=dev)
+    state = {"t": 0}
+
+    def step():
+        t = state["t"]
+        amq.lm_step(Ep, ae, E, Wxp, ax, Whp, ah, H, None, Wsp, as_, bs, ids[t % 8], h, c, k, k, T, ws=ws,
+                    logprob=logprob)
+        state["t"] = t + 1
+
+    ms = wall_time_ms(step, steps, warmup)
+    ws2 = amq.softmax_layer_workspace(V, H, B, k, dev)
+    ms_layer = event_time_ms(lambda: amq.softmax_layer(Wsp, as_, H, bs, h, k, T, ws=ws2, logprob=logprob), 200, 20)
+    ms_lsm = event_time_ms(lambda: amq.log_softmax(logprob, out=logprob), 200, 20)
+    return ms, ms_layer, ms_lsm
+
+
 def cpu_baseline_lstm(cfg, budget_s=15.0):
     """The oracle, as it stands, on the same LSTM workload: whole steps on all host threads."""
     import oracle
@@ -262,7 +293,7 @@ def cpu_baseline_lstm(cfg, budget_s=15.0):
                       % (n, B, H, k_w, k_a)}
 
 
-SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "quantizer", "cpu"]
+SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "lm", "quantizer", "cpu"]
 
 
 def copy_probe(dev, nbytes=512 << 20, iters=10):
@@ -370,6 +401,15 @@ def main():
 
     if "gru" in sections:
         also["gru_b256_with_projection_steps_per_s"] = 1e3 / bench_gru(amq, dev, 100, 10)
+
+    if "lm" in sections:
+        # full language-model step at the paper's large shape: embedding lookup, LSTM 1024, output layer
+        # 42000 x 1024 with log-softmax, W2/A2
+        for b in (1, 64):
+            ms, ms_layer, ms_lsm = bench_lm(amq, dev, b, 300, 30)
+            also["lm_h1024_v42000_w2a2_b%d_steps_per_s" % b] = 1e3 / ms
+            also["lm_output_layer_42000x1024_b%d_us" % b] = ms_layer * 1e3
+            also["lm_log_softmax_42000_b%d_us" % b] = ms_lsm * 1e3
 
     if "quantizer" in sections:
         for k in (1, 2, 3, 4):

@@ -198,9 +198,9 @@ int amq_log_softmax(const float* Y, int64_t B, int64_t V, float* out, void* stre
 /*
  * Output layer of Eq. 6: log softmax(W_s h_t + b_s), W_s (V x H) row-wise k_w-bit, h_t quantized
  * on line to k_a bits (T cycles).  logprob [B][V] receives the logits first and is then normalised
- * in place.  workspace: at least amq_softmax_layer_workspace_bytes(H, B, k_a) bytes, 256-byte aligned.
+ * in place.  workspace: at least amq_softmax_layer_workspace_bytes(V, H, B, k_a) bytes, 256-byte aligned.
  */
-size_t amq_softmax_layer_workspace_bytes(int64_t H, int64_t B, int k_a);
+size_t amq_softmax_layer_workspace_bytes(int64_t V, int64_t H, int64_t B, int k_a);
 int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_w,
                       const float* bias, const float* h, int64_t B, int k_a, int T, float* logprob,
                       void* workspace, size_t workspace_bytes, void* stream);
@@ -210,9 +210,9 @@ int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int6
  * embedding (k_a planes: the table must be quantized with k = k_a), h_{t-1} quantized on line (k_a),
  * LSTM cell (h and c [B][H] are read and overwritten), h_t quantized again (k_as) and the output
  * layer W_s (V x H, k_ws-bit) with log-softmax -> logprob [B][V].
- *   workspace: at least amq_lm_workspace_bytes(E, H, B, k_a, k_as) bytes, 256-byte aligned.
+ *   workspace: at least amq_lm_workspace_bytes(E, H, V, B, k_a, k_as) bytes, 256-byte aligned.
  */
-size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t B, int k_a, int k_as);
+size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as);
 int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
                 const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
                 const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,

@@ -63,10 +63,10 @@ def lib():
                                    _sz, _p]
         L.amq_embedding_lookup.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p, _p, _p]
         L.amq_log_softmax.argtypes = [_p, _i64, _i64, _p, _p]
-        L.amq_softmax_layer_workspace_bytes.argtypes = [_i64, _i64, _int]
+        L.amq_softmax_layer_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.amq_softmax_layer_workspace_bytes.restype = _sz
         L.amq_softmax_layer.argtypes = [_p, _p, _i64, _i64, _int, _p, _p, _i64, _int, _int, _p, _p, _sz, _p]
-        L.amq_lm_workspace_bytes.argtypes, L.amq_lm_workspace_bytes.restype = [_i64, _i64, _i64, _int, _int], _sz
+        L.amq_lm_workspace_bytes.argtypes, L.amq_lm_workspace_bytes.restype = [_i64, _i64, _i64, _i64, _int, _int], _sz
         L.amq_lm_step.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         _lib = L
@@ -294,8 +294,8 @@ def log_softmax(Y, out=None):
     return out
 
 
-def softmax_layer_workspace(H, B, k_a, device):
-    nbytes = int(lib().amq_softmax_layer_workspace_bytes(H, B, k_a))
+def softmax_layer_workspace(V, H, B, k_a, device):
+    nbytes = int(lib().amq_softmax_layer_workspace_bytes(V, H, B, k_a))
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
@@ -304,7 +304,7 @@ def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T, ws=None, logprob=None):
     k_w, V, _ = Wsp.shape
     B = h.shape[0]
     if ws is None:
-        ws = softmax_layer_workspace(H, B, k_a, h.device)
+        ws = softmax_layer_workspace(V, H, B, k_a, h.device)
     if logprob is None:
         logprob = _empty((B, V), torch.float32, h)
     _check(lib().amq_softmax_layer(_dev(Wsp, torch.int32), _dev(alpha_s, torch.float32), V, H, k_w, _opt(bias),
@@ -313,8 +313,8 @@ def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T, ws=None, logprob=None):
     return logprob
 
 
-def lm_workspace(E, H, B, k_a, k_as, device):
-    nbytes = int(lib().amq_lm_workspace_bytes(E, H, B, k_a, k_as))
+def lm_workspace(E, H, V, B, k_a, k_as, device):
+    nbytes = int(lib().amq_lm_workspace_bytes(E, H, V, B, k_a, k_as))
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
@@ -327,7 +327,7 @@ def lm_step(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, b
     k_ws, V, _ = Wsp.shape
     B = ids.shape[0]
     if ws is None:
-        ws = lm_workspace(E, H, B, k_a, k_as, h.device)
+        ws = lm_workspace(E, H, V, B, k_a, k_as, h.device)
     if logprob is None:
         logprob = _empty((B, V), torch.float32, h)
     _check(lib().amq_lm_step(_dev(Ep, torch.int32), _dev(alpha_e, torch.float32), vocab, E,

@@ -75,13 +75,17 @@ amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64
   g.accumulate = accumulate;
   g.Y = Y;
   g.D = nullptr;
+  g.lse_part = nullptr;
+  g.lse_cap = 0;
   g.groups = 1;
   return g;
 }
 
 // Matrix-core product: fp4 kernel when the vectors fit one 1024-entry chunk, int8 kernel otherwise.
-hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, hipStream_t s) {
-  if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s);
+hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, hipStream_t s,
+                              int* lse_slots = nullptr) {
+  if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s, lse_slots);
+  if (lse_slots) *lse_slots = 0;
   return amq::launch_mfma(b, k_w, k_a, epi, s);
 }
 
@@ -95,6 +99,8 @@ amq::BmvArgs store_args(const amq::GemmArgs& g) {
   b.accumulate = g.accumulate;
   b.Y = g.Y;
   b.D = g.D;
+  b.lse_part = g.lse_part;
+  b.lse_cap = g.lse_cap;
   b.groups = g.groups;
   b.g_Wp = g.g_Wp; b.g_alpha = g.g_alpha; b.g_Xp = g.g_Xp; b.g_beta = g.g_beta; b.g_Y = g.g_Y;
   return b;
@@ -103,11 +109,14 @@ amq::BmvArgs store_args(const amq::GemmArgs& g) {
 // One quantized product.  Batch <= 16: weights-in-registers popcount kernel (memory-bound
 // regime).  Larger batches: the int8 matrix-core kernel (dense contraction).  The general
 // popcount kernel covers what is left (very long vectors at small batch, small-batch integer dots).
-int run_product(const amq::GemmArgs& g, hipStream_t s) {
+// lse_slots (nullable): receives the number of (max, sum) pairs per batch entry the kernel left
+// in g.lse_part, or 0 if the kernel that ran does not produce them.
+int run_product(const amq::GemmArgs& g, hipStream_t s, int* lse_slots = nullptr) {
+  if (lse_slots) *lse_slots = 0;
   if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch))
-    return hip_status(amq::launch_bmv(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s));
+    return hip_status(amq::launch_bmv(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s, lse_slots));
   if (g.groups == 1 && g.batch > amq::kBmvMaxBatch && amq::mfma_supported(g.batch))
-    return hip_status(launch_matrix_core(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s));
+    return hip_status(launch_matrix_core(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s, lse_slots));
   return hip_status(amq::launch_gemm(g, s));
 }
 
@@ -402,13 +411,16 @@ int amq_log_softmax(const float* Y, int64_t B, int64_t V, float* out, void* stre
   return hip_status(amq::launch_log_softmax(Y, B, V, out, static_cast<hipStream_t>(stream)));
 }
 
-// Workspace of the output layer: the quantized h_t.
+// Workspace of the output layer: the quantized h_t and the (max, sum of exponentials) pairs the
+// product kernel leaves for the log-softmax.
 struct SoftmaxWs {
   uint32_t* hp;
   float* beta;
+  float* lse_part;
+  int lse_cap;  // pairs per batch entry
   size_t total;
 };
-static SoftmaxWs carve_softmax(void* ws, int64_t H, int64_t B, int k_a) {
+static SoftmaxWs carve_softmax(void* ws, int64_t V, int64_t H, int64_t B, int k_a) {
   SoftmaxWs w;
   char* base = static_cast<char*>(ws);
   size_t off = 0;
@@ -416,13 +428,16 @@ static SoftmaxWs carve_softmax(void* ws, int64_t H, int64_t B, int k_a) {
   off += up256(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(H));
   w.beta = reinterpret_cast<float*>(base ? base + off : nullptr);
   off += up256(sizeof(float) * (size_t)B * k_a);
+  w.lse_part = reinterpret_cast<float*>(base ? base + off : nullptr);
+  w.lse_cap = (int)(V + 64 < amq::kLseMaxSlots ? V + 64 : amq::kLseMaxSlots);
+  off += up256(sizeof(float) * 2 * (size_t)B * w.lse_cap);
   w.total = off;
   return w;
 }
 
-size_t amq_softmax_layer_workspace_bytes(int64_t H, int64_t B, int k_a) {
-  if (H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
-  return carve_softmax(nullptr, H, B, k_a).total;
+size_t amq_softmax_layer_workspace_bytes(int64_t V, int64_t H, int64_t B, int k_a) {
+  if (V <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve_softmax(nullptr, V, H, B, k_a).total;
 }
 
 static int softmax_layer_launch(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_w,
@@ -435,8 +450,12 @@ static int softmax_layer_launch(const uint32_t* Wsp, const float* alpha_s, int64
   int st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
   amq::GemmArgs g = gemm_args(Wsp, alpha_s, V, H, k_w, w.hp, w.beta, B, k_a, bias, 0, logprob);
-  st = run_product(g, s);
+  g.lse_part = B <= 65535 ? w.lse_part : nullptr;
+  g.lse_cap = w.lse_cap;
+  int slots = 0;
+  st = run_product(g, s, &slots);
   if (st != AMQ_OK) return st;
+  if (slots > 0) return hip_status(amq::launch_log_softmax_finish(logprob, B, V, w.lse_part, slots, logprob, s));
   return hip_status(amq::launch_log_softmax(logprob, B, V, logprob, s));
 }
 
@@ -446,16 +465,16 @@ int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int6
   if (!Wsp || !alpha_s || !h || !logprob || !workspace) return AMQ_ERR_INVALID;
   if (!bits_ok(k_w) || !bits_ok(k_a) || T < 0 || V <= 0 || H <= 0 || B <= 0) return AMQ_ERR_INVALID;
   if (!aligned(Wsp, 16) || !aligned(workspace, 256)) return AMQ_ERR_INVALID;
-  if (workspace_bytes < carve_softmax(nullptr, H, B, k_a).total) return AMQ_ERR_INVALID;
+  if (workspace_bytes < carve_softmax(nullptr, V, H, B, k_a).total) return AMQ_ERR_INVALID;
   if (H > AMQ_MAX_QUANT_N || B > (1 << 24) || V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
-  SoftmaxWs w = carve_softmax(workspace, H, B, k_a);
+  SoftmaxWs w = carve_softmax(workspace, V, H, B, k_a);
   return softmax_layer_launch(Wsp, alpha_s, V, H, k_w, bias, h, B, k_a, T, logprob, w,
                               static_cast<hipStream_t>(stream));
 }
 
-size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t B, int k_a, int k_as) {
-  if (E <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
-  return carve(nullptr, E, H, B, k_a, 4, 1).total + carve_softmax(nullptr, H, B, k_as).total;
+size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
+  if (E <= 0 || H <= 0 || V <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
+  return carve(nullptr, E, H, B, k_a, 4, 1).total + carve_softmax(nullptr, V, H, B, k_as).total;
 }
 
 int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
@@ -467,7 +486,7 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
   if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
   const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
   const size_t need_step = sizes_ok ? carve(nullptr, E, H, B, k_a, 4, 1).total : 0;
-  const size_t need = sizes_ok ? need_step + carve_softmax(nullptr, H, B, k_as).total : 0;
+  const size_t need = sizes_ok ? need_step + carve_softmax(nullptr, V, H, B, k_as).total : 0;
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, ids, h, B, k_a, T, h, workspace, workspace_bytes,
                       need);
   if (st != AMQ_OK) return st;
@@ -475,7 +494,7 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
   if (V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
-  SoftmaxWs sw = carve_softmax(static_cast<char*>(workspace) + need_step, H, B, k_as);
+  SoftmaxWs sw = carve_softmax(static_cast<char*>(workspace) + need_step, V, H, B, k_as);
 
   // h_{t-1} quantized on line and x_t looked up in the quantized embedding, one launch
   amq::QuantArgs q{};

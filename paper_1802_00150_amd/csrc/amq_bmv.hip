@@ -35,7 +35,9 @@ __device__ __forceinline__ float group_sum(float v, int lg) {
   return v;
 }
 
-template <int KW, int KA, int NSEG, int NBLK, int EPI>
+// LSE (store mode only): also leave, per batch entry and wave, the (max, sum of exponentials) of
+// the outputs the wave produced, for a log-softmax over the rows that follows.
+template <int KW, int KA, int NSEG, int NBLK, int EPI, bool LSE = false>
 __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
   extern __shared__ uint4 xs[];
   const int lane = lane_id(), wv = wave_id();
@@ -116,6 +118,8 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
     if (first >= nrow) return;  // whole wave past the end (after the barrier)
   }
 
+  float* const lse_part = LSE ? a.lse_part : nullptr;  // read once, not per batch entry
+  const int lse_slots = a.lse_slots;
   for (int b = 0; b < batch; ++b) {
     // previous state / old output of this batch entry, requested before the popcount work
     float prev[NSEG];
@@ -159,11 +163,22 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
     }
 
     if constexpr (EPI == kEpiStore) {
+      float yv[NSEG];
 #pragma unroll
       for (int s = 0; s < NSEG; ++s) {
-        const float v = group_sum(part[0][s], lg);
-        if (sub == 0 && ok[s]) {
-          a.Y[grp * a.g_Y + (long long)b * a.m + row[s]] = v + bs0[s] + prev[s];
+        yv[s] = group_sum(part[0][s], lg) + bs0[s] + prev[s];
+        if (sub == 0 && ok[s]) a.Y[grp * a.g_Y + (long long)b * a.m + row[s]] = yv[s];
+      }
+      if constexpr (LSE) {  // (max, sum of exponentials) over this wave's outputs
+        float pm = kLseLow, ps = 0.0f;
+#pragma unroll
+        for (int s = 0; s < NSEG; ++s)
+          if (sub == 0 && ok[s]) lse_merge(pm, ps, yv[s], 1.0f);
+        lse_wave_merge(pm, ps);
+        if (lane == 0) {
+          float* dst = lse_part + ((long long)b * lse_slots + wave_global) * 2;
+          dst[0] = pm;
+          dst[1] = ps;
         }
       }
     } else if constexpr (EPI == kEpiLstm) {
@@ -202,15 +217,25 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
 }
 
 template <int KW, int KA, int NSEG, int NBLK, int EPI>
-hipError_t launch_one(const BmvArgs& a, long long waves, size_t lds, hipStream_t s) {
+hipError_t launch_one(BmvArgs a, long long waves, size_t lds, hipStream_t s, int* lse_slots) {
   const long long blocks = (waves + 3) / 4;
-  hipLaunchKernelGGL((bmv_kernel<KW, KA, NSEG, NBLK, EPI>), dim3((unsigned)blocks, (unsigned)a.groups),
-                     dim3(256), lds, s, a);
+  const dim3 grid((unsigned)blocks, (unsigned)a.groups);
+  // every wave that owns at least one row fills one slot per batch entry
+  if (a.lse_part && (waves > kLseMaxSlots || waves > a.lse_cap || a.groups != 1)) a.lse_part = nullptr;
+  a.lse_slots = (int)waves;
+  if (lse_slots) *lse_slots = a.lse_part ? (int)waves : 0;
+  if constexpr (EPI == kEpiStore) {
+    if (a.lse_part) {
+      hipLaunchKernelGGL((bmv_kernel<KW, KA, NSEG, NBLK, EPI, true>), grid, dim3(256), lds, s, a);
+      return hipGetLastError();
+    }
+  }
+  hipLaunchKernelGGL((bmv_kernel<KW, KA, NSEG, NBLK, EPI, false>), grid, dim3(256), lds, s, a);
   return hipGetLastError();
 }
 
 template <int KW, int KA>
-hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s) {
+hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s, int* lse_slots) {
   const int R = 64 >> a.lg;
   size_t lds = 0;
   const int nblk = (epi == kEpiStore) ? 1 : 2;
@@ -220,22 +245,22 @@ hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s) {
       // four row groups per wave (all loads in flight) when there are enough rows to fill the
       // chip that way; one row group per wave for small products, where parallelism matters more
       const long long waves4 = (a.m + 4LL * R - 1) / (4LL * R);
-      if (waves4 * a.groups >= 2048) return launch_one<KW, KA, 4, 1, kEpiStore>(a, waves4, lds, s);
-      return launch_one<KW, KA, 1, 1, kEpiStore>(a, (a.m + R - 1) / R, lds, s);
+      if (waves4 * a.groups >= 2048) return launch_one<KW, KA, 4, 1, kEpiStore>(a, waves4, lds, s, lse_slots);
+      return launch_one<KW, KA, 1, 1, kEpiStore>(a, (a.m + R - 1) / R, lds, s, lse_slots);
     }
-    case kEpiLstm: return launch_one<KW, KA, 4, 2, kEpiLstm>(a, (a.H + R - 1) / R, lds, s);
-    case kEpiGru: return launch_one<KW, KA, 3, 2, kEpiGru>(a, (a.H + R - 1) / R, lds, s);
+    case kEpiLstm: return launch_one<KW, KA, 4, 2, kEpiLstm>(a, (a.H + R - 1) / R, lds, s, nullptr);
+    case kEpiGru: return launch_one<KW, KA, 3, 2, kEpiGru>(a, (a.H + R - 1) / R, lds, s, nullptr);
   }
   return hipErrorInvalidValue;
 }
 
 template <int KW>
-hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s) {
+hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s, int* lse_slots) {
   switch (k_a) {
-    case 1: return launch_epi<KW, 1>(a, epi, s);
-    case 2: return launch_epi<KW, 2>(a, epi, s);
-    case 3: return launch_epi<KW, 3>(a, epi, s);
-    case 4: return launch_epi<KW, 4>(a, epi, s);
+    case 1: return launch_epi<KW, 1>(a, epi, s, lse_slots);
+    case 2: return launch_epi<KW, 2>(a, epi, s, lse_slots);
+    case 3: return launch_epi<KW, 3>(a, epi, s, lse_slots);
+    case 4: return launch_epi<KW, 4>(a, epi, s, lse_slots);
   }
   return hipErrorInvalidValue;
 }
@@ -248,7 +273,9 @@ bool bmv_supported(int n0, int n1, int k_a, long long batch) {
   return (size_t)k_a * batch * (c0 + c1) * 16 <= 48 * 1024;
 }
 
-hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s) {
+hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots) {
+  if (lse_slots) *lse_slots = 0;
+  if (epi != kEpiStore) a.lse_part = nullptr;
   int nmax = a.blk[0].n;
   if (epi != kEpiStore && a.blk[1].n > nmax) nmax = a.blk[1].n;
   const int cpr = (nmax + 127) / 128;
@@ -256,10 +283,10 @@ hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s) {
   while ((1 << lg) < cpr) ++lg;
   a.lg = lg;
   switch (k_w) {
-    case 1: return launch_ka<1>(a, k_a, epi, s);
-    case 2: return launch_ka<2>(a, k_a, epi, s);
-    case 3: return launch_ka<3>(a, k_a, epi, s);
-    case 4: return launch_ka<4>(a, k_a, epi, s);
+    case 1: return launch_ka<1>(a, k_a, epi, s, lse_slots);
+    case 2: return launch_ka<2>(a, k_a, epi, s, lse_slots);
+    case 3: return launch_ka<3>(a, k_a, epi, s, lse_slots);
+    case 4: return launch_ka<4>(a, k_a, epi, s, lse_slots);
   }
   return hipErrorInvalidValue;
 }

@@ -52,4 +52,21 @@ __device__ __forceinline__ float tanhf_dev(float a) {
   return copysignf((1.0f - e) * __builtin_amdgcn_rcpf(1.0f + e), a);
 }
 
+// Running log-sum-exp state: (m, s) stands for s * exp(m).  kLseLow is the neutral maximum
+// (finite, so that differences never produce NaN).
+constexpr float kLseLow = -3.0e38f;
+__device__ __forceinline__ void lse_merge(float& m, float& s, float m2, float s2) {
+  const float mn = fmaxf(m, m2);
+  s = s * __expf(m - mn) + s2 * __expf(m2 - mn);
+  m = mn;
+}
+// Merge over the 64 lanes; every lane ends with the total.
+__device__ __forceinline__ void lse_wave_merge(float& m, float& s) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(m, o, kWave), s2 = __shfl_xor(s, o, kWave);
+    lse_merge(m, s, m2, s2);
+  }
+}
+
 }  // namespace amq

@@ -62,6 +62,8 @@ struct GemmArgs {
   int accumulate;
   float* Y;            // [batch][m] or null
   int32_t* D;          // [batch][m][k_w][k_a] or null (test hook)
+  float* lse_part;     // null, or room for lse_cap (max, sum-of-exponentials) pairs per batch entry
+  int lse_cap;
   // grouped batch-1 products: strides in elements between consecutive groups (0 when groups == 1)
   int groups;
   long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
@@ -96,21 +98,30 @@ struct BmvArgs {
   float* h_out;
   float* c_out;
   float* hs_out;        // LSTM, nullable
+  float* lse_part;      // store mode, nullable: per batch entry and slot a (max, sum exp(y - max)) pair over
+                        // the outputs one wave produced, [batch][lse_slots][2]
+  int lse_slots;        // filled by the launcher: slots per batch entry
+  int lse_cap;          // slots per batch entry the buffer has room for
   int lg;               // filled by launch_bmv
   int groups;           // store mode: independent products in one launch (1 otherwise)
   long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
 };
 
+// Most (max, sum) slots per batch entry worth merging afterwards; a launch that would need more
+// (or more than the buffer's lse_cap) leaves lse_part untouched and reports 0 slots.
+constexpr int kLseMaxSlots = 8192;
+
 // true if the register-resident kernel can take these vector lengths / batch
 bool bmv_supported(int n0, int n1, int k_a, long long batch);
-hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s);
+// lse_slots (nullable) receives the number of slots written per batch entry when a.lse_part is set
+hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 
 // ---- batched products on the matrix cores (int8 MFMA on expanded codes), same epilogues ------
 bool mfma_supported(long long batch);
 hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 // fp4 matrix-core kernel for vectors of at most 1024 entries (the fast path)
 bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
-hipError_t launch_mfma4(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
+hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 
 // ---- whole batch-1 LSTM sequences in one launch (small models: weights resident in one CU) ---
 struct Seq1Args {
@@ -135,6 +146,9 @@ hipError_t launch_lstm_seq1(Seq1Args a, int k_w, int k_a, hipStream_t s);
 // ---- output layer -----------------------------------------------------------------------
 // out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])); out may alias Y.
 hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* out, hipStream_t s);
+// The same when a product kernel has already reduced its outputs to `slots` (max, sum) pairs per row.
+hipError_t launch_log_softmax_finish(const float* Y, long long B, long long V, const float* part, int slots,
+                                     float* out, hipStream_t s);
 
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU

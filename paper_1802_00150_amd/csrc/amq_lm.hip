@@ -3,6 +3,9 @@
 // lane-interleaved so that every load is a coalesced 256-byte wave access), the maximum and the
 // sum of exponentials are reduced across the workgroup, and the shifted row is written back.
 // Rows longer than 64 * 1024 values take the re-reading variant (three passes, same arithmetic).
+// When the product kernel that wrote the logits has already reduced them to per-wave
+// (max, sum of exponentials) pairs, only the finishing kernel below runs: it spreads a row over
+// many workgroups, which a single workgroup per row (bound by one CU's load path) cannot.
 //
 // Precision: binary32 throughout; exp through v_exp_f32, the sum of V <= 2^16 positive terms as
 // per-lane partial sums + a tree, log through logf.  Absolute error of a result is a few 1e-6.
@@ -84,6 +87,71 @@ __global__ __launch_bounds__(kLsmThreads) void log_softmax_kernel(const float* Y
   }
 }
 
+// Second half of the fused form: the product kernel has left, per row, `slots` pairs
+// (max, sum of exp(y - max)) over disjoint parts of the row.  Every workgroup merges the pairs
+// of its row (a few KB, from cache) and shifts its own stretch of kFinChunk outputs.
+constexpr int kFinThreads = 256;
+constexpr int kFinPer = 16;
+constexpr int kFinChunk = kFinThreads * kFinPer;
+constexpr int kFinRounds = kLseMaxSlots / (8 * kFinThreads);
+static_assert(kFinRounds * 8 * kFinThreads == kLseMaxSlots, "slot rounds must cover the maximum exactly");
+
+__global__ __launch_bounds__(kFinThreads) void log_softmax_finish_kernel(const float* Y, long long V,
+                                                                        const float* part, int slots, float* out) {
+  __shared__ float shm[kFinThreads / kWave], shs[kFinThreads / kWave];
+  const int t = threadIdx.x;
+  const long long row = blockIdx.y;
+  const float* y = Y + row * V;
+  float* o = out + row * V;
+  const long long e0 = (long long)blockIdx.x * kFinChunk + t;
+  float v[kFinPer];
+#pragma unroll
+  for (int j = 0; j < kFinPer; ++j) {
+    const long long e = e0 + (long long)j * kFinThreads;
+    v[j] = e < V ? y[e] : 0.0f;
+  }
+  const float2* pr = reinterpret_cast<const float2*>(part) + row * slots;
+  // every pair of the row is requested before the first is used (slots <= kLseMaxSlots, so at
+  // most kFinRounds * 8 per thread; rounds past the end are skipped uniformly)
+  float2 q[kFinRounds][8];
+#pragma unroll
+  for (int r = 0; r < kFinRounds; ++r) {
+    if (r * 8 * kFinThreads < slots) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int i = (r * 8 + j) * kFinThreads + t;
+        q[r][j] = i < slots ? pr[i] : make_float2(kLseLow, 0.0f);
+      }
+    }
+  }
+  float m = kLseLow, s = 0.0f;
+#pragma unroll
+  for (int r = 0; r < kFinRounds; ++r) {
+    if (r * 8 * kFinThreads < slots) {
+      float mx = m;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) mx = fmaxf(mx, q[r][j].x);
+      float acc = s * __expf(m - mx);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc = fmaf(q[r][j].y, __expf(q[r][j].x - mx), acc);
+      m = mx;
+      s = acc;
+    }
+  }
+  lse_wave_merge(m, s);
+  if (lane_id() == 0) { shm[wave_id()] = m; shs[wave_id()] = s; }
+  __syncthreads();
+  m = shm[0]; s = shs[0];
+#pragma unroll
+  for (int i = 1; i < kFinThreads / kWave; ++i) lse_merge(m, s, shm[i], shs[i]);
+  const float lse = m + logf(s);
+#pragma unroll
+  for (int j = 0; j < kFinPer; ++j) {
+    const long long e = e0 + (long long)j * kFinThreads;
+    if (e < V) o[e] = v[j] - lse;
+  }
+}
+
 template <int NV>
 void launch_lsm(const float* Y, long long B, long long V, float* out, hipStream_t s) {
   hipLaunchKernelGGL((log_softmax_kernel<NV>), dim3((unsigned)B), dim3(kLsmThreads), 0, s, Y, V, out);
@@ -99,6 +167,15 @@ hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* o
   else if (nv <= 44) launch_lsm<44>(Y, B, V, out, s);
   else if (nv <= 64) launch_lsm<64>(Y, B, V, out, s);
   else launch_lsm<0>(Y, B, V, out, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_log_softmax_finish(const float* Y, long long B, long long V, const float* part, int slots,
+                                     float* out, hipStream_t s) {
+  const long long chunks = (V + kFinChunk - 1) / kFinChunk;
+  if (B > 65535 || chunks > 0x7fffffffLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(log_softmax_finish_kernel, dim3((unsigned)chunks, (unsigned)B), dim3(kFinThreads), 0, s, Y, V,
+                     part, slots, out);
   return hipGetLastError();
 }
 

@@ -135,6 +135,8 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
 
   int rb_end = (blockIdx.x + 1) * rb_per_wg;
   if (rb_end > rowblocks) rb_end = rowblocks;
+  float lse_m = kLseLow, lse_s = 0.0f;  // store mode: running (max, sum exp) of this lane's outputs
+  float* const lse_part = (EPI == kEpiStore) ? a.lse_part : nullptr;
   for (int rb = blockIdx.x * rb_per_wg + wv; rb < rb_end; rb += NWV) {
     // A-operand view: lane = (tile row l16, k-block l4)
     int wrow;
@@ -326,17 +328,29 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     // (no early exit for padded batch columns: every lane stays active through the loop, the
     // stores below are predicated instead)
     if constexpr (EPI == kEpiStore) {
+      float yv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) yv[r] = ysum[0][r] + bias0[r] + yold[r];
       if (a.Y && bok) {
         float* yp = a.Y + (long long)b * m + crow[0];
         if ((m & 3) == 0 && cok[3]) {
           // the four rows of this lane are consecutive in Y[b][.]: one aligned 16-byte store
-          *reinterpret_cast<float4*>(yp) = make_float4(ysum[0][0] + bias0[0] + yold[0], ysum[0][1] + bias0[1] + yold[1],
-                                                       ysum[0][2] + bias0[2] + yold[2], ysum[0][3] + bias0[3] + yold[3]);
+          *reinterpret_cast<float4*>(yp) = make_float4(yv[0], yv[1], yv[2], yv[3]);
         } else {
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (cok[r]) yp[r] = ysum[0][r] + bias0[r] + yold[r];
+            if (cok[r]) yp[r] = yv[r];
         }
+      }
+      if (lse_part) {  // uniform: fold this row block's outputs into the running (max, sum)
+        float mx = lse_m;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, cok[r] ? yv[r] : kLseLow);
+        float sm = lse_s * __expf(lse_m - mx);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm += cok[r] ? __expf(yv[r] - mx) : 0.0f;
+        lse_m = mx;
+        lse_s = sm;
       }
     } else if constexpr (EPI == kEpiLstm) {
       if (bok && cok[0]) {
@@ -361,10 +375,26 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       }
     }
   }
+  if constexpr (EPI == kEpiStore) {
+    if (lse_part) {
+      // one slot per wave and batch column: merge the four row quads (lanes 16 apart); a wave
+      // that had no row block writes the neutral pair
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float m2 = __shfl_xor(lse_m, o, kWave), s2 = __shfl_xor(lse_s, o, kWave);
+        lse_merge(lse_m, lse_s, m2, s2);
+      }
+      if (l4 == 0 && bok) {
+        float* dst = lse_part + ((long long)b * a.lse_slots + blockIdx.x * NWV + wv) * 2;
+        dst[0] = lse_m;
+        dst[1] = lse_s;
+      }
+    }
+  }
 }
 
 template <int KW, int KA, int EPI, int NWV>
-hipError_t launch_one(const BmvArgs& a, int rowblocks, int rb_per_wg, hipStream_t s) {
+hipError_t launch_one(BmvArgs a, int rowblocks, int rb_per_wg, hipStream_t s, int* lse_slots) {
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
   const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + sizeof(int) * NBLK * KA * kTileB;
   static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
@@ -375,12 +405,16 @@ hipError_t launch_one(const BmvArgs& a, int rowblocks, int rb_per_wg, hipStream_
     configured = true;
   }
   dim3 grid((unsigned)((rowblocks + rb_per_wg - 1) / rb_per_wg), (unsigned)((a.batch + kTileB - 1) / kTileB));
+  const long long slots = (long long)grid.x * NWV;  // one per wave of a batch tile's workgroups
+  if (EPI != kEpiStore || slots > kLseMaxSlots || slots > a.lse_cap) a.lse_part = nullptr;
+  a.lse_slots = (int)slots;
+  if (lse_slots) *lse_slots = a.lse_part ? (int)slots : 0;
   hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
   return hipGetLastError();
 }
 
 template <int KW, int KA, int EPI>
-hipError_t launch_mode(const BmvArgs& a, hipStream_t s) {
+hipError_t launch_mode(const BmvArgs& a, hipStream_t s, int* lse_slots) {
   const int rowblocks = (int)((EPI == kEpiStore) ? (a.m + 15) / 16 : (a.H + 3) / 4);
   const int btiles = (a.batch + kTileB - 1) / kTileB;
   // about two workgroups per CU; each expands its activation tile once and then walks row blocks
@@ -388,27 +422,27 @@ hipError_t launch_mode(const BmvArgs& a, hipStream_t s) {
   int per = (rowblocks + splits - 1) / splits;
   if (per < 4) per = 4;
   // 8 waves (two per SIMD) when there is work for them and 256 registers per wave suffice
-  if (per >= 16 && KW * KA <= (EPI == kEpiStore ? 9 : 4)) return launch_one<KW, KA, EPI, 8>(a, rowblocks, per, s);
-  return launch_one<KW, KA, EPI, 4>(a, rowblocks, per, s);
+  if (per >= 16 && KW * KA <= (EPI == kEpiStore ? 9 : 4)) return launch_one<KW, KA, EPI, 8>(a, rowblocks, per, s, lse_slots);
+  return launch_one<KW, KA, EPI, 4>(a, rowblocks, per, s, lse_slots);
 }
 
 template <int KW, int KA>
-hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s) {
+hipError_t launch_epi(const BmvArgs& a, int epi, hipStream_t s, int* lse_slots) {
   switch (epi) {
-    case kEpiStore: return launch_mode<KW, KA, kEpiStore>(a, s);
-    case kEpiLstm: return launch_mode<KW, KA, kEpiLstm>(a, s);
-    case kEpiGru: return launch_mode<KW, KA, kEpiGru>(a, s);
+    case kEpiStore: return launch_mode<KW, KA, kEpiStore>(a, s, lse_slots);
+    case kEpiLstm: return launch_mode<KW, KA, kEpiLstm>(a, s, lse_slots);
+    case kEpiGru: return launch_mode<KW, KA, kEpiGru>(a, s, lse_slots);
   }
   return hipErrorInvalidValue;
 }
 
 template <int KW>
-hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s) {
+hipError_t launch_ka(const BmvArgs& a, int k_a, int epi, hipStream_t s, int* lse_slots) {
   switch (k_a) {
-    case 1: return launch_epi<KW, 1>(a, epi, s);
-    case 2: return launch_epi<KW, 2>(a, epi, s);
-    case 3: return launch_epi<KW, 3>(a, epi, s);
-    case 4: return launch_epi<KW, 4>(a, epi, s);
+    case 1: return launch_epi<KW, 1>(a, epi, s, lse_slots);
+    case 2: return launch_epi<KW, 2>(a, epi, s, lse_slots);
+    case 3: return launch_epi<KW, 3>(a, epi, s, lse_slots);
+    case 4: return launch_epi<KW, 4>(a, epi, s, lse_slots);
   }
   return hipErrorInvalidValue;
 }
@@ -426,12 +460,14 @@ bool mfma4_supported(const BmvArgs& a, int k_w, int epi) {
   return true;
 }
 
-hipError_t launch_mfma4(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s) {
+hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots) {
+  if (lse_slots) *lse_slots = 0;
+  if (epi != kEpiStore) a.lse_part = nullptr;
   switch (k_w) {
-    case 1: return launch_ka<1>(a, k_a, epi, s);
-    case 2: return launch_ka<2>(a, k_a, epi, s);
-    case 3: return launch_ka<3>(a, k_a, epi, s);
-    case 4: return launch_ka<4>(a, k_a, epi, s);
+    case 1: return launch_ka<1>(a, k_a, epi, s, lse_slots);
+    case 2: return launch_ka<2>(a, k_a, epi, s, lse_slots);
+    case 3: return launch_ka<3>(a, k_a, epi, s, lse_slots);
+    case 4: return launch_ka<4>(a, k_a, epi, s, lse_slots);
   }
   return hipErrorInvalidValue;
 }

@@ -80,14 +80,14 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_log_softmax(p, 0, 8, p, None) == INVALID
     assert L.amq_log_softmax(null, 1, 8, p, None) == INVALID
     assert L.amq_log_softmax(p, 1, (1 << 31) + 1, p, None) == UNSUPPORTED
-    need_s = L.amq_softmax_layer_workspace_bytes(8, 1, 2)
+    need_s = L.amq_softmax_layer_workspace_bytes(16, 8, 1, 2)
     assert need_s > 0 and need_s % 256 == 0
-    assert L.amq_softmax_layer_workspace_bytes(8, 1, 0) == 0
+    assert L.amq_softmax_layer_workspace_bytes(16, 8, 1, 0) == 0
     assert L.amq_softmax_layer(p, p, 16, 8, 2, None, p, 1, 2, 2, p, ws, need_s - 1, None) == INVALID
     assert L.amq_softmax_layer(p, p, 16, 8, 2, None, p, 1, 2, -1, p, ws, need_s, None) == INVALID
     assert L.amq_softmax_layer(p, p, 16, 8, 2, None, null, 1, 2, 2, p, ws, need_s, None) == INVALID
-    need_l = L.amq_lm_workspace_bytes(8, 8, 1, 2, 3)
-    assert need_l == need + L.amq_softmax_layer_workspace_bytes(8, 1, 3)
+    need_l = L.amq_lm_workspace_bytes(8, 8, 16, 1, 2, 3)
+    assert need_l == need + L.amq_softmax_layer_workspace_bytes(16, 8, 1, 3)
     lm = lambda **kw: L.amq_lm_step(p, p, kw.get("vocab", 10), 8, p, p, p, p, 8, 2, None, p, p, 16, kw.get("k_ws", 2),
                                     None, kw.get("ids", p), p, p, 1, 2, kw.get("k_as", 3), 2, p, ws,
                                     kw.get("bytes", need_l), None)
