@@ -20,6 +20,8 @@
 // 8 * (l / 16) .. + 7).  In the cell modes the 16 tile rows are 4 hidden units x 4 gates, so
 // that in the 16x16 C layout (lane: column l % 16, rows 4 * (l / 16) + 0..3) one lane holds all
 // gates of one unit for one batch entry and the LSTM / GRU cell is applied in registers.
+#include <type_traits>
+
 #include "amq_device.h"
 #include "amq_launch.h"
 
@@ -53,8 +55,9 @@ __device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
   return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
 }
 
-template <int KW, int KA, int EPI, int NWV>
+template <int KW, int KA, int EPI, int NWV, bool SPLIT = false>
 __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_wg, int rowblocks) {
+  static_assert(!SPLIT || (EPI != kEpiStore && NWV % 2 == 0), "SPLIT pairs the waves over the two operand blocks");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
   constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
@@ -65,7 +68,8 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   unsigned char* btile = smem;
   int* pops = reinterpret_cast<int*>(smem + NBLK * kTileBytes);  // [NBLK][KA][kTileB]
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform to the compiler
   const int l16 = lane & 15, l4 = lane >> 4;
   const int b0 = blockIdx.y * kTileB;
   const int batch = a.batch;
@@ -80,6 +84,107 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     nlen[k] = a.blk[k].n;
     wq[k] = (nlen[k] + 127) >> 7;  // 16-byte groups per row
   }
+
+  const int b = b0 + l16;
+  const bool bok = b < batch;
+  const int bc = bok ? b : batch - 1;
+  const int rb_first = blockIdx.x * rb_per_wg;
+  int rb_end = rb_first + rb_per_wg;
+  if (rb_end > rowblocks) rb_end = rowblocks;
+
+  // SPLIT (cell modes): the two operand blocks of a row block go to two waves (kb = 0: x block and
+  // the cell, kb = 1: h block), which halves the dependent work per wave when there are too few
+  // row blocks to give every SIMD more than one wave anyway.  The h-block sums cross through LDS.
+  constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;  // row blocks a workgroup has in flight
+  const int wr = SPLIT ? (wv >> 1) : wv;
+  const int kb = SPLIT ? (wv & 1) : 0;
+  float4* xch = reinterpret_cast<float4*>(smem + NBLK * kTileBytes + 16 * ((NBLK * KA * kTileB * 4 + 15) / 16));
+
+  // A-operand view of row block rb: lane = (tile row l16, k-block l4)
+  auto a_row = [&](int rb, bool& wok) -> int {
+    int wrow;
+    if constexpr (EPI == kEpiStore) {
+      wrow = rb * 16 + l16;
+      wok = wrow < m;
+    } else {
+      const int unit = rb * 4 + (l16 >> 2);
+      const int gate = l16 & 3;
+      wok = unit < H && gate < NG;
+      wrow = gate * H + unit;
+    }
+    return wok ? wrow : 0;
+  };
+  // packed weight words of one operand block of a row block, straight into the operand layout
+  auto load_a = [&](auto kc, int rb, uint4 (&araw)[KW][2]) {
+    constexpr int k = decltype(kc)::value;
+    bool wok;
+    const int wrow = a_row(rb, wok);
+    const int base = wrow * wq[k];
+    const int plane = m * wq[k];
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int v = 0; v < 2; ++v) {
+        const int g = 2 * l4 + v;
+        const uint4 t4 = Wp4[k][base + i * plane + (g < wq[k] ? g : 0)];
+        araw[i][v] = (wok && g < wq[k]) ? t4 : make_uint4(0, 0, 0, 0);
+      }
+  };
+  // C view of row block rb: rows 4 * l4 + r
+  auto c_rows = [&](int rb, int (&crow)[4], bool (&cok)[4]) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if constexpr (EPI == kEpiStore) {
+        crow[r] = rb * 16 + 4 * l4 + r;
+        cok[r] = crow[r] < m;
+      } else {
+        const int unit = rb * 4 + l4;
+        cok[r] = unit < H && r < NG;
+        crow[r] = r * H + unit;
+      }
+      if (!cok[r]) crow[r] = 0;
+    }
+  };
+  auto load_alpha = [&](auto kc, const int (&crow)[4], float (&alr)[4][KW]) {
+    constexpr int k = decltype(kc)::value;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < KW; ++i) alr[r][i] = alpha[k][crow[r] * KW + i];
+  };
+  using K0 = std::integral_constant<int, 0>;
+  using K1 = std::integral_constant<int, NBLK - 1>;
+
+  const int iters = (rb_end - rb_first + NSLOT - 1) / NSLOT;  // SPLIT: the same trip count for every wave
+
+  // SPLIT: everything a wave's row block needs from memory, requested at the top of the pass
+  // (requesting it before the activation tile is staged was measured slower)
+  struct Ahead {
+    uint4 araw[KW][2];
+    float alr[4][KW];
+    int crow[4];
+    bool cok[4];
+    float bias0[4], bias1[4], prev;
+  } nx{};
+  auto fetch_rowblock = [&](int rb) {
+    if (rb >= rb_end) return;
+    c_rows(rb, nx.crow, nx.cok);
+    if (kb == 0) {
+      load_a(K0{}, rb, nx.araw);
+      load_alpha(K0{}, nx.crow, nx.alr);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        nx.bias0[r] = a.bias0 ? a.bias0[nx.crow[r]] : 0.0f;
+        nx.bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[nx.crow[r]] : 0.0f;
+      }
+      nx.prev = 0.0f;
+      if constexpr (EPI == kEpiLstm) nx.prev = a.c_prev[bc * H + nx.crow[0]];
+      if constexpr (EPI == kEpiGru) nx.prev = a.h_prev[bc * H + nx.crow[0]];
+    } else {
+      load_a(K1{}, rb, nx.araw);
+      load_alpha(K1{}, nx.crow, nx.alr);
+    }
+  };
 
   // ---- prologue: packed activation words of every operand block, 16 bytes per thread, coalesced
   uint4 xw[NBLK][kIter];
@@ -120,9 +225,6 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   }
   __syncthreads();
 
-  const int b = b0 + l16;
-  const bool bok = b < batch;
-  const int bc = bok ? b : batch - 1;
   float btv[NBLK][KA];
   float cx[NBLK][KA];  // n - 2 * popc(activation plane): the column-only part of the dot product
 #pragma unroll
@@ -133,196 +235,187 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       cx[k][j] = (float)(nlen[k] - 2 * pops[(k * KA + j) * kTileB + l16]);
     }
 
-  int rb_end = (blockIdx.x + 1) * rb_per_wg;
-  if (rb_end > rowblocks) rb_end = rowblocks;
   float lse_m = kLseLow, lse_s = 0.0f;  // store mode: running (max, sum exp) of this lane's outputs
   float* const lse_part = (EPI == kEpiStore) ? a.lse_part : nullptr;
-  for (int rb = blockIdx.x * rb_per_wg + wv; rb < rb_end; rb += NWV) {
-    // A-operand view: lane = (tile row l16, k-block l4)
-    int wrow;
-    bool wok;
-    if constexpr (EPI == kEpiStore) {
-      wrow = rb * 16 + l16;
-      wok = wrow < m;
-    } else {
-      const int unit = rb * 4 + (l16 >> 2);
-      const int gate = l16 & 3;
-      wok = unit < H && gate < NG;
-      wrow = gate * H + unit;
-    }
-    if (!wok) wrow = 0;
-    uint4 araw[NBLK][KW][2];
+
+  // one operand block of one row block: matrix-core contraction and coefficient epilogue -> ys[r]
+  auto run_block = [&](auto kc, const uint4 (&araw)[KW][2], const float (&alr)[4][KW], const int (&crow)[4],
+                       const bool (&cok)[4], float (&ys)[4]) {
+    constexpr int k = decltype(kc)::value;
+    // popcount of every weight row plane: this lane's 8 words, then the four k-blocks of the
+    // row (lanes 16 apart), then fetched for the rows of the C view
+    float pw2[KW][4];
 #pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-      const int base = wrow * wq[k];
-      const int plane = m * wq[k];
+    for (int i = 0; i < KW; ++i) {
+      int pc = 0;
+#pragma unroll
+      for (int v = 0; v < 2; ++v)
+        pc += __popc(araw[i][v].x) + __popc(araw[i][v].y) + __popc(araw[i][v].z) + __popc(araw[i][v].w);
+      pc += __shfl_xor(pc, 16, kWave);
+      pc += __shfl_xor(pc, 32, kWave);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pw2[i][r] = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
+    }
+
+    v4f acc[KW][KA];
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int j = 0; j < KA; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+    const unsigned char* tile = btile + k * kTileBytes + l16 * 64 + l4 * 16;
+    uint4 bop[KA], bnx[KA], aop[KW], anx[KW];
+#pragma unroll
+    for (int j = 0; j < KA; ++j) bop[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes);
+#pragma unroll
+    for (int i = 0; i < KW; ++i) aop[i] = expand4(word_of(araw[i], 0));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < kSteps; ++t) {
+      if (t + 1 < kSteps) {
+#pragma unroll
+        for (int j = 0; j < KA; ++j)
+          bnx[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes + (t + 1) * kTileB * 64);
+#pragma unroll
+        for (int i = 0; i < KW; ++i) anx[i] = expand4(word_of(araw[i], t + 1));
+      }
 #pragma unroll
       for (int i = 0; i < KW; ++i)
 #pragma unroll
-        for (int v = 0; v < 2; ++v) {
-          const int g = 2 * l4 + v;
-          const uint4 t4 = Wp4[k][base + i * plane + (g < wq[k] ? g : 0)];
-          araw[k][i][v] = (wok && g < wq[k]) ? t4 : make_uint4(0, 0, 0, 0);
-        }
-    }
-    // C view: rows 4 * l4 + r.  Everything the epilogue reads from memory is requested now.
-    int crow[4];
-    bool cok[4];
+        for (int j = 0; j < KA; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(aop[i]), as_operand(bop[j]), acc[i][j],
+                                                                       4, 4, 0, kScaleOne, 0, kScaleOne);
+      // issue order inside a step: the LDS reads of the next step first, then every MFMA
+      // followed by up to three of the VALU instructions that expand the next step's weights
+      __builtin_amdgcn_sched_group_barrier(0x100, KA, 0);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      if constexpr (EPI == kEpiStore) {
-        crow[r] = rb * 16 + 4 * l4 + r;
-        cok[r] = crow[r] < m;
-      } else {
-        const int unit = rb * 4 + l4;
-        cok[r] = unit < H && r < NG;
-        crow[r] = r * H + unit;
+      for (int g = 0; g < KW * KA; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
       }
-      if (!cok[r]) crow[r] = 0;
-    }
-    float alr[NBLK][4][KW];
-#pragma unroll
-    for (int k = 0; k < NBLK; ++k)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int i = 0; i < KW; ++i) alr[k][r][i] = alpha[k][crow[r] * KW + i];
-    float bias0[4], bias1[4], yold[4], prev = 0.0f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      bias0[r] = a.bias0 ? a.bias0[crow[r]] : 0.0f;
-      bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[crow[r]] : 0.0f;
-      yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
-    }
-    if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
-    if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
-
-    float ysum[NBLK][4];
-#pragma unroll
-    for (int k = 0; k < NBLK; ++k) {
-      // popcount of every weight row plane: this lane's 8 words, then the four k-blocks of the
-      // row (lanes 16 apart), then fetched for the rows of the C view
-      float pw2[KW][4];
-#pragma unroll
-      for (int i = 0; i < KW; ++i) {
-        int pc = 0;
-#pragma unroll
-        for (int v = 0; v < 2; ++v)
-          pc += __popc(araw[k][i][v].x) + __popc(araw[k][i][v].y) + __popc(araw[k][i][v].z) + __popc(araw[k][i][v].w);
-        pc += __shfl_xor(pc, 16, kWave);
-        pc += __shfl_xor(pc, 32, kWave);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pw2[i][r] = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
-      }
-
-      v4f acc[KW][KA];
-#pragma unroll
-      for (int i = 0; i < KW; ++i)
-#pragma unroll
-        for (int j = 0; j < KA; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
-      const unsigned char* tile = btile + k * kTileBytes + l16 * 64 + l4 * 16;
-      uint4 bop[KA], bnx[KA], aop[KW], anx[KW];
-#pragma unroll
-      for (int j = 0; j < KA; ++j) bop[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes);
-#pragma unroll
-      for (int i = 0; i < KW; ++i) aop[i] = expand4(word_of(araw[k][i], 0));
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int t = 0; t < kSteps; ++t) {
-        if (t + 1 < kSteps) {
+      for (int j = 0; j < KA; ++j) bop[j] = bnx[j];
 #pragma unroll
-          for (int j = 0; j < KA; ++j)
-            bnx[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes + (t + 1) * kTileB * 64);
+      for (int i = 0; i < KW; ++i) aop[i] = anx[i];
+    }
+    // An MFMA reads its operands from all 64 lanes, but the compiler treats it as lane-local
+    // and would sink it (and the VALU code producing its operands) into the divergent branch
+    // that guards the final stores, where lanes of padded batch columns -- which still supply
+    // weight rows -- are masked off.  Pin the accumulators here, in uniform control flow.
 #pragma unroll
-          for (int i = 0; i < KW; ++i) anx[i] = expand4(word_of(araw[k][i], t + 1));
-        }
+    for (int i = 0; i < KW; ++i)
 #pragma unroll
-        for (int i = 0; i < KW; ++i)
+      for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
+    // block epilogue in the C view: lane = (batch column l16, row quad l4), with
+    //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j))   (integers below 2^24: exact in binary32)
+    //   y = sum_i alpha_i sum_j beta_j d_ij.
+    if constexpr (EPI == kEpiStore) {
+      // plain products (logits): the factored form
+      //   4 sum_i alpha_i (sum_j beta_j acc_ij) - (sum_i alpha_i 2 popc(w_i)) (sum_j beta_j)
+      //     + (sum_i alpha_i) (sum_j beta_j (n - 2 popc(x_j)))
+      // halves the arithmetic; its cancellation costs about one decimal digit (error ~1e-6
+      // relative), irrelevant for an output that nothing feeds back into the quantizer
+      float sb = 0.0f, sbcx = 0.0f;
 #pragma unroll
-          for (int j = 0; j < KA; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(aop[i]), as_operand(bop[j]), acc[i][j],
-                                                                         4, 4, 0, kScaleOne, 0, kScaleOne);
-        // issue order inside a step: the LDS reads of the next step first, then every MFMA
-        // followed by up to three of the VALU instructions that expand the next step's weights
-        __builtin_amdgcn_sched_group_barrier(0x100, KA, 0);
-#pragma unroll
-        for (int g = 0; g < KW * KA; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < KA; ++j) bop[j] = bnx[j];
-#pragma unroll
-        for (int i = 0; i < KW; ++i) aop[i] = anx[i];
+      for (int j = 0; j < KA; ++j) {
+        sb += btv[k][j];
+        sbcx = fmaf(btv[k][j], cx[k][j], sbcx);
       }
-      // An MFMA reads its operands from all 64 lanes, but the compiler treats it as lane-local
-      // and would sink it (and the VALU code producing its operands) into the divergent branch
-      // that guards the final stores, where lanes of padded batch columns -- which still supply
-      // weight rows -- are masked off.  Pin the accumulators here, in uniform control flow.
 #pragma unroll
-      for (int i = 0; i < KW; ++i)
+      for (int r = 0; r < 4; ++r) {
+        float y = 0.0f, pa = 0.0f, sa = 0.0f;
 #pragma unroll
-        for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
-      // block epilogue in the C view: lane = (batch column l16, row quad l4), with
-      //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j))   (integers below 2^24: exact in binary32)
-      //   y = sum_i alpha_i sum_j beta_j d_ij.
-      if constexpr (EPI == kEpiStore) {
-        // plain products (logits): the factored form
-        //   4 sum_i alpha_i (sum_j beta_j acc_ij) - (sum_i alpha_i 2 popc(w_i)) (sum_j beta_j)
-        //     + (sum_i alpha_i) (sum_j beta_j (n - 2 popc(x_j)))
-        // halves the arithmetic; its cancellation costs about one decimal digit (error ~1e-6
-        // relative), irrelevant for an output that nothing feeds back into the quantizer
-        float sb = 0.0f, sbcx = 0.0f;
+        for (int i = 0; i < KW; ++i) {
+          float inner = 0.0f;
 #pragma unroll
-        for (int j = 0; j < KA; ++j) {
-          sb += btv[k][j];
-          sbcx = fmaf(btv[k][j], cx[k][j], sbcx);
+          for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], acc[i][j][r], inner);
+          y = fmaf(alr[r][i], inner, y);
+          pa = fmaf(alr[r][i], pw2[i][r], pa);
+          sa += alr[r][i];
         }
+        ys[r] = fmaf(4.0f, y, fmaf(sa, sbcx, -pa * sb));
+      }
+      if (a.D && bok) {  // integer test hook: the dot products themselves
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (cok[r]) {
+#pragma unroll
+            for (int i = 0; i < KW; ++i)
+#pragma unroll
+              for (int j = 0; j < KA; ++j)
+                a.D[(((long long)b * m + crow[r]) * KW + i) * KA + j] = (int)(4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j]);
+          }
+      }
+    } else {
+      // recurrent cells: h_t goes back into the on-line quantizer, where a difference in the
+      // last digits can move an entry across an interval boundary; form the exact integer
+      // dot products first, as the reference arithmetic does
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float y = 0.0f;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          float inner = 0.0f;
+#pragma unroll
+          for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], 4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j], inner);
+          y = fmaf(alr[r][i], inner, y);
+        }
+        ys[r] = y;
+      }
+    }
+  };
+  for (int it = 0; it < iters; ++it) {
+    const int rb = rb_first + it * NSLOT + wr;
+    if (!SPLIT && rb >= rb_end) break;
+    const bool live = rb < rb_end;  // SPLIT: a wave without a row block still meets the barrier
+    float ysum[NBLK][4];
+    int crow[4];
+    bool cok[4];
+    float bias0[4], bias1[4], yold[4], prev = 0.0f;
+    if (live) {
+      if constexpr (!SPLIT) c_rows(rb, crow, cok);
+      if constexpr (SPLIT) {
+        fetch_rowblock(rb);
+        const Ahead& cur = nx;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float y = 0.0f, pa = 0.0f, sa = 0.0f;
-#pragma unroll
-          for (int i = 0; i < KW; ++i) {
-            float inner = 0.0f;
-#pragma unroll
-            for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], acc[i][j][r], inner);
-            y = fmaf(alr[k][r][i], inner, y);
-            pa = fmaf(alr[k][r][i], pw2[i][r], pa);
-            sa += alr[k][r][i];
-          }
-          ysum[k][r] = fmaf(4.0f, y, fmaf(sa, sbcx, -pa * sb));
+          crow[r] = cur.crow[r];
+          cok[r] = cur.cok[r];
+          bias0[r] = cur.bias0[r];
+          bias1[r] = cur.bias1[r];
+        }
+        prev = cur.prev;
+        if (kb == 0) {
+          run_block(K0{}, cur.araw, cur.alr, crow, cok, ysum[0]);
+        } else {
+          run_block(K1{}, cur.araw, cur.alr, crow, cok, ysum[NBLK - 1]);
+          xch[((it & 1) * NSLOT + wr) * 64 + lane] = make_float4(ysum[NBLK - 1][0], ysum[NBLK - 1][1],
+                                                                 ysum[NBLK - 1][2], ysum[NBLK - 1][3]);
         }
       } else {
-        // recurrent cells: h_t goes back into the on-line quantizer, where a difference in the
-        // last digits can move an entry across an interval boundary; form the exact integer
-        // dot products first, as the reference arithmetic does
+        uint4 araw[NBLK][KW][2];
+        float alr[NBLK][4][KW];
+        load_a(K0{}, rb, araw[0]);
+        if constexpr (NBLK == 2) load_a(K1{}, rb, araw[NBLK - 1]);
+        load_alpha(K0{}, crow, alr[0]);
+        if constexpr (NBLK == 2) load_alpha(K1{}, crow, alr[NBLK - 1]);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float y = 0.0f;
-#pragma unroll
-          for (int i = 0; i < KW; ++i) {
-            float inner = 0.0f;
-#pragma unroll
-            for (int j = 0; j < KA; ++j) inner = fmaf(btv[k][j], 4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j], inner);
-            y = fmaf(alr[k][r][i], inner, y);
-          }
-          ysum[k][r] = y;
+          bias0[r] = a.bias0 ? a.bias0[crow[r]] : 0.0f;
+          bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[crow[r]] : 0.0f;
+          yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
         }
+        if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
+        if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
+        run_block(K0{}, araw[0], alr[0], crow, cok, ysum[0]);
+        if constexpr (NBLK == 2) run_block(K1{}, araw[NBLK - 1], alr[NBLK - 1], crow, cok, ysum[NBLK - 1]);
       }
-      if constexpr (EPI == kEpiStore) {
-        if (a.D && bok) {  // integer test hook: the dot products themselves
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (cok[r]) {
-#pragma unroll
-              for (int i = 0; i < KW; ++i)
-#pragma unroll
-                for (int j = 0; j < KA; ++j)
-                  a.D[(((long long)b * m + crow[r]) * KW + i) * KA + j] = (int)(4.0f * acc[i][j][r] - pw2[i][r] + cx[k][j]);
-            }
-        }
-      }
+    }
+    if constexpr (SPLIT) {
+      __syncthreads();  // (alternating exchange buffers: one barrier per iteration suffices)
+      if (!live || kb != 0) continue;
+      const float4 o = xch[((it & 1) * NSLOT + wr) * 64 + lane];
+      ysum[NBLK - 1][0] = o.x; ysum[NBLK - 1][1] = o.y; ysum[NBLK - 1][2] = o.z; ysum[NBLK - 1][3] = o.w;
     }
 
     // (no early exit for padded batch columns: every lane stays active through the loop, the
@@ -393,13 +486,16 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   }
 }
 
-template <int KW, int KA, int EPI, int NWV>
+template <int KW, int KA, int EPI, int NWV, bool SPLIT = false>
 hipError_t launch_one(BmvArgs a, int rowblocks, int rb_per_wg, hipStream_t s, int* lse_slots) {
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
-  const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + sizeof(int) * NBLK * KA * kTileB;
+  constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;
+  // activation tiles, their popcounts (padded to 16 bytes), and the exchange buffers of SPLIT
+  const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + 16 * ((sizeof(int) * NBLK * KA * kTileB + 15) / 16) +
+                     (SPLIT ? sizeof(float4) * 2 * NSLOT * 64 : 0);
   static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV, SPLIT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     configured = true;
@@ -409,7 +505,7 @@ hipError_t launch_one(BmvArgs a, int rowblocks, int rb_per_wg, hipStream_t s, in
   if (EPI != kEpiStore || slots > kLseMaxSlots || slots > a.lse_cap) a.lse_part = nullptr;
   a.lse_slots = (int)slots;
   if (lse_slots) *lse_slots = a.lse_part ? (int)slots : 0;
-  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
+  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV, SPLIT>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
   return hipGetLastError();
 }
 
@@ -417,6 +513,13 @@ template <int KW, int KA, int EPI>
 hipError_t launch_mode(const BmvArgs& a, hipStream_t s, int* lse_slots) {
   const int rowblocks = (int)((EPI == kEpiStore) ? (a.m + 15) / 16 : (a.H + 3) / 4);
   const int btiles = (a.batch + kTileB - 1) / kTileB;
+  if constexpr (EPI != kEpiStore) {
+    // few row-block tasks (at most two per SIMD of the chip): pair the waves over the x and h blocks,
+    // four row blocks per 8-wave workgroup
+    // (up to 3 weight planes and 9 plane pairs: beyond that the paired kernel no longer fits 256 registers)
+    if constexpr (KW <= 3 && KW * KA <= 9)
+      if ((long long)rowblocks * btiles <= 2048) return launch_one<KW, KA, EPI, 8, true>(a, rowblocks, 4, s, lse_slots);
+  }
   // about two workgroups per CU; each expands its activation tile once and then walks row blocks
   int splits = (512 + btiles - 1) / btiles;
   int per = (rowblocks + splits - 1) / splits;
