@@ -57,6 +57,10 @@ def lib():
         L.amq_oracle_log_softmax.argtypes = [_f32p, _i64, _i64, _f32p]
         L.amq_oracle_softmax_layer.argtypes = [_u32p, _f32p, _i64, _i64, _int, C.c_void_p, _f32p, _i64,
                                                _int, _int, _f32p, _f32p]
+        L.amq_oracle_refined_greedy.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
+        L.amq_oracle_refined_greedy_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p]
+        L.amq_oracle_relative_mse.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p, _f64p, _f64p]
+        L.amq_oracle_relative_mse.restype = C.c_double
         L.amq_oracle_gamma.argtypes = [C.c_double] * 4
         L.amq_oracle_gamma.restype = C.c_double
         _lib = L
@@ -266,6 +270,37 @@ def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T):
     bias_a, bias_p = _opt(bias)
     lib().amq_oracle_softmax_layer(Wsp, _f32(alpha_s), V, H, k_w, bias_p, h, B, k_a, T, logits, logprob)
     return logits, logprob
+
+
+def refined_greedy(w, k):
+    """Refined greedy approximation of one vector: code [k, n] uint8 (1 = +1), alpha [k]."""
+    w = _f32(w)
+    n = w.shape[0]
+    code = np.zeros((k, n), np.uint8)
+    alpha = np.zeros(k, np.float32)
+    lib().amq_oracle_refined_greedy(w, n, k, code, alpha)
+    return code, alpha
+
+
+def refined_greedy_rows(W, k):
+    W = _f32(W)
+    rows, cols = W.shape
+    planes = np.zeros((k, rows, wpr(cols)), np.uint32)
+    alpha = np.zeros((rows, k), np.float32)
+    lib().amq_oracle_refined_greedy_rows(W, rows, cols, cols, k, planes, alpha)
+    return planes, alpha
+
+
+def relative_mse(W, planes, alpha):
+    """(ratio, row_err [rows], row_norm [rows]) of a row-wise quantization, binary64."""
+    W = _f32(W)
+    rows, cols = W.shape
+    planes = np.ascontiguousarray(planes, np.uint32)
+    k = planes.shape[0]
+    row_err = np.zeros(rows, np.float64)
+    row_norm = np.zeros(rows, np.float64)
+    ratio = lib().amq_oracle_relative_mse(W, rows, cols, cols, k, planes, _f32(alpha), row_err, row_norm)
+    return float(ratio), row_err, row_norm
 
 
 def gamma(m, n, k_w, k_h):

@@ -26,8 +26,10 @@
  * cells against dense fp64 products of the de-quantized operands; the
  * embedding lookup against quantizing the looked-up row; the log-softmax
  * against a library routine, the two-class closed form and normalisation;
- * the output layer against a dense fp64 layer on de-quantized operands; the
- * operation-count model of Sec. 4.
+ * the output layer against a dense fp64 layer on de-quantized operands;
+ * refined greedy against a library least-squares routine stage by stage; the
+ * relative error against a norm computed by a library; the operation-count
+ * model of Sec. 4.
  * Parity unpinned: nothing in this file.  (Trained-model accuracy tables are
  * outside what this oracle computes.)
  *
@@ -527,6 +529,86 @@ void amq_oracle_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32
     }
   free(ax);
   free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * Refined greedy approximation (Sec. 2, the comparison method built on
+ * Eq. 3-5): for j = 1..k, plane j is the sign of the current residual and
+ * alpha_j its mean absolute value (Eq. 4); then all of alpha_1..alpha_j are
+ * replaced by the least-squares solution for the first j planes (Eq. 5 on
+ * B_j = [b_1 .. b_j]); the next residual is w minus the reconstruction with
+ * the refined coefficients.  Codes are never revisited.
+ * Precision as everywhere: the reconstruction value of an entry is the
+ * binary32 left-to-right sum of +-alpha_i (a code-table value), the residual
+ * one binary32 subtraction, the reductions and the solve binary64.  A
+ * singular Gram matrix skips that refinement.
+ * ------------------------------------------------------------------ */
+void amq_oracle_refined_greedy(const float* w, int64_t n, int k, uint8_t* code, float* alpha) {
+  float* r = (float*)malloc(sizeof(float) * (size_t)n);
+  for (int64_t l = 0; l < n; ++l) r[l] = w[l];
+  for (int j = 0; j < k; ++j) {
+    double s = 0.0;
+    for (int64_t l = 0; l < n; ++l) s += fabs((double)r[l]);
+    alpha[j] = (float)(s / (double)n);
+    for (int64_t l = 0; l < n; ++l) code[(size_t)j * n + l] = sign_code(r[l]);
+    amq_oracle_ls(w, n, j + 1, code, alpha); /* the first j + 1 planes are contiguous in `code` */
+    for (int64_t l = 0; l < n; ++l) {
+      float v = 0.0f;
+      for (int i = 0; i <= j; ++i) {
+        float term = code[(size_t)i * n + l] ? alpha[i] : -alpha[i];
+        v = (i == 0) ? term : v + term;
+      }
+      r[l] = w[l] - v;
+    }
+  }
+  free(r);
+}
+
+/* Row-wise refined greedy on a matrix, packed output as amq_oracle_quantize_rows. */
+void amq_oracle_refined_greedy_rows(const float* W, int64_t rows, int64_t cols, int64_t ld, int k,
+                                    uint32_t* planes, float* alpha) {
+  int64_t wpr = amq_oracle_wpr(cols);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(amq_oracle_get_threads()) schedule(static)
+#endif
+  for (int64_t r = 0; r < rows; ++r) {
+    uint8_t* code = (uint8_t*)malloc((size_t)k * (size_t)cols);
+    amq_oracle_refined_greedy(W + r * ld, cols, k, code, alpha + r * k);
+    for (int i = 0; i < k; ++i)
+      amq_oracle_pack(code + (size_t)i * cols, cols, planes + ((size_t)i * rows + r) * wpr);
+    free(code);
+  }
+}
+
+/* ------------------------------------------------------------------ *
+ * Relative mean squared error of a row-wise quantization (the measure of
+ * Tables 1-2): sum over the matrix of (W - sum_i alpha_i B_i)^2 divided by
+ * the sum of W^2, in binary64.  row_err / row_norm (nullable) receive the
+ * two sums of every row.
+ * ------------------------------------------------------------------ */
+double amq_oracle_relative_mse(const float* W, int64_t rows, int64_t cols, int64_t ld, int k,
+                               const uint32_t* planes, const float* alpha, double* row_err,
+                               double* row_norm) {
+  int64_t wpr = amq_oracle_wpr(cols);
+  double num = 0.0, den = 0.0;
+  for (int64_t r = 0; r < rows; ++r) {
+    double e = 0.0, q = 0.0;
+    for (int64_t l = 0; l < cols; ++l) {
+      double rec = 0.0;
+      for (int i = 0; i < k; ++i) {
+        int bit = unpack_bit(planes + ((size_t)i * rows + r) * wpr, l);
+        rec += bit ? (double)alpha[r * k + i] : -(double)alpha[r * k + i];
+      }
+      double d = (double)W[r * ld + l] - rec;
+      e += d * d;
+      q += (double)W[r * ld + l] * (double)W[r * ld + l];
+    }
+    if (row_err) row_err[r] = e;
+    if (row_norm) row_norm[r] = q;
+    num += e;
+    den += q;
+  }
+  return num / den;
 }
 
 /* ------------------------------------------------------------------ *
