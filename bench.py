@@ -271,6 +271,28 @@ def bench_lm(amq, dev, B, steps, warmup):
     return ms, ms_layer, ms_lsm
 
 
+def bench_relative_mse(amq, dev):
+    """Relative MSE of greedy (T = 0), refined greedy and alternating (T = 2) quantization of the
+    config-3 gate matrix (4096 x 2048, Gaussian) and of a heavy-tailed 4096 x 4096 matrix."""
+    from paper_1802_00150_amd import inputs
+    cfg = inputs.lstm_large(steps=1)
+    mats = {"lstm_4096x2048_gaussian": np.concatenate([cfg["Wx"], cfg["Wh"]], axis=1),
+            "heavy_tailed_4096x4096": inputs.heavy_tailed(rows=4096, cols=4096)}
+    out = {}
+    for name, W in mats.items():
+        d = dv(W, dev)
+        tab = {}
+        for k in (2, 3, 4):
+            row = {}
+            for method, (pl, al) in (("greedy", amq.quantize_weights(d, k, 0)),
+                                     ("refined", amq.quantize_refined_greedy(d, k)),
+                                     ("alternating", amq.quantize_weights(d, k, 2))):
+                row[method] = float(amq.relative_mse(d, pl, al)[0][2].item())
+            tab["k%d" % k] = row
+        out[name] = tab
+    return out
+
+
 def cpu_baseline_lstm(cfg, budget_s=15.0):
     """The oracle, as it stands, on the same LSTM workload: whole steps on all host threads."""
     import oracle
@@ -293,7 +315,7 @@ def cpu_baseline_lstm(cfg, budget_s=15.0):
                       % (n, B, H, k_w, k_a)}
 
 
-SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "lm", "quantizer", "cpu"]
+SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "lm", "quantizer", "mse", "cpu"]
 
 
 def copy_probe(dev, nbytes=512 << 20, iters=10):
@@ -415,6 +437,9 @@ def main():
         for k in (1, 2, 3, 4):
             ms, nbytes = bench_quantizer(amq, dev, k)
             also["quantize_weights_16384x4096_k%d_GBps" % k] = nbytes / (ms * 1e-3) / 1e9
+
+    if "mse" in sections:
+        also["relative_mse"] = bench_relative_mse(amq, dev)
 
     if "copy_probe" in sections:
         also["copy_probe"] = copy_probe(dev)

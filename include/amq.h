@@ -177,6 +177,27 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                  float* h_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Refined greedy approximation (Sec. 2; the strongest earlier method in Tables 1-2), every row
+ * on its own: for j = 1..k plane j is the sign of the current residual and alpha_j its mean
+ * absolute value (Eq. 4), then alpha_1..alpha_j are replaced by the least-squares solution for
+ * the first j planes (Eq. 5) and the residual is rebuilt from them.  Codes are never revisited.
+ * Arguments as amq_quantize_weights.  (The plain greedy approximation is amq_quantize_weights
+ * with T = 0.)
+ */
+int amq_quantize_refined_greedy(const float* W, int64_t rows, int64_t cols, int64_t ld, int k,
+                                uint32_t* planes, float* alpha, void* stream);
+
+/*
+ * Relative mean squared error of a row-wise quantization (the measure of Tables 1-2):
+ *   result[0] = sum over the matrix of (W - sum_i alpha_i B_i)^2,  result[1] = sum of W^2,
+ *   result[2] = result[0] / result[1];  row_err [rows], row_norm [rows] receive the two sums of
+ *   every row.  All three outputs are device arrays of double.
+ */
+int amq_relative_mse(const float* W, int64_t rows, int64_t cols, int64_t ld, int k,
+                     const uint32_t* planes, const float* alpha, double* row_err, double* row_norm,
+                     double* result, void* stream);
+
+/*
  * Embedding lookup (Eq. 6, first line; Sec. 4): with one-hot inputs W_e x_t is a row of the
  * embedding matrix, and a table quantized off line by amq_quantize_weights (Ep [k][vocab][wpr(n)],
  * alpha_e [vocab][k]) holds that row as a finished k-bit quantization.  Copies rows ids[0..B)

@@ -21,6 +21,7 @@ EXPORTS = [
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step",
+    "amq_quantize_refined_greedy", "amq_relative_mse",
 ]
 
 _lib = None
@@ -69,6 +70,8 @@ def lib():
         L.amq_lm_workspace_bytes.argtypes, L.amq_lm_workspace_bytes.restype = [_i64, _i64, _i64, _i64, _int, _int], _sz
         L.amq_lm_step.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
+        L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
+        L.amq_relative_mse.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p]
         _lib = L
     return _lib
 
@@ -337,3 +340,30 @@ def lm_step(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, b
                              _dev(h, torch.float32), _dev(c, torch.float32), B, k_a, k_as, T,
                              _dev(logprob, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
     return logprob
+
+
+def quantize_refined_greedy(W, k):
+    """Refined greedy approximation of every row of W [rows, cols] -> planes [k, rows, wpr], alpha [rows, k]."""
+    if W.dim() != 2 or W.stride(1) != 1 or W.dtype != torch.float32 or not W.is_cuda:
+        raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
+    rows, cols = W.shape
+    planes = _empty((k, rows, wpr(cols)), torch.int32, W)
+    alpha = _empty((rows, k), torch.float32, W)
+    _check(lib().amq_quantize_refined_greedy(W.data_ptr(), rows, cols, W.stride(0), k, planes.data_ptr(),
+                                             alpha.data_ptr(), _stream()))
+    return planes, alpha
+
+
+def relative_mse(W, planes, alpha):
+    """Returns (result [3] = error, norm, error / norm; row_err [rows]; row_norm [rows]), float64 GPU tensors."""
+    if W.dim() != 2 or W.stride(1) != 1 or W.dtype != torch.float32 or not W.is_cuda:
+        raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
+    rows, cols = W.shape
+    k = planes.shape[0]
+    row_err = _empty((rows,), torch.float64, W)
+    row_norm = _empty((rows,), torch.float64, W)
+    result = _empty((3,), torch.float64, W)
+    _check(lib().amq_relative_mse(W.data_ptr(), rows, cols, W.stride(0), k, _dev(planes, torch.int32),
+                                  _dev(alpha, torch.float32), row_err.data_ptr(), row_norm.data_ptr(),
+                                  result.data_ptr(), _stream()))
+    return result, row_err, row_norm

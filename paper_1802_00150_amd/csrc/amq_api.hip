@@ -394,6 +394,25 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
 }
 
+int amq_quantize_refined_greedy(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, uint32_t* planes,
+                                float* alpha, void* stream) {
+  if (!W || !planes || !alpha) return AMQ_ERR_INVALID;
+  if (!bits_ok(k) || rows <= 0 || cols <= 0 || ld < cols) return AMQ_ERR_INVALID;
+  if (!aligned(planes, 16)) return AMQ_ERR_INVALID;
+  if (cols > AMQ_MAX_QUANT_N || rows > 0x7fffffffLL) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_refined_greedy(W, ld, (int)cols, (int)rows, k, planes, alpha,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int amq_relative_mse(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, const uint32_t* planes,
+                     const float* alpha, double* row_err, double* row_norm, double* result, void* stream) {
+  if (!W || !planes || !alpha || !row_err || !row_norm || !result) return AMQ_ERR_INVALID;
+  if (!bits_ok(k) || rows <= 0 || cols <= 0 || ld < cols) return AMQ_ERR_INVALID;
+  if (cols > (1 << 30) || rows > (1LL << 33)) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_relative_mse(W, rows, (int)cols, ld, k, planes, alpha, row_err, row_norm, result,
+                                             static_cast<hipStream_t>(stream)));
+}
+
 int amq_embedding_lookup(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t n, int k,
                          const int64_t* ids, int64_t B, uint32_t* Xp, float* beta, void* stream) {
   if (!Ep || !alpha_e || !ids || !Xp || !beta) return AMQ_ERR_INVALID;

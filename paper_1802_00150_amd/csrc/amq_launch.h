@@ -44,6 +44,15 @@ struct QuantArgs {
 
 hipError_t launch_quantize(const QuantArgs& a, int k, hipStream_t s);
 
+// ---- comparison quantizer and error measure ------------------------------------------------
+// Refined greedy approximation of `count` vectors X [count][ld] of length n (Sec. 2).
+hipError_t launch_refined_greedy(const float* X, long long ld, int n, int count, int k, uint32_t* planes, float* coef,
+                                 hipStream_t s);
+// Sums of squared error and squared norm of every row, then result = {error, norm, error / norm}.
+hipError_t launch_relative_mse(const float* W, long long rows, int cols, long long ld, int k, const uint32_t* planes,
+                               const float* alpha, double* row_err, double* row_norm, double* result,
+                               hipStream_t s);
+
 // ---- binary products -------------------------------------------------------------------
 struct GemmOperand {
   const uint32_t* Wp;   // [k_w][m][wpr]

@@ -72,6 +72,14 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 16000, 16000, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
+    # comparison quantizer and error measure
+    assert L.amq_quantize_refined_greedy(null, 4, 4, 4, 2, p, p, None) == INVALID
+    assert L.amq_quantize_refined_greedy(p, 4, 8, 4, 2, p, p, None) == INVALID
+    assert L.amq_quantize_refined_greedy(p, 4, 4, 4, 5, p, p, None) == INVALID
+    assert L.amq_quantize_refined_greedy(p, 4, 16385, 16385, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_relative_mse(p, 4, 4, 4, 2, p, p, p, p, null, None) == INVALID
+    assert L.amq_relative_mse(p, 0, 4, 4, 2, p, p, p, p, p, None) == INVALID
+    assert L.amq_relative_mse(p, 4, 4, 2, 2, p, p, p, p, p, None) == INVALID
     # language-model entry points
     assert L.amq_embedding_lookup(p, p, 10, 8, 2, null, 1, p, p, None) == INVALID
     assert L.amq_embedding_lookup(p, p, 0, 8, 2, p, 1, p, p, None) == INVALID
