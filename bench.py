@@ -397,6 +397,7 @@ def main():
         cb = inputs.lstm_large(B=1)
         msb, _ = bench_lstm_steps(amq, cb, dev, 700, 70)
         also["lstm_b1_hidden1024_w3a3_steps_per_s"] = 1e3 / msb
+        also["lstm_b1_hidden1024_w3a3_sequence_call_steps_per_s"] = 1e3 / bench_lstm_sequence(amq, cb, dev, 20, 2)
 
     if "gemv" in sections:
         # batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency

@@ -26,6 +26,11 @@ struct StepWs {
   float* beta_h;
   float* pre0;
   float* pre1;
+  // batch 1 only: scratch of the grid-wide sequence kernel
+  unsigned* sync;
+  unsigned long long* hbuf;
+  uint32_t* xq;
+  float* xbeta;
   size_t total;
 };
 
@@ -44,6 +49,13 @@ StepWs carve(void* ws, int64_t I, int64_t H, int64_t B, int k_a, int gates, int 
   w.beta_h = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * k_a));
   w.pre0 = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H));
   w.pre1 = n_pre > 1 ? reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H)) : nullptr;
+  w.sync = nullptr; w.hbuf = nullptr; w.xq = nullptr; w.xbeta = nullptr;
+  if (B == 1 && gates == 4) {
+    w.sync = reinterpret_cast<unsigned*>(take(sizeof(unsigned) * (1 + amq::kSeqGMaxGrid)));
+    w.hbuf = reinterpret_cast<unsigned long long*>(take(sizeof(unsigned long long) * 2 * (size_t)H));
+    w.xq = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * amq::kSeqGMaxSteps * (size_t)k_a * amq_wpr(I)));
+    w.xbeta = reinterpret_cast<float*>(take(sizeof(float) * amq::kSeqGMaxSteps * 4));
+  }
   w.total = off;
   return w;
 }
@@ -56,6 +68,21 @@ int check_step(const void* Wxp, const void* ax, const void* Whp, const void* ah,
   if (!aligned(Wxp, 16) || !aligned(Whp, 16) || !aligned(ws, 256) || ws_bytes < need) return AMQ_ERR_INVALID;
   if (I > AMQ_MAX_QUANT_N || H > AMQ_MAX_QUANT_N || B > (1 << 24)) return AMQ_ERR_UNSUPPORTED;
   return AMQ_OK;
+}
+
+// The grid-wide sequence kernel needs all of its (at most kSeqGMaxGrid) workgroups resident at
+// once: true when the current device has at least that many compute units.
+bool grid_fits_device() {
+  static thread_local int cached_dev = -1, cached_cus = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (dev != cached_dev) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+    cached_dev = dev;
+    cached_cus = cus;
+  }
+  return cached_cus >= amq::kSeqGMaxGrid;
 }
 
 amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64_t n, int k_w,
@@ -326,6 +353,19 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, xs, h, B, k_a, T, h, workspace, workspace_bytes,
                       need);
   if (st != AMQ_OK) return st;
+  if (steps < (1 << 30) && amq::lstm_seqg_supported(I, H, B, k_w, k_a) && grid_fits_device()) {
+    // batch 1: the whole sequence (in pieces of at most kSeqGMaxSteps steps) in one launch over the
+    // chip, weights resident in registers
+    StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
+    for (int64_t t0 = 0; t0 < steps; t0 += amq::kSeqGMaxSteps) {
+      const int n = (int)(steps - t0 < amq::kSeqGMaxSteps ? steps - t0 : amq::kSeqGMaxSteps);
+      amq::SeqGArgs q{Wxp, alpha_x, Whp, alpha_h, (int)I, (int)H, bias, xs + t0 * I, n, h, c,
+                      hs ? hs + t0 * H : nullptr, T, 0, w.sync, w.hbuf, w.xq, w.xbeta};
+      st = hip_status(amq::launch_lstm_seqg(q, k_w, k_a, static_cast<hipStream_t>(stream)));
+      if (st != AMQ_OK) return st;
+    }
+    return AMQ_OK;
+  }
   if (steps < (1 << 30) && amq::lstm_seq1_supported(I, H, B, k_w, k_a)) {
     // small model, batch 1: the whole sequence in one persistent single-workgroup launch
     amq::Seq1Args q{Wxp, alpha_x, Whp, alpha_h, (int)I, (int)H, bias, xs, (int)steps, h, c, hs, T, 0, 0};

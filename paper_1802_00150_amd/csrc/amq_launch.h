@@ -159,6 +159,33 @@ hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* o
 hipError_t launch_log_softmax_finish(const float* Y, long long B, long long V, const float* part, int slots,
                                      float* out, hipStream_t s);
 
+// ---- whole batch-1 LSTM sequences in one launch spread over the chip (weights resident in
+// registers, one grid barrier per time step) ------------------------------------------------
+constexpr int kSeqGMaxGrid = 256;   // workgroups: one per compute unit, all resident at once
+constexpr int kSeqGMaxSteps = 64;   // time steps per launch (size of the table of input codes)
+struct SeqGArgs {
+  const uint32_t* Wxp;  // [k_w][4H][wpr(I)]
+  const float* ax;      // [4H][k_w]
+  const uint32_t* Whp;  // [k_w][4H][wpr(H)]
+  const float* ah;      // [4H][k_w]
+  int I, H;
+  const float* bias;    // [4H] or null
+  const float* xs;      // [steps][I]
+  int steps;            // at most kSeqGMaxSteps
+  float* h;             // [H] in: h_0, out: h_steps
+  float* c;             // [H] in: c_0, out: c_steps
+  float* hs;            // [steps][H] or null
+  int T;
+  int lg;               // filled by launch_lstm_seqg
+  // scratch in global memory (the caller's workspace)
+  unsigned* sync;       // give-up flag (left non-zero if the launch was abandoned), then kSeqGMaxGrid arrival bytes
+  unsigned long long* hbuf;  // [2][H]: h_t as published by the grid, {value, step tag} pairs, double-buffered
+  uint32_t* xq;         // [steps][k_a][wpr(I)]: codes of the inputs
+  float* xbeta;         // [steps][4]: their coefficients
+};
+bool lstm_seqg_supported(long long I, long long H, long long B, int k_w, int k_a);
+hipError_t launch_lstm_seqg(SeqGArgs a, int k_w, int k_a, hipStream_t s);
+
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU
 hipError_t launch_lstm_pointwise(const float* pre /*[B][4H]*/, const float* c_prev, float* h_out,

@@ -160,7 +160,9 @@ def test_config1_lstm_300_sequence(amq):
 
 
 @pytest.mark.parametrize("I,H,k_w,k_a,steps", [(300, 300, 2, 2, 7), (100, 64, 3, 3, 5), (512, 200, 2, 3, 4),
-                                               (130, 256, 3, 2, 3), (64, 1, 2, 2, 3)])
+                                               (130, 256, 3, 2, 3), (64, 1, 2, 2, 3), (1024, 1024, 3, 3, 4),
+                                               (1000, 600, 2, 2, 3), (33, 1024, 2, 3, 3), (100, 64, 2, 2, 70),
+                                               (129, 129, 3, 3, 2)])
 def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
     # small models at batch 1 run the whole sequence in one persistent launch; every h_t of the
     # series is compared with the oracle's step-by-step recurrence (with bias, non-zero start)
