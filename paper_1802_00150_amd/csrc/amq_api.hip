@@ -366,11 +366,6 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
     }
     return AMQ_OK;
   }
-  if (steps < (1 << 30) && amq::lstm_seq1_supported(I, H, B, k_w, k_a)) {
-    // small model, batch 1: the whole sequence in one persistent single-workgroup launch
-    amq::Seq1Args q{Wxp, alpha_x, Whp, alpha_h, (int)I, (int)H, bias, xs, (int)steps, h, c, hs, T, 0, 0};
-    return hip_status(amq::launch_lstm_seq1(q, k_w, k_a, static_cast<hipStream_t>(stream)));
-  }
   StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
   for (int64_t t = 0; t < steps; ++t) {
     st = lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, xs + t * B * I, h, c, B, k_a, T, h, c,

@@ -132,26 +132,6 @@ hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t 
 bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 
-// ---- whole batch-1 LSTM sequences in one launch (small models: weights resident in one CU) ---
-struct Seq1Args {
-  const uint32_t* Wxp;  // [k_w][4H][wpr(I)]
-  const float* ax;      // [4H][k_w]
-  const uint32_t* Whp;  // [k_w][4H][wpr(H)]
-  const float* ah;      // [4H][k_w]
-  int I, H;
-  const float* bias;    // [4H] or null
-  const float* xs;      // [steps][I]
-  int steps;
-  float* h;             // [H] in: h_0, out: h_steps
-  float* c;             // [H] in: c_0, out: c_steps
-  float* hs;            // [steps][H] or null
-  int T;
-  int lg;               // filled by launch_lstm_seq1
-  int xchunk;           // time steps whose input codes are held in LDS at once (filled by launch_lstm_seq1)
-};
-bool lstm_seq1_supported(long long I, long long H, long long B, int k_w, int k_a);
-hipError_t launch_lstm_seq1(Seq1Args a, int k_w, int k_a, hipStream_t s);
-
 // ---- output layer -----------------------------------------------------------------------
 // out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])); out may alias Y.
 hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* out, hipStream_t s);

@@ -34,7 +34,7 @@ def assert_coef_close(got, ref, what="coef"):
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     scale = np.abs(ref).max(axis=-1, keepdims=True)
-    bad = np.abs(got - ref) > 1e-4 * scale + 1e-30
+    bad = ~(np.abs(got - ref) <= 1e-4 * scale + 1e-30)   # (NaN counts as a mismatch)
     assert not bad.any(), "%s: %d mismatches, worst %g" % (what, bad.sum(), np.abs(got - ref).max())
 
 
@@ -43,7 +43,7 @@ def assert_vec_close(got, ref, what="y"):
     ref = np.asarray(ref, np.float64)
     rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
     tol = 1e-4 * np.abs(ref) + 1e-4 * rms + 1e-30
-    bad = np.abs(got - ref) > tol
+    bad = ~(np.abs(got - ref) <= tol)   # (NaN counts as a mismatch)
     assert not bad.any(), "%s: %d mismatches, worst ratio %g" % (what, bad.sum(), (np.abs(got - ref) / tol).max())
 
 

@@ -164,8 +164,9 @@ def test_config1_lstm_300_sequence(amq):
                                                (1000, 600, 2, 2, 3), (33, 1024, 2, 3, 3), (100, 64, 2, 2, 70),
                                                (129, 129, 3, 3, 2)])
 def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
-    # small models at batch 1 run the whole sequence in one persistent launch; every h_t of the
-    # series is compared with the oracle's step-by-step recurrence (with bias, non-zero start)
+    # batch-1 models with vectors of at most 1024 entries run the whole sequence in one launch over
+    # the chip (more than 64 steps: several launches); every h_t of the series is compared with the
+    # oracle's step-by-step recurrence (with bias, non-zero start)
     import torch
     g = np.random.default_rng(I * 7 + H)
     Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
@@ -184,6 +185,39 @@ def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
         hs_ref.append(h.copy())
     dh, dc = to_dev(h0), to_dev(c0)
     hs = torch.empty((steps, 1, H), dtype=torch.float32, device=dh.device)
+    amq.lstm_sequence(to_dev(Wxp), to_dev(ax), to_dev(Whp), to_dev(ah), I, H, to_dev(bias), to_dev(xs), dh, dc,
+                      k_a, 2, hs=hs)
+    hs_g = host(hs)
+    for t in range(steps):
+        assert_vec_close(hs_g[t], hs_ref[t], "h_%d" % t)
+    assert_vec_close(host(dh), h, "h final")
+    assert_vec_close(host(dc), c, "c final")
+
+
+@pytest.mark.parametrize("I,H,B,k_w,k_a,steps", [(64, 48, 5, 2, 2, 4), (300, 200, 17, 3, 3, 5), (130, 1000, 33, 2, 3, 3),
+                                                 (1024, 1024, 64, 3, 3, 3), (100, 64, 20, 2, 2, 70),
+                                                 (513, 129, 2, 1, 4, 3), (1024, 1024, 48, 2, 2, 2)])
+def test_lstm_sequence_batched(amq, I, H, B, k_w, k_a, steps):
+    # several concurrent sequences through one amq_lstm_sequence call (free-running on the GPU);
+    # every h_t is compared with the oracle's step-by-step recurrence
+    import torch
+    g = np.random.default_rng(I * 7 + H + B)
+    Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((4 * H, H)) * 0.08).astype(np.float32)
+    bias = (g.standard_normal(4 * H) * 0.1).astype(np.float32)
+    xs = g.standard_normal((steps, B, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    c0 = g.standard_normal((B, H)).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    say("batched sequence I=%d H=%d B=%d kw=%d ka=%d steps=%d" % (I, H, B, k_w, k_a, steps))
+    h, c = h0.copy(), c0.copy()
+    hs_ref = []
+    for t in range(steps):
+        h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, xs[t], h, c, k_a, 2)
+        hs_ref.append(h.copy())
+    dh, dc = to_dev(h0), to_dev(c0)
+    hs = torch.full((steps, B, H), float("nan"), dtype=torch.float32, device=dh.device)
     amq.lstm_sequence(to_dev(Wxp), to_dev(ax), to_dev(Whp), to_dev(ah), I, H, to_dev(bias), to_dev(xs), dh, dc,
                       k_a, 2, hs=hs)
     hs_g = host(hs)
