@@ -29,6 +29,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0                       # MI355X HBM3E
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T integer lane-ops/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 FP4_MFMA_PEAK_TFLOPS = 10100.0               # dense fp4 matrix cores
+# HBM bytes per launch of the streamed W2/A2 GEMV from the rocprofv3 counter runs summarised in
+# profiles/gemv_streamed_4096x1024.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (scale factors from a plain
+# 512 MiB device copy) = (2 x 270909.0 + 8192.4) KiB
+GEMV_TRAFFIC_BYTES = (2 * 270909.0 + 8192.4) * 1024
 
 
 def dv(a, dev):
@@ -408,7 +412,7 @@ def main():
             if k == 2:
                 out["roofline_gemv"] = {"kernel": "binary GEMV 4096x1024 W2/A2 batch 1, %d matrices streamed" % G,
                                         "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                        "frac": gbps / HBM_PEAK_GBPS, "traffic": None, "launch_ms": ms,
+                                        "frac": gbps / HBM_PEAK_GBPS, "traffic": GEMV_TRAFFIC_BYTES, "launch_ms": ms,
                                         "bytes_per_launch": nbytes}
             also["gemv_b1_w%da%d_warm_call_us" % (k, k)] = bench_gemv_warm(amq, dev, 4096, 1024, k) * 1e3
 

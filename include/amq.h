@@ -154,7 +154,15 @@ int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32
  * sequence): xs [steps][B][I]; h and c [B][H] are read as the initial state and
  * overwritten with the final state; hs [steps][B][H] (nullable) receives every
  * h_t.  Same arithmetic as `steps` calls of amq_lstm_step.
+ * For B = 1 with I, H <= 1024 and 2- or 3-bit codes the recurrence runs inside one
+ * launch that occupies the whole chip (pieces of 64 steps), the workgroups exchanging
+ * h_t through the workspace.  That launch needs all its workgroups resident at once:
+ * do not run it concurrently with other work that keeps compute units busy.  Its waits
+ * are bounded; if one gives up, h and c are left as they were, hs is incomplete, and
+ * the 32-bit word at byte amq_lstm_sequence_flag_offset(...) of the workspace is
+ * non-zero (it is zero after a completed call; SIZE_MAX: this shape has no such word).
  */
+size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a);
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                       const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
                       const float* xs, int64_t steps, float* h, float* c, int64_t B, int k_a, int T,

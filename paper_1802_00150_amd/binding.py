@@ -18,6 +18,7 @@ EXPORTS = [
     "amq_quantize_weights", "amq_quantize_activations", "amq_ls_update", "amq_bst_assign",
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_packed", "amq_lstm_sequence",
+    "amq_lstm_sequence_flag_offset",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step",
@@ -54,6 +55,8 @@ def lib():
         L.amq_binary_gemv_grouped.argtypes = [_i64, _p, _p, _i64, _i64, _int, _p, _p, _int, _p, _p, _p]
         L.amq_lstm_workspace_bytes.argtypes, L.amq_lstm_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
         L.amq_gru_workspace_bytes.argtypes, L.amq_gru_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
+        L.amq_lstm_sequence_flag_offset.argtypes = [_i64, _i64, _i64, _int]
+        L.amq_lstm_sequence_flag_offset.restype = _sz
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
                                     _p, _sz, _p]
         L.amq_lstm_step_packed.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _i64, _int,
@@ -260,6 +263,14 @@ def lstm_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias, xs, h, c, k_a, T, ws=N
                                    None if hs is None else _dev(hs, torch.float32), ws.data_ptr(),
                                    ws.numel(), _stream()))
     return h, c
+
+
+def lstm_sequence_abandoned(ws, I, H, B, k_a):
+    """True if the last lstm_sequence call on workspace `ws` gave up a bounded wait (see include/amq.h)."""
+    off = int(lib().amq_lstm_sequence_flag_offset(I, H, B, k_a))
+    if off == C.c_size_t(-1).value:
+        return False
+    return bool(ws[off:off + 4].view(torch.int32).item() != 0)
 
 
 def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T, ws=None, h_out=None):

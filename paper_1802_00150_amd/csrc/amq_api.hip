@@ -344,6 +344,13 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
                           c_out, nullptr, w, static_cast<hipStream_t>(stream));
 }
 
+size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return SIZE_MAX;
+  char base[1];  // any non-null address: only the offset of the region is of interest
+  StepWs w = carve(base, I, H, B, k_a, 4, 1);
+  return w.sync ? (size_t)(reinterpret_cast<char*>(w.sync) - base) : SIZE_MAX;
+}
+
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
                       int64_t I, int64_t H, int k_w, const float* bias, const float* xs, int64_t steps,
                       float* h, float* c, int64_t B, int k_a, int T, float* hs, void* workspace,

@@ -42,6 +42,10 @@ def test_host_helpers(L):
     assert L.amq_lstm_workspace_bytes(1024, 1024, 64, 3) % 256 == 0
     assert L.amq_lstm_workspace_bytes(1024, 1024, 64, 3) >= 64 * 4096 * 4 + 2 * 3 * 64 * 32 * 4
     assert L.amq_gru_workspace_bytes(1024, 1024, 0, 2) == 0
+    L.amq_lstm_sequence_flag_offset.restype = C.c_size_t
+    off = L.amq_lstm_sequence_flag_offset(300, 300, 1, 2)
+    assert off % 256 == 0 and off + 4 <= L.amq_lstm_workspace_bytes(300, 300, 1, 2)
+    assert L.amq_lstm_sequence_flag_offset(300, 300, 8, 2) == C.c_size_t(-1).value
 
 
 def test_validation_rejects_before_touching_the_device(L):

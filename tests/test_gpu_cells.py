@@ -184,9 +184,11 @@ def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
         h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, xs[t], h, c, k_a, 2)
         hs_ref.append(h.copy())
     dh, dc = to_dev(h0), to_dev(c0)
-    hs = torch.empty((steps, 1, H), dtype=torch.float32, device=dh.device)
+    hs = torch.full((steps, 1, H), float("nan"), dtype=torch.float32, device=dh.device)
+    ws = amq.lstm_workspace(I, H, 1, k_a, dh.device)
     amq.lstm_sequence(to_dev(Wxp), to_dev(ax), to_dev(Whp), to_dev(ah), I, H, to_dev(bias), to_dev(xs), dh, dc,
-                      k_a, 2, hs=hs)
+                      k_a, 2, ws=ws, hs=hs)
+    assert not amq.lstm_sequence_abandoned(ws, I, H, 1, k_a)
     hs_g = host(hs)
     for t in range(steps):
         assert_vec_close(hs_g[t], hs_ref[t], "h_%d" % t)
