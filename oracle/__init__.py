@@ -57,6 +57,9 @@ def lib():
         L.amq_oracle_log_softmax.argtypes = [_f32p, _i64, _i64, _f32p]
         L.amq_oracle_softmax_layer.argtypes = [_u32p, _f32p, _i64, _i64, _int, C.c_void_p, _f32p, _i64,
                                                _int, _int, _f32p, _f32p]
+        L.amq_oracle_quantize_rows_final_ls.argtypes = [_f32p, _i64, _i64, _i64, _int, _int, _u32p, _f32p]
+        L.amq_oracle_dequantize.argtypes = [_u32p, _f32p, _i64, _i64, _int, _f32p, _i64]
+        L.amq_oracle_clip.argtypes = [_f32p, _i64, C.c_float, C.c_float]
         L.amq_oracle_refined_greedy.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
         L.amq_oracle_refined_greedy_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p]
         L.amq_oracle_relative_mse.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p, _f64p, _f64p]
@@ -270,6 +273,31 @@ def softmax_layer(Wsp, alpha_s, H, bias, h, k_a, T):
     bias_a, bias_p = _opt(bias)
     lib().amq_oracle_softmax_layer(Wsp, _f32(alpha_s), V, H, k_w, bias_p, h, B, k_a, T, logits, logprob)
     return logits, logprob
+
+
+def quantize_rows_final_ls(W, k, T):
+    """Alg. 2 followed by one more coefficient update (Eq. 5) on the final codes."""
+    W = _f32(W)
+    rows, cols = W.shape
+    planes = np.zeros((k, rows, wpr(cols)), np.uint32)
+    alpha = np.zeros((rows, k), np.float32)
+    lib().amq_oracle_quantize_rows_final_ls(W, rows, cols, cols, k, T, planes, alpha)
+    return planes, alpha
+
+
+def dequantize(planes, alpha, cols):
+    """Reconstruction [rows, cols] float32 of a row-wise quantization."""
+    planes = np.ascontiguousarray(planes, np.uint32)
+    k, rows, _ = planes.shape
+    out = np.zeros((rows, cols), np.float32)
+    lib().amq_oracle_dequantize(planes, _f32(alpha), rows, cols, k, out, cols)
+    return out
+
+
+def clip(w, lo=-1.0, hi=1.0):
+    out = _f32(w).copy()
+    lib().amq_oracle_clip(out.reshape(-1), out.size, lo, hi)
+    return out
 
 
 def refined_greedy(w, k):

@@ -27,7 +27,9 @@
  * embedding lookup against quantizing the looked-up row; the log-softmax
  * against a library routine, the two-class closed form and normalisation;
  * the output layer against a dense fp64 layer on de-quantized operands;
- * refined greedy against a library least-squares routine stage by stage; the
+ * the trailing-least-squares variant against a library least-squares routine;
+ * the reconstruction against the code table and a dense product; refined
+ * greedy against a library least-squares routine stage by stage; the
  * relative error against a norm computed by a library; the operation-count
  * model of Sec. 4.
  * Parity unpinned: nothing in this file.  (Trained-model accuracy tables are
@@ -529,6 +531,59 @@ void amq_oracle_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32
     }
   free(ax);
   free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * Variant of Alg. 2 with one more coefficient update (Eq. 5) after the last
+ * code assignment, so that the returned coefficients are the least-squares
+ * optimum for the returned codes (the algorithm as printed stops after the
+ * codes).  Row-wise, packed output as amq_oracle_quantize_rows.
+ * ------------------------------------------------------------------ */
+void amq_oracle_quantize_rows_final_ls(const float* W, int64_t rows, int64_t cols, int64_t ld, int k,
+                                       int T, uint32_t* planes, float* alpha) {
+  int64_t wpr = amq_oracle_wpr(cols);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(amq_oracle_get_threads()) schedule(static)
+#endif
+  for (int64_t r = 0; r < rows; ++r) {
+    uint8_t* code = (uint8_t*)malloc((size_t)k * (size_t)cols);
+    float a[ORACLE_MAX_K];
+    amq_oracle_quantize(W + r * ld, cols, k, T, code, a, NULL);
+    amq_oracle_ls(W + r * ld, cols, k, code, a);
+    for (int i = 0; i < k; ++i) {
+      amq_oracle_pack(code + (size_t)i * cols, cols, planes + ((size_t)i * rows + r) * wpr);
+      alpha[r * k + i] = a[i];
+    }
+    free(code);
+  }
+}
+
+/* ------------------------------------------------------------------ *
+ * Reconstruction w_hat = sum_i alpha_i b_i of a row-wise quantization, the
+ * quantity the network sees in the forward pass of training (Sec. 4,
+ * "Training": w_hat is derived from w and fed to f; the gradient with respect
+ * to w is taken equal to the gradient with respect to w_hat).  An entry's
+ * value is a code-table value: the binary32 left-to-right sum of +-alpha_i.
+ * out: rows x cols with leading dimension ld_out.
+ * ------------------------------------------------------------------ */
+void amq_oracle_dequantize(const uint32_t* planes, const float* alpha, int64_t rows, int64_t cols,
+                           int k, float* out, int64_t ld_out) {
+  int64_t wpr = amq_oracle_wpr(cols);
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t l = 0; l < cols; ++l) {
+      float v = 0.0f;
+      for (int i = 0; i < k; ++i) {
+        float term = unpack_bit(planes + ((size_t)i * rows + r) * wpr, l) ? alpha[r * k + i] : -alpha[r * k + i];
+        v = (i == 0) ? term : v + term;
+      }
+      out[r * ld_out + l] = v;
+    }
+}
+
+/* Clipping of the full-precision weights to [lo, hi] (Sec. 4, "Training":
+ * outliers are cut to [-1, 1]). */
+void amq_oracle_clip(float* w, int64_t n, float lo, float hi) {
+  for (int64_t l = 0; l < n; ++l) w[l] = w[l] < lo ? lo : (w[l] > hi ? hi : w[l]);
 }
 
 /* ------------------------------------------------------------------ *

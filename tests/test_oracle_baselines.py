@@ -103,3 +103,45 @@ def test_method_order_matches_tables_1_and_2():
             e_r = oracle.relative_mse(W, *oracle.refined_greedy_rows(W, k))[0]
             e_a = oracle.relative_mse(W, *oracle.quantize_rows(W, k, 2))[0]
             assert e_g > e_r > e_a, (k, e_g, e_r, e_a)
+
+
+def test_final_ls_coefficients_are_least_squares_for_the_final_codes():
+    g = np.random.default_rng(21)
+    W = (g.standard_normal((6, 333)) * 0.1).astype(np.float32)
+    for k in (1, 2, 3, 4):
+        p0, a0 = oracle.quantize_rows(W, k, 2)
+        p1, a1 = oracle.quantize_rows_final_ls(W, k, 2)
+        assert np.array_equal(p0, p1)                              # same codes, only the coefficients move
+        bits = np.unpackbits(p1.view(np.uint8).reshape(k, 6, -1), axis=-1, bitorder="little")[..., :333]
+        for r in range(6):
+            B = (bits[:, r].astype(np.float64) * 2 - 1).T
+            ref = np.linalg.lstsq(B, W[r].astype(np.float64), rcond=None)[0]
+            assert np.allclose(a1[r], ref, rtol=1e-5, atol=1e-7)
+        e0 = oracle.relative_mse(W, p0, a0)[0]
+        e1 = oracle.relative_mse(W, p1, a1)[0]
+        assert e1 <= e0 * (1 + 1e-9)
+
+
+def test_dequantize_is_the_code_table_value_and_the_dense_reconstruction():
+    g = np.random.default_rng(22)
+    W = (g.standard_normal((5, 200)) * 0.1).astype(np.float32)
+    for k in (1, 2, 3, 4):
+        planes, alpha = oracle.quantize_rows(W, k, 2)
+        rec = oracle.dequantize(planes, alpha, 200)
+        bits = np.unpackbits(planes.view(np.uint8).reshape(k, 5, -1), axis=-1, bitorder="little")[..., :200]
+        dense = np.einsum("krn,rk->rn", bits.astype(np.float64) * 2 - 1, alpha.astype(np.float64))
+        assert np.allclose(rec, dense, rtol=0, atol=2e-7 * np.abs(alpha).max() * k)
+        for r in range(5):
+            v, pat, _ = oracle.code_table(alpha[r])
+            table = dict(zip(pat.tolist(), v.tolist()))
+            pattern = (bits[:, r].astype(np.int64) << np.arange(k - 1, -1, -1)[:, None]).sum(axis=0)
+            assert np.array_equal(rec[r], np.array([table[p] for p in pattern], np.float32))
+        # the reconstruction error it implies is the relative MSE
+        err = ((W.astype(np.float64) - rec.astype(np.float64)) ** 2).sum() / (W.astype(np.float64) ** 2).sum()
+        assert abs(err - oracle.relative_mse(W, planes, alpha)[0]) < 1e-6
+
+
+def test_clip():
+    w = np.array([-3.0, -1.0, -0.5, 0.0, 0.99, 1.0, 7.5], np.float32)
+    assert np.array_equal(oracle.clip(w), np.clip(w, -1.0, 1.0))
+    assert np.array_equal(oracle.clip(w, -0.25, 0.5), np.clip(w, -0.25, 0.5))
