@@ -185,6 +185,28 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                  float* h_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * amq_quantize_weights with options.  AMQ_QUANT_FINAL_LS adds one more coefficient update
+ * (Eq. 5) after the last code assignment, so that the coefficients returned are the
+ * least-squares optimum for the codes returned (Alg. 2 as printed ends with the codes).
+ * Unknown flag bits are AMQ_ERR_INVALID.
+ */
+#define AMQ_QUANT_FINAL_LS 1
+int amq_quantize_weights_ex(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T,
+                            int flags, uint32_t* planes, float* alpha, void* stream);
+
+/*
+ * Training-side helpers (Sec. 4, "Training": the forward pass uses the quantized weights
+ * w_hat = sum_i alpha_i b_i, the gradient with respect to w is taken equal to the gradient
+ * with respect to w_hat, and the full-precision weights are clipped to [-1, 1]).
+ *   amq_dequantize: out [rows][ld_out] (ld_out >= cols) receives w_hat of a row-wise
+ *     quantization; an entry is the binary32 left-to-right sum of +-alpha[r][i].
+ *   amq_clip: w[0..n) clipped to [lo, hi] in place.
+ */
+int amq_dequantize(const uint32_t* planes, const float* alpha, int64_t rows, int64_t cols, int k,
+                   float* out, int64_t ld_out, void* stream);
+int amq_clip(float* w, int64_t n, float lo, float hi, void* stream);
+
+/*
  * Refined greedy approximation (Sec. 2; the strongest earlier method in Tables 1-2), every row
  * on its own: for j = 1..k plane j is the sign of the current residual and alpha_j its mean
  * absolute value (Eq. 4), then alpha_1..alpha_j are replaced by the least-squares solution for

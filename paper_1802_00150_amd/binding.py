@@ -23,6 +23,7 @@ EXPORTS = [
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step",
     "amq_quantize_refined_greedy", "amq_relative_mse",
+    "amq_quantize_weights_ex", "amq_dequantize", "amq_clip",
 ]
 
 _lib = None
@@ -75,6 +76,9 @@ def lib():
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
         L.amq_relative_mse.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p]
+        L.amq_quantize_weights_ex.argtypes = [_p, _i64, _i64, _i64, _int, _int, _int, _p, _p, _p]
+        L.amq_dequantize.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p]
+        L.amq_clip.argtypes = [_p, _i64, C.c_float, C.c_float, _p]
         _lib = L
     return _lib
 
@@ -116,15 +120,23 @@ def _empty(shape, dtype, like):
     return torch.empty(shape, dtype=dtype, device=like.device)
 
 
-def quantize_weights(W, k, T):
-    """W [rows, cols] float32 (rows may be strided) -> planes [k, rows, wpr] int32, alpha [rows, k]."""
+QUANT_FINAL_LS = 1
+
+
+def quantize_weights(W, k, T, final_ls=False):
+    """W [rows, cols] float32 (rows may be strided) -> planes [k, rows, wpr] int32, alpha [rows, k].
+    final_ls: one more coefficient update (Eq. 5) after the last code assignment."""
     if W.dim() != 2 or W.stride(1) != 1 or W.dtype != torch.float32 or not W.is_cuda:
         raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
     rows, cols = W.shape
     planes = _empty((k, rows, wpr(cols)), torch.int32, W)
     alpha = _empty((rows, k), torch.float32, W)
-    _check(lib().amq_quantize_weights(W.data_ptr(), rows, cols, W.stride(0), k, T, planes.data_ptr(),
-                                      alpha.data_ptr(), _stream()))
+    if final_ls:
+        _check(lib().amq_quantize_weights_ex(W.data_ptr(), rows, cols, W.stride(0), k, T, QUANT_FINAL_LS,
+                                             planes.data_ptr(), alpha.data_ptr(), _stream()))
+    else:
+        _check(lib().amq_quantize_weights(W.data_ptr(), rows, cols, W.stride(0), k, T, planes.data_ptr(),
+                                          alpha.data_ptr(), _stream()))
     return planes, alpha
 
 
@@ -378,3 +390,40 @@ def relative_mse(W, planes, alpha):
                                   _dev(alpha, torch.float32), row_err.data_ptr(), row_norm.data_ptr(),
                                   result.data_ptr(), _stream()))
     return result, row_err, row_norm
+
+
+def dequantize(planes, alpha, cols, out=None):
+    """Reconstruction [rows, cols] float32 of a row-wise quantization (planes [k, rows, wpr], alpha [rows, k])."""
+    k, rows, _ = planes.shape
+    if out is None:
+        out = _empty((rows, cols), torch.float32, planes)
+    if out.dim() != 2 or out.stride(1) != 1 or out.dtype != torch.float32 or not out.is_cuda:
+        raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
+    _check(lib().amq_dequantize(_dev(planes, torch.int32), _dev(alpha, torch.float32), rows, cols, k, out.data_ptr(),
+                                out.stride(0), _stream()))
+    return out
+
+
+def clip_(w, lo=-1.0, hi=1.0):
+    """Clips a contiguous float32 GPU tensor to [lo, hi] in place."""
+    _check(lib().amq_clip(_dev(w, torch.float32), w.numel(), lo, hi, _stream()))
+    return w
+
+
+class _FakeQuantize(torch.autograd.Function):
+    """w -> w_hat = sum_i alpha_i b_i (row-wise alternating quantization) with the straight-through
+    gradient of Sec. 4: d f / d w = d f / d w_hat.  Both directions are argument marshalling: the
+    forward pass is two library calls, the backward pass returns its argument."""
+
+    @staticmethod
+    def forward(ctx, W, k, T):
+        planes, alpha = quantize_weights(W.detach().contiguous(), k, T)
+        return dequantize(planes, alpha, W.shape[1])
+
+    @staticmethod
+    def backward(ctx, grad):
+        return grad, None, None
+
+
+def fake_quantize(W, k, T=2):
+    return _FakeQuantize.apply(W, k, T)

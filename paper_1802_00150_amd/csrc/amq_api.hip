@@ -436,6 +436,31 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
 }
 
+int amq_quantize_weights_ex(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T, int flags,
+                            uint32_t* planes, float* alpha, void* stream) {
+  if (flags & ~AMQ_QUANT_FINAL_LS) return AMQ_ERR_INVALID;
+  int st = quantize_common(W, rows, cols, ld, k, T, planes, alpha, amq::kQuantFull, stream);
+  if (st != AMQ_OK || !(flags & AMQ_QUANT_FINAL_LS)) return st;
+  // the trailing coefficient update is the staged Eq. 5 pass on the codes just written (a second
+  // launch, so that the main kernel carries no code for it)
+  return quantize_common(W, rows, cols, ld, k, 1, planes, alpha, amq::kQuantLsOnly, stream);
+}
+
+int amq_dequantize(const uint32_t* planes, const float* alpha, int64_t rows, int64_t cols, int k, float* out,
+                   int64_t ld_out, void* stream) {
+  if (!planes || !alpha || !out) return AMQ_ERR_INVALID;
+  if (!bits_ok(k) || rows <= 0 || cols <= 0 || ld_out < cols) return AMQ_ERR_INVALID;
+  if (cols > (1 << 30) || rows > (1LL << 33)) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_dequantize(planes, alpha, rows, (int)cols, k, out, ld_out,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+int amq_clip(float* w, int64_t n, float lo, float hi, void* stream) {
+  if (!w || n <= 0 || !(lo <= hi)) return AMQ_ERR_INVALID;
+  if (n > (1LL << 39)) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_clip(w, n, lo, hi, static_cast<hipStream_t>(stream)));
+}
+
 int amq_quantize_refined_greedy(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, uint32_t* planes,
                                 float* alpha, void* stream) {
   if (!W || !planes || !alpha) return AMQ_ERR_INVALID;

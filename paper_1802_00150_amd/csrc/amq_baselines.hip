@@ -1,5 +1,6 @@
-// The comparison quantizer of Sec. 2 (refined greedy approximation) and the relative mean squared
-// error of Tables 1-2, on gfx950.  Same vector layout and reductions as the alternating quantizer
+// The comparison quantizer of Sec. 2 (refined greedy approximation), the relative mean squared
+// error of Tables 1-2, and the training-side helpers of Sec. 4 (reconstruction of the quantized
+// weights for the forward pass, clipping of the full-precision weights), on gfx950.  Same vector layout and reductions as the alternating quantizer
 // (amq_quantize_core.h): one wavefront or one 4-wave workgroup per vector, the vector in registers.
 #include "amq_launch.h"
 #include "amq_quantize_core.h"
@@ -217,7 +218,59 @@ __global__ __launch_bounds__(1024) void relmse_final_kernel(const double* row_er
   }
 }
 
+// ---- training-side helpers (Sec. 4, "Training") ------------------------------------------------
+// One wavefront per row: out[r][l] = binary32 left-to-right sum of +-alpha[r][i].
+template <int K>
+__global__ __launch_bounds__(256) void dequantize_kernel(const uint32_t* planes, const float* alpha, long long rows,
+                                                         int cols, float* out, long long ld_out) {
+  const long long row = (long long)blockIdx.x * 4 + wave_id();
+  if (row >= rows) return;
+  const int lane = lane_id();
+  const int wpr = 4 * ((cols + 127) >> 7);
+  float al[K];
+#pragma unroll
+  for (int i = 0; i < K; ++i) al[i] = alpha[row * K + i];
+  for (int l0 = 0; l0 < cols; l0 += 64) {
+    const int l = l0 + lane;
+    float v = 0.0f;
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      // the 64 entries of this round are two words of the plane; every lane reads the one it needs
+      const uint32_t word = planes[((long long)i * rows + row) * wpr + (l0 >> 5) + (lane >> 5)];
+      const float term = ((word >> (lane & 31)) & 1u) ? al[i] : -al[i];
+      v = (i == 0) ? term : v + term;
+    }
+    if (l < cols) out[row * ld_out + l] = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void clip_kernel(float* w, long long n, float lo, float hi) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    const float v = w[i];
+    w[i] = v < lo ? lo : (v > hi ? hi : v);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_dequantize(const uint32_t* planes, const float* alpha, long long rows, int cols, int k, float* out,
+                             long long ld_out, hipStream_t s) {
+  const dim3 grid((unsigned)((rows + 3) / 4));
+  switch (k) {
+    case 1: hipLaunchKernelGGL(dequantize_kernel<1>, grid, dim3(256), 0, s, planes, alpha, rows, cols, out, ld_out); break;
+    case 2: hipLaunchKernelGGL(dequantize_kernel<2>, grid, dim3(256), 0, s, planes, alpha, rows, cols, out, ld_out); break;
+    case 3: hipLaunchKernelGGL(dequantize_kernel<3>, grid, dim3(256), 0, s, planes, alpha, rows, cols, out, ld_out); break;
+    case 4: hipLaunchKernelGGL(dequantize_kernel<4>, grid, dim3(256), 0, s, planes, alpha, rows, cols, out, ld_out); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_clip(float* w, long long n, float lo, float hi, hipStream_t s) {
+  hipLaunchKernelGGL(clip_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w, n, lo, hi);
+  return hipGetLastError();
+}
 
 hipError_t launch_refined_greedy(const float* X, long long ld, int n, int count, int k, uint32_t* planes, float* coef,
                                  hipStream_t s) {

@@ -53,6 +53,12 @@ hipError_t launch_relative_mse(const float* W, long long rows, int cols, long lo
                                const float* alpha, double* row_err, double* row_norm, double* result,
                                hipStream_t s);
 
+// Reconstruction out[r][l] = sum_i +-alpha[r][i] (the binary32 code-table value of the entry's code).
+hipError_t launch_dequantize(const uint32_t* planes, const float* alpha, long long rows, int cols, int k, float* out,
+                             long long ld_out, hipStream_t s);
+// In-place clipping of n values to [lo, hi].
+hipError_t launch_clip(float* w, long long n, float lo, float hi, hipStream_t s);
+
 // ---- binary products -------------------------------------------------------------------
 struct GemmOperand {
   const uint32_t* Wp;   // [k_w][m][wpr]

@@ -84,6 +84,12 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_relative_mse(p, 4, 4, 4, 2, p, p, p, p, null, None) == INVALID
     assert L.amq_relative_mse(p, 0, 4, 4, 2, p, p, p, p, p, None) == INVALID
     assert L.amq_relative_mse(p, 4, 4, 2, 2, p, p, p, p, p, None) == INVALID
+    assert L.amq_quantize_weights_ex(p, 4, 4, 4, 2, 2, 4, p, p, None) == INVALID        # unknown flag
+    assert L.amq_quantize_weights_ex(null, 4, 4, 4, 2, 2, 1, p, p, None) == INVALID
+    assert L.amq_dequantize(p, p, 4, 8, 2, p, 4, None) == INVALID                       # ld_out < cols
+    assert L.amq_dequantize(p, null, 4, 8, 2, p, 8, None) == INVALID
+    assert L.amq_clip(null, C.c_int64(4), C.c_float(-1.0), C.c_float(1.0), None) == INVALID
+    assert L.amq_clip(p, C.c_int64(4), C.c_float(1.0), C.c_float(-1.0), None) == INVALID  # lo > hi
     # language-model entry points
     assert L.amq_embedding_lookup(p, p, 10, 8, 2, null, 1, p, p, None) == INVALID
     assert L.amq_embedding_lookup(p, p, 0, 8, 2, p, 1, p, p, None) == INVALID

@@ -122,3 +122,68 @@ def test_method_order_on_gpu_matches_the_tables(amq):
                 assert abs(got - ref) <= 1e-5 * ref
                 vals.append(got)
             assert vals[0] > vals[1] > vals[2]
+
+
+@pytest.mark.parametrize("rows,n,k,T", [(9, 300, 2, 2), (33, 1024, 3, 2), (3, 129, 4, 1), (1200, 600, 2, 2), (5, 4096, 3, 0),
+                                        (4, 70, 1, 2)])
+def test_quantize_final_ls(amq, rows, n, k, T):
+    from gpu_util import compare_codes
+    g = np.random.default_rng(rows + n + k + T)
+    W = (g.standard_normal((rows, n)) * 0.05).astype(np.float32)
+    say("final_ls rows=%d n=%d k=%d T=%d" % (rows, n, k, T))
+    pr, ar = oracle.quantize_rows_final_ls(W, k, T)
+    p0, a0 = oracle.quantize_rows(W, k, T)           # (the codes are those of the plain algorithm)
+    pg, ag = amq.quantize_weights(to_dev(W), k, T, final_ls=True)
+    flips, flipped_rows = compare_codes(W, planes_host(pg), pr, a0)
+    assert flips == 0
+    assert_coef_close(host(ag), ar, "alpha")
+
+
+def test_quantize_weights_ex_rejects_unknown_flags(amq):
+    import torch
+    W = torch.zeros((2, 64), device="cuda:0")
+    planes = torch.zeros((2, 2, 4), dtype=torch.int32, device="cuda:0")
+    alpha = torch.zeros((2, 2), device="cuda:0")
+    L = amq.binding.lib()
+    assert L.amq_quantize_weights_ex(W.data_ptr(), 2, 64, 64, 2, 2, 2, planes.data_ptr(), alpha.data_ptr(), None) == 1
+
+
+@pytest.mark.parametrize("rows,n,k", [(7, 300, 2), (130, 1024, 3), (3, 129, 4), (1, 5000, 1), (1200, 600, 2), (2, 64, 3)])
+def test_dequantize(amq, rows, n, k):
+    import torch
+    g = np.random.default_rng(rows * 3 + n + k)
+    W = (g.standard_normal((rows, n)) * 0.05).astype(np.float32)
+    planes, alpha = oracle.quantize_rows(W, k, 2)
+    say("dequantize rows=%d n=%d k=%d" % (rows, n, k))
+    ref = oracle.dequantize(planes, alpha, n)
+    got = amq.dequantize(to_dev(planes), to_dev(alpha), n)
+    assert np.array_equal(host(got), ref)          # single binary32 operations in the same order: bit-exact
+    # into a strided destination
+    big = torch.full((rows, n + 37), 7.0, device="cuda:0")
+    amq.dequantize(to_dev(planes), to_dev(alpha), n, out=big[:, 5:5 + n])
+    b = host(big)
+    assert np.array_equal(b[:, 5:5 + n], ref) and (b[:, :5] == 7.0).all() and (b[:, 5 + n:] == 7.0).all()
+
+
+def test_clip(amq):
+    g = np.random.default_rng(4)
+    w = (g.standard_normal(100003) * 2.0).astype(np.float32)
+    d = to_dev(w)
+    amq.clip_(d)
+    assert np.array_equal(host(d), oracle.clip(w))
+    d = to_dev(w)
+    amq.clip_(d, -0.25, 0.5)
+    assert np.array_equal(host(d), oracle.clip(w, -0.25, 0.5))
+
+
+def test_fake_quantize_forward_and_straight_through_gradient(amq):
+    import torch
+    g = np.random.default_rng(5)
+    W = (g.standard_normal((40, 300)) * 0.05).astype(np.float32)
+    Wd = to_dev(W).requires_grad_(True)
+    What = amq.fake_quantize(Wd, 2, 2)
+    planes, alpha = oracle.quantize_rows(W, 2, 2)
+    assert np.array_equal(host(What.detach()), oracle.dequantize(planes, alpha, 300))
+    G = to_dev((g.standard_normal((40, 300))).astype(np.float32))
+    (What * G).sum().backward()
+    assert np.array_equal(host(Wd.grad), host(G))   # d f / d w = d f / d w_hat
