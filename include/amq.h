@@ -185,6 +185,24 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                  float* h_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * GRU step in the original form of the cell (the reset gate multiplies the previous state
+ * before the candidate's hidden-side product):
+ *   r = sigmoid(ax_r + ah_r), z = sigmoid(ax_z + ah_z),
+ *   n = tanh(ax_n + Wh_n q(r * h_prev) + bias_h_n),  h = (1 - z) * n + z * h_prev,
+ * ax = Wx q(x) + bias_x, ah = Wh q(h_prev) + bias_h, q = on-line quantization (k_a bits, T cycles).
+ * r * h_prev is quantized on line like any activation: a second quantization and a second,
+ * dependent product per step (which amq_gru_step avoids).  Arguments as amq_gru_step; h_out must not
+ * alias h_prev; g_out [B][H] (nullable) receives r * h_prev (for step-by-step parity checks);
+ * workspace at least amq_gru_reset_before_workspace_bytes(I, H, B, k_a) bytes.
+ */
+size_t amq_gru_reset_before_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a);
+int amq_gru_step_reset_before(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                              const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias_x,
+                              const float* bias_h, const float* x, const float* h_prev, int64_t B,
+                              int k_a, int T, float* h_out, float* g_out, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
  * amq_quantize_weights with options.  AMQ_QUANT_FINAL_LS adds one more coefficient update
  * (Eq. 5) after the last code assignment, so that the coefficients returned are the
  * least-squares optimum for the codes returned (Alg. 2 as printed ends with the codes).

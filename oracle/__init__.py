@@ -64,6 +64,8 @@ def lib():
         L.amq_oracle_refined_greedy_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p]
         L.amq_oracle_relative_mse.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p, _f64p, _f64p]
         L.amq_oracle_relative_mse.restype = C.c_double
+        L.amq_oracle_gru_step_rb.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
+                                             C.c_void_p, _f32p, _f32p, _i64, _int, _int, C.c_void_p, _f32p, _f32p]
         L.amq_oracle_gamma.argtypes = [C.c_double] * 4
         L.amq_oracle_gamma.restype = C.c_double
         _lib = L
@@ -329,6 +331,24 @@ def relative_mse(W, planes, alpha):
     row_norm = np.zeros(rows, np.float64)
     ratio = lib().amq_oracle_relative_mse(W, rows, cols, cols, k, planes, _f32(alpha), row_err, row_norm)
     return float(ratio), row_err, row_norm
+
+
+def gru_step_reset_before(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T, g=None,
+                          return_g=False):
+    """g (optional): use this r * h_prev instead of computing it.  return_g: also return the one used."""
+    Wxp = np.ascontiguousarray(Wxp, np.uint32)
+    Whp = np.ascontiguousarray(Whp, np.uint32)
+    k_w = Wxp.shape[0]
+    x, h_prev = _f32(x), _f32(h_prev)
+    B = x.shape[0]
+    h = np.zeros((B, H), np.float32)
+    bx_a, bx_p = _opt(bias_x)
+    bh_a, bh_p = _opt(bias_h)
+    g_a, g_p = _opt(g)
+    g_used = np.zeros((B, H), np.float32)
+    lib().amq_oracle_gru_step_rb(Wxp, _f32(alpha_x), Whp, _f32(alpha_h), I, H, k_w, bx_p, bh_p, x, h_prev,
+                                 B, k_a, T, g_p, g_used, h)
+    return (h, g_used) if return_g else h
 
 
 def gamma(m, n, k_w, k_h):

@@ -27,7 +27,8 @@
  * embedding lookup against quantizing the looked-up row; the log-softmax
  * against a library routine, the two-class closed form and normalisation;
  * the output layer against a dense fp64 layer on de-quantized operands;
- * the trailing-least-squares variant against a library least-squares routine;
+ * the reset-before GRU against a dense fp64 cell and against the reset-after
+ * cell when the reset gate is saturated; the trailing-least-squares variant against a library least-squares routine;
  * the reconstruction against the code table and a dense product; refined
  * greedy against a library least-squares routine stage by stage; the
  * relative error against a norm computed by a library; the operation-count
@@ -531,6 +532,48 @@ void amq_oracle_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32
     }
   free(ax);
   free(ah);
+}
+
+/* ------------------------------------------------------------------ *
+ * GRU step in the original form of the cell, where the reset gate multiplies
+ * the previous state before the candidate's hidden-side product:
+ *   r = sigmoid(ax_r + ah_r), z = sigmoid(ax_z + ah_z),
+ *   n = tanh(ax_n + (Wh_n q(r * h_prev) + bias_h_n)),  h = (1 - z) * n + z * h_prev,
+ * with ax = Wx q(x) + bias_x, ah = Wh q(h_prev) + bias_h (rows r, z), q = on-line
+ * quantization (k_a bits, T cycles).  r * h_prev is a stored binary32 vector
+ * and is quantized on line like any other activation: a second quantization
+ * and a second, dependent product per step.
+ * g_in (nullable): use this r * h_prev instead of computing it (staged checks);
+ * g_out (nullable): receives the r * h_prev that was used.
+ * ------------------------------------------------------------------ */
+void amq_oracle_gru_step_rb(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                            const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias_x,
+                            const float* bias_h, const float* x, const float* h_prev, int64_t B,
+                            int k_a, int T, const float* g_in, float* g_out, float* h_out) {
+  int64_t m = 3 * H;
+  double* ax = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  double* ah = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  double* ag = (double*)malloc(sizeof(double) * (size_t)B * (size_t)m);
+  float* g = (float*)malloc(sizeof(float) * (size_t)B * (size_t)H);
+  preact(Wxp, alpha_x, m, I, k_w, x, B, k_a, T, bias_x, ax);
+  preact(Whp, alpha_h, m, H, k_w, h_prev, B, k_a, T, bias_h, ah);
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t u = 0; u < H; ++u) {
+      double r = sigmoid(ax[b * m + u] + ah[b * m + u]);
+      g[b * H + u] = g_in ? g_in[b * H + u] : (float)(r * (double)h_prev[b * H + u]);
+      if (g_out) g_out[b * H + u] = g[b * H + u];
+    }
+  preact(Whp, alpha_h, m, H, k_w, g, B, k_a, T, bias_h, ag);
+  for (int64_t b = 0; b < B; ++b)
+    for (int64_t u = 0; u < H; ++u) {
+      double z = sigmoid(ax[b * m + H + u] + ah[b * m + H + u]);
+      double nn = tanh(ax[b * m + 2 * H + u] + ag[b * m + 2 * H + u]);
+      h_out[b * H + u] = (float)((1.0 - z) * nn + z * (double)h_prev[b * H + u]);
+    }
+  free(ax);
+  free(ah);
+  free(ag);
+  free(g);
 }
 
 /* ------------------------------------------------------------------ *

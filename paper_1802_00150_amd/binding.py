@@ -24,6 +24,7 @@ EXPORTS = [
     "amq_lm_workspace_bytes", "amq_lm_step",
     "amq_quantize_refined_greedy", "amq_relative_mse",
     "amq_quantize_weights_ex", "amq_dequantize", "amq_clip",
+    "amq_gru_reset_before_workspace_bytes", "amq_gru_step_reset_before",
 ]
 
 _lib = None
@@ -76,6 +77,10 @@ def lib():
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
         L.amq_relative_mse.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p]
+        L.amq_gru_reset_before_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.amq_gru_reset_before_workspace_bytes.restype = _sz
+        L.amq_gru_step_reset_before.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
+                                                _p, _sz, _p]
         L.amq_quantize_weights_ex.argtypes = [_p, _i64, _i64, _i64, _int, _int, _int, _p, _p, _p]
         L.amq_dequantize.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p]
         L.amq_clip.argtypes = [_p, _i64, C.c_float, C.c_float, _p]
@@ -275,6 +280,25 @@ def lstm_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias, xs, h, c, k_a, T, ws=N
                                    None if hs is None else _dev(hs, torch.float32), ws.data_ptr(),
                                    ws.numel(), _stream()))
     return h, c
+
+
+def gru_step_reset_before(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T, ws=None, h_out=None,
+                          g_out=None):
+    """GRU step with the reset gate applied to the previous state before the candidate's product.
+    g_out [B, H] (optional) receives r * h_prev."""
+    k_w = Wxp.shape[0]
+    B = x.shape[0]
+    if ws is None:
+        ws = torch.empty(int(lib().amq_gru_reset_before_workspace_bytes(I, H, B, k_a)), dtype=torch.uint8,
+                         device=x.device)
+    if h_out is None:
+        h_out = torch.empty_like(h_prev)
+    _check(lib().amq_gru_step_reset_before(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
+                                           _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, k_w,
+                                           _opt(bias_x), _opt(bias_h), _dev(x, torch.float32),
+                                           _dev(h_prev, torch.float32), B, k_a, T, _dev(h_out, torch.float32),
+                                           _opt(g_out), ws.data_ptr(), ws.numel(), _stream()))
+    return h_out
 
 
 def lstm_sequence_abandoned(ws, I, H, B, k_a):

@@ -436,6 +436,72 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
 }
 
+// Workspace of the reset-before GRU step: that of amq_gru_step, then a third pre-activation
+// buffer and g = r * h_prev.
+struct GruRbWs {
+  StepWs base;
+  float* pre2;
+  float* g;
+  size_t total;
+};
+static GruRbWs carve_gru_rb(void* ws, int64_t I, int64_t H, int64_t B, int k_a) {
+  GruRbWs w;
+  w.base = carve(ws, I, H, B, k_a, 3, 2);
+  char* p = static_cast<char*>(ws);
+  size_t off = w.base.total;
+  w.pre2 = reinterpret_cast<float*>(p ? p + off : nullptr);
+  off += up256(sizeof(float) * (size_t)B * 3 * H);
+  w.g = reinterpret_cast<float*>(p ? p + off : nullptr);
+  off += up256(sizeof(float) * (size_t)B * H);
+  w.total = off;
+  return w;
+}
+
+size_t amq_gru_reset_before_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve_gru_rb(nullptr, I, H, B, k_a).total;
+}
+
+int amq_gru_step_reset_before(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                              int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h,
+                              const float* x, const float* h_prev, int64_t B, int k_a, int T, float* h_out,
+                              float* g_out, void* workspace, size_t workspace_bytes, void* stream) {
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve_gru_rb(nullptr, I, H, B, k_a).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out, workspace,
+                      workspace_bytes, need);
+  if (st != AMQ_OK) return st;
+  GruRbWs w = carve_gru_rb(workspace, I, H, B, k_a);
+  if (g_out) w.g = g_out;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{x, I, (int)I, (int)B, w.base.xp, w.base.beta_x};
+  q.seg[1] = amq::QuantSeg{h_prev, H, (int)H, (int)B, w.base.hp, w.base.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.base.xp, w.base.beta_x, B, k_a, bias_x, 0, w.base.pre0);
+  st = run_product(gx, s);
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gh = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.base.hp, w.base.beta_h, B, k_a, bias_h, 0, w.base.pre1);
+  st = run_product(gh, s);
+  if (st != AMQ_OK) return st;
+  st = hip_status(amq::launch_gru_rb_reset(w.base.pre0, w.base.pre1, h_prev, w.g, B, H, s));
+  if (st != AMQ_OK) return st;
+  // g = r * h_prev is quantized on line like any activation (its codes reuse the buffer of h's),
+  // and the whole hidden-side product is formed again; only its candidate rows are used
+  amq::QuantArgs qg{};
+  qg.seg[0] = amq::QuantSeg{w.g, H, (int)H, (int)B, w.base.hp, w.base.beta_h};
+  qg.T = T;
+  qg.mode = amq::kQuantFull;
+  st = hip_status(amq::launch_quantize(qg, k_a, s));
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gg = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.base.hp, w.base.beta_h, B, k_a, bias_h, 0, w.pre2);
+  st = run_product(gg, s);
+  if (st != AMQ_OK) return st;
+  return hip_status(amq::launch_gru_rb_final(w.base.pre0, w.base.pre1, w.pre2, h_prev, h_out, B, H, s));
+}
+
 int amq_quantize_weights_ex(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, int T, int flags,
                             uint32_t* planes, float* alpha, void* stream) {
   if (flags & ~AMQ_QUANT_FINAL_LS) return AMQ_ERR_INVALID;

@@ -40,7 +40,47 @@ __global__ __launch_bounds__(256) void gru_pointwise_kernel(const float* __restr
   h_out[t] = fmaf(z, h_prev[t] - nn, nn);  // (1 - z) * n + z * h_prev
 }
 
+// GRU in the original form (reset gate applied to the previous state before the candidate's
+// hidden-side product): first the reset gate and g = r * h_prev, later the rest of the cell.
+__global__ __launch_bounds__(256) void gru_rb_reset_kernel(const float* __restrict__ pre_x,
+                                                           const float* __restrict__ pre_h, const float* h_prev,
+                                                           float* g_out, long long B, long long H) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= B * H) return;
+  const long long b = t / H, u = t - b * H;
+  const float r = sigmoidf_dev(pre_x[b * 3 * H + u] + pre_h[b * 3 * H + u]);
+  g_out[t] = r * h_prev[t];
+}
+
+__global__ __launch_bounds__(256) void gru_rb_final_kernel(const float* __restrict__ pre_x,
+                                                           const float* __restrict__ pre_h,
+                                                           const float* __restrict__ pre_g, const float* h_prev,
+                                                           float* h_out, long long B, long long H) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= B * H) return;
+  const long long b = t / H, u = t - b * H;
+  const float z = sigmoidf_dev(pre_x[b * 3 * H + H + u] + pre_h[b * 3 * H + H + u]);
+  const float nn = tanhf_dev(pre_x[b * 3 * H + 2 * H + u] + pre_g[b * 3 * H + 2 * H + u]);
+  h_out[t] = fmaf(z, h_prev[t] - nn, nn);
+}
+
 }  // namespace
+
+hipError_t launch_gru_rb_reset(const float* pre_x, const float* pre_h, const float* h_prev, float* g_out, long long B,
+                               long long H, hipStream_t s) {
+  const long long total = B * H;
+  hipLaunchKernelGGL(gru_rb_reset_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pre_x, pre_h,
+                     h_prev, g_out, B, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_gru_rb_final(const float* pre_x, const float* pre_h, const float* pre_g, const float* h_prev,
+                               float* h_out, long long B, long long H, hipStream_t s) {
+  const long long total = B * H;
+  hipLaunchKernelGGL(gru_rb_final_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pre_x, pre_h,
+                     pre_g, h_prev, h_out, B, H);
+  return hipGetLastError();
+}
 
 hipError_t launch_lstm_pointwise(const float* pre, const float* c_prev, float* h_out, float* c_out,
                                  float* hs_out, long long B, long long H, hipStream_t s) {

@@ -179,5 +179,11 @@ hipError_t launch_lstm_pointwise(const float* pre /*[B][4H]*/, const float* c_pr
                                  hipStream_t s);
 hipError_t launch_gru_pointwise(const float* pre_x /*[B][3H]*/, const float* pre_h, const float* h_prev,
                                 float* h_out, long long B, long long H, hipStream_t s);
+// GRU with the reset gate applied before the candidate's hidden-side product: g = r * h_prev, then
+// (with pre_g = Wh q(g) + bias_h) the rest of the cell
+hipError_t launch_gru_rb_reset(const float* pre_x, const float* pre_h, const float* h_prev, float* g_out, long long B,
+                               long long H, hipStream_t s);
+hipError_t launch_gru_rb_final(const float* pre_x, const float* pre_h, const float* pre_g, const float* h_prev,
+                               float* h_out, long long B, long long H, hipStream_t s);
 
 }  // namespace amq

@@ -90,6 +90,10 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_dequantize(p, null, 4, 8, 2, p, 8, None) == INVALID
     assert L.amq_clip(null, C.c_int64(4), C.c_float(-1.0), C.c_float(1.0), None) == INVALID
     assert L.amq_clip(p, C.c_int64(4), C.c_float(1.0), C.c_float(-1.0), None) == INVALID  # lo > hi
+    need_rb = L.amq_gru_reset_before_workspace_bytes(8, 8, 1, 2)
+    assert need_rb > L.amq_gru_workspace_bytes(8, 8, 1, 2)
+    assert L.amq_gru_step_reset_before(p, p, p, p, 8, 8, 2, None, None, p, p, 1, 2, 2, p, None, ws, need_rb - 1, None) == INVALID
+    assert L.amq_gru_step_reset_before(p, p, p, p, 8, 8, 2, None, None, p, null, 1, 2, 2, p, None, ws, need_rb, None) == INVALID
     # language-model entry points
     assert L.amq_embedding_lookup(p, p, 10, 8, 2, null, 1, p, p, None) == INVALID
     assert L.amq_embedding_lookup(p, p, 0, 8, 2, p, 1, p, p, None) == INVALID

@@ -196,6 +196,43 @@ def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
     assert_vec_close(host(dc), c, "c final")
 
 
+@pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (1024, 512, 9, 2, 2),
+                                           (200, 136, 21, 2, 3), (1024, 1024, 37, 3, 3), (1500, 1100, 5, 2, 2)])
+def test_gru_step_reset_before(amq, I, H, B, k_w, k_a):
+    g = np.random.default_rng(I + H + B + 2)
+    Wx = (g.standard_normal((3 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((3 * H, H)) * 0.08).astype(np.float32)
+    bx = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    bh = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    x = g.standard_normal((B, I)).astype(np.float32)
+    h = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    d = [to_dev(t) for t in (Wxp, ax, Whp, ah)]
+    import torch
+    for b1, b2 in ((None, None), (bx, bh)):
+        say("gru reset-before I=%d H=%d B=%d bias=%s" % (I, H, B, b1 is not None))
+        h_ref, g_ref = oracle.gru_step_reset_before(Wxp, ax, Whp, ah, I, H, b1, b2, x, h, k_a, 2, return_g=True)
+        g_g = torch.empty((B, H), device="cuda:0")
+        h_g = amq.gru_step_reset_before(*d, I, H, None if b1 is None else to_dev(b1),
+                                        None if b2 is None else to_dev(b2), to_dev(x), to_dev(h), k_a, 2, g_out=g_g)
+        # stage 1: r * h_prev within tolerance
+        assert_vec_close(host(g_g), g_ref, "r * h")
+        # stage 2: the rest of the cell, the oracle fed the GPU's own r * h (so that both quantize the
+        # same vector: a last-digit difference in r * h may move an entry across a code boundary, which
+        # legitimately shifts that row's coefficients by O(1/H))
+        h_fed = oracle.gru_step_reset_before(Wxp, ax, Whp, ah, I, H, b1, b2, x, h, k_a, 2, g=host(g_g))
+        assert_vec_close(host(h_g), h_fed, "h given r * h")
+        # end to end: rows whose r * h quantizes identically on both sides (same codes, and same
+        # coefficients -- a flip in an earlier cycle can leave the final codes equal) must agree
+        pg, ag = oracle.quantize_rows(host(g_g), k_a, 2)
+        pr, ar = oracle.quantize_rows(g_ref, k_a, 2)
+        same = ~(pg != pr).any(axis=(0, 2)) & (np.abs(ag - ar).max(axis=1) <= 1e-5 * np.abs(ar).max(axis=1))
+        say("  rows whose r * h quantizes identically: %d of %d" % (same.sum(), B))
+        assert same.sum() >= B - max(2, B // 8)
+        assert_vec_close(host(h_g)[same], h_ref[same], "h end to end")
+
+
 @pytest.mark.parametrize("I,H,B,k_w,k_a,steps", [(64, 48, 5, 2, 2, 4), (300, 200, 17, 3, 3, 5), (130, 1000, 33, 2, 3, 3),
                                                  (1024, 1024, 64, 3, 3, 3), (100, 64, 20, 2, 2, 70),
                                                  (513, 129, 2, 1, 4, 3), (1024, 1024, 48, 2, 2, 2)])

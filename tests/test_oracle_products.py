@@ -166,3 +166,46 @@ def test_threads_do_not_change_results():
     p4, a4 = oracle.quantize_rows(W, 3, 2)
     oracle.set_threads(1)
     assert np.array_equal(p1, p4) and np.array_equal(a1, a4)
+
+
+def _dq(planes, alpha, n):
+    k, rows, w = planes.shape
+    bits = np.unpackbits(planes.view(np.uint8).reshape(k, rows, w * 4), axis=-1, bitorder="little")[..., :n]
+    return np.einsum("krn,rk->rn", bits.astype(np.float64) * 2 - 1, alpha.astype(np.float64))
+
+
+def test_gru_reset_before_matches_dense_cell_on_dequantized_operands():
+    g = np.random.default_rng(31)
+    I, H, B, k = 40, 24, 3, 2
+    Wx = (g.standard_normal((3 * H, I)) * 0.2).astype(np.float32)
+    Wh = (g.standard_normal((3 * H, H)) * 0.2).astype(np.float32)
+    bx = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    bh = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    x = g.standard_normal((B, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    Wxp, ax = oracle.quantize_rows(Wx, k, 2)
+    Whp, ah = oracle.quantize_rows(Wh, k, 2)
+    h1 = oracle.gru_step_reset_before(Wxp, ax, Whp, ah, I, H, bx, bh, x, h0, k, 2)
+    Wxd, Whd = _dq(Wxp, ax, I), _dq(Whp, ah, H)
+    q = lambda v: _dq(*oracle.quantize_rows(v, k, 2), v.shape[1])
+    sig = lambda t: 1.0 / (1.0 + np.exp(-t))
+    a_x = q(x) @ Wxd.T + bx
+    a_h = q(h0) @ Whd.T + bh
+    r = sig(a_x[:, :H] + a_h[:, :H])
+    z = sig(a_x[:, H:2 * H] + a_h[:, H:2 * H])
+    gvec = (r * h0).astype(np.float32)
+    a_g = q(gvec) @ Whd.T + bh
+    n = np.tanh(a_x[:, 2 * H:] + a_g[:, 2 * H:])
+    ref = (1 - z) * n + z * h0
+    assert np.allclose(h1, ref, rtol=1e-6, atol=1e-6)
+    # it is not the reset-after cell in general ...
+    h_after = oracle.gru_step(Wxp, ax, Whp, ah, I, H, bx, bh, x, h0, k, 2)
+    assert np.abs(h1 - h_after).max() > 1e-3
+    # ... but coincides with it when the reset gate is saturated at 1 (r * h = h exactly, and with
+    # zero hidden-side bias on the candidate rows r * (U h) = U h)
+    bx2, bh2 = bx.copy(), bh.copy()
+    bx2[:H] = 60.0
+    bh2[2 * H:] = 0.0
+    a = oracle.gru_step_reset_before(Wxp, ax, Whp, ah, I, H, bx2, bh2, x, h0, k, 2)
+    b = oracle.gru_step(Wxp, ax, Whp, ah, I, H, bx2, bh2, x, h0, k, 2)
+    assert np.allclose(a, b, rtol=0, atol=1e-7)
