@@ -269,10 +269,17 @@ def bench_lm(amq, dev, B, steps, warmup):
         state["t"] = t + 1
 
     ms = wall_time_ms(step, steps, warmup)
+    # the same as whole 35-step sequences through one call
+    ids35 = torch.from_numpy(inputs.language_model(steps=35, B=B)["ids"]).to(dev)
+    wsq = torch.empty(int(amq.binding.lib().amq_lm_sequence_workspace_bytes(E, H, V, B, k, k)), dtype=torch.uint8,
+                      device=dev)
+    lp35 = torch.empty((35, B, V), device=dev)
+    ms_seq = wall_time_ms(lambda: amq.lm_sequence(Ep, ae, E, Wxp, ax, Whp, ah, H, None, Wsp, as_, bs, ids35, h, c, k, k,
+                                                  T, ws=wsq, logprob=lp35), 10, 2) / 35
     ws2 = amq.softmax_layer_workspace(V, H, B, k, dev)
     ms_layer = event_time_ms(lambda: amq.softmax_layer(Wsp, as_, H, bs, h, k, T, ws=ws2, logprob=logprob), 200, 20)
     ms_lsm = event_time_ms(lambda: amq.log_softmax(logprob, out=logprob), 200, 20)
-    return ms, ms_layer, ms_lsm
+    return ms, ms_layer, ms_lsm, ms_seq
 
 
 def bench_relative_mse(amq, dev):
@@ -433,8 +440,9 @@ def main():
         # full language-model step at the paper's large shape: embedding lookup, LSTM 1024, output layer
         # 42000 x 1024 with log-softmax, W2/A2
         for b in (1, 64):
-            ms, ms_layer, ms_lsm = bench_lm(amq, dev, b, 300, 30)
+            ms, ms_layer, ms_lsm, ms_seq = bench_lm(amq, dev, b, 300, 30)
             also["lm_h1024_v42000_w2a2_b%d_steps_per_s" % b] = 1e3 / ms
+            also["lm_h1024_v42000_w2a2_b%d_sequence_call_steps_per_s" % b] = 1e3 / ms_seq
             also["lm_output_layer_42000x1024_b%d_us" % b] = ms_layer * 1e3
             also["lm_log_softmax_42000_b%d_us" % b] = ms_lsm * 1e3
 

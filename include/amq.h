@@ -288,6 +288,23 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
                 const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as,
                 int T, float* logprob, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * `steps` consecutive language-model steps in one call: ids [steps][B], logprob [steps][B][V];
+ * h and c [B][H] are read as the initial state and overwritten with the final state.  Same
+ * arithmetic as `steps` calls of amq_lm_step.  For B = 1 (with E, H <= 1024 and 2- or 3-bit codes)
+ * the recurrence runs in one launch per 64 steps (see amq_lstm_sequence, including its residency
+ * requirement and its flag word: amq_lstm_sequence_flag_offset(E, H, 1, k_a) applies to this
+ * workspace too) and the output layer then takes all h_t of those steps as one batch.
+ *   workspace: at least amq_lm_sequence_workspace_bytes(E, H, V, B, k_a, k_as) bytes, 256-byte aligned.
+ */
+size_t amq_lm_sequence_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as);
+int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E,
+                    const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                    int64_t H, int k_w, const float* bias, const uint32_t* Wsp, const float* alpha_s,
+                    int64_t V, int k_ws, const float* bias_s, const int64_t* ids, int64_t steps, float* h,
+                    float* c, int64_t B, int k_a, int k_as, int T, float* logprob, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

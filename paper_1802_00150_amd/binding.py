@@ -21,7 +21,7 @@ EXPORTS = [
     "amq_lstm_sequence_flag_offset",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
-    "amq_lm_workspace_bytes", "amq_lm_step",
+    "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
     "amq_quantize_refined_greedy", "amq_relative_mse",
     "amq_quantize_weights_ex", "amq_dequantize", "amq_clip",
     "amq_gru_reset_before_workspace_bytes", "amq_gru_step_reset_before",
@@ -75,6 +75,10 @@ def lib():
         L.amq_lm_workspace_bytes.argtypes, L.amq_lm_workspace_bytes.restype = [_i64, _i64, _i64, _i64, _int, _int], _sz
         L.amq_lm_step.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
+        L.amq_lm_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int]
+        L.amq_lm_sequence_workspace_bytes.restype = _sz
+        L.amq_lm_sequence.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
+                                      _p, _i64, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
         L.amq_relative_mse.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p]
         L.amq_gru_reset_before_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
@@ -386,6 +390,27 @@ def lm_step(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, b
                              _dev(alpha_s, torch.float32), V, k_ws, _opt(bias_s), _dev(ids, torch.int64),
                              _dev(h, torch.float32), _dev(c, torch.float32), B, k_a, k_as, T,
                              _dev(logprob, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
+    return logprob
+
+
+def lm_sequence(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, bias_s, ids, h, c, k_a, k_as, T,
+                ws=None, logprob=None):
+    """ids [steps, B] -> logprob [steps, B, V]; h, c [B, H] updated in place."""
+    vocab = Ep.shape[1]
+    k_w = Wxp.shape[0]
+    k_ws, V, _ = Wsp.shape
+    steps, B = ids.shape
+    if ws is None:
+        ws = torch.empty(int(lib().amq_lm_sequence_workspace_bytes(E, H, V, B, k_a, k_as)), dtype=torch.uint8,
+                         device=h.device)
+    if logprob is None:
+        logprob = _empty((steps, B, V), torch.float32, h)
+    _check(lib().amq_lm_sequence(_dev(Ep, torch.int32), _dev(alpha_e, torch.float32), vocab, E,
+                                 _dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                                 _dev(alpha_h, torch.float32), H, k_w, _opt(bias), _dev(Wsp, torch.int32),
+                                 _dev(alpha_s, torch.float32), V, k_ws, _opt(bias_s), _dev(ids, torch.int64), steps,
+                                 _dev(h, torch.float32), _dev(c, torch.float32), B, k_a, k_as, T,
+                                 _dev(logprob, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
     return logprob
 
 

@@ -624,6 +624,37 @@ int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int6
                               static_cast<hipStream_t>(stream));
 }
 
+// The launches of one language-model step on carved workspaces (arguments already validated).
+static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                          const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                          const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                          const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as,
+                          int T, float* logprob, const StepWs& w, const SoftmaxWs& sw, hipStream_t s) {
+  int st;
+  // h_{t-1} quantized on line and x_t looked up in the quantized embedding, one launch
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  q.gather = amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids), (int)E, (int)B, w.xp,
+                            w.beta_x};
+  st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, bias, w.xp, w.beta_x, w.hp, w.beta_h, c, B, k_a,
+                         h, c, nullptr, s);
+  if (st < 0) {
+    amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, E, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
+    st = run_product(gx, s);
+    if (st != AMQ_OK) return st;
+    amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
+    st = run_product(gh, s);
+    if (st != AMQ_OK) return st;
+    st = hip_status(amq::launch_lstm_pointwise(w.pre0, c, h, c, nullptr, B, H, s));
+  }
+  if (st != AMQ_OK) return st;
+  return softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, h, B, k_as, T, logprob, sw, s);
+}
+
 size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
   if (E <= 0 || H <= 0 || V <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
   return carve(nullptr, E, H, B, k_a, 4, 1).total + carve_softmax(nullptr, V, H, B, k_as).total;
@@ -648,28 +679,86 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
   StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
   SoftmaxWs sw = carve_softmax(static_cast<char*>(workspace) + need_step, V, H, B, k_as);
 
-  // h_{t-1} quantized on line and x_t looked up in the quantized embedding, one launch
-  amq::QuantArgs q{};
-  q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
-  q.T = T;
-  q.mode = amq::kQuantFull;
-  q.gather = amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids), (int)E, (int)B, w.xp,
-                            w.beta_x};
-  st = hip_status(amq::launch_quantize(q, k_a, s));
+  return lm_step_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
+                        ids, h, c, B, k_a, k_as, T, logprob, w, sw, s);
+}
+
+// Workspace of amq_lm_sequence: that of a step, then every h_t of a piece of the sequence and the
+// output layer's workspace for as many rows (batch 1: pieces of kSeqGMaxSteps steps go through the
+// output layer together).
+struct LmSeqWs {
+  size_t step_bytes;
+  float* hs;
+  size_t soft_off;
+  int soft_batch;
+  size_t total;
+};
+static LmSeqWs carve_lm_seq(void* ws, int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
+  LmSeqWs w;
+  char* base = static_cast<char*>(ws);
+  w.step_bytes = carve(nullptr, E, H, B, k_a, 4, 1).total;
+  size_t off = w.step_bytes;
+  w.hs = reinterpret_cast<float*>(base ? base + off : nullptr);
+  w.soft_batch = (int)(B == 1 ? amq::kSeqGMaxSteps : B);
+  if (B == 1) off += up256(sizeof(float) * amq::kSeqGMaxSteps * (size_t)H);
+  w.soft_off = off;
+  off += carve_softmax(nullptr, V, H, w.soft_batch, k_as).total;
+  w.total = off;
+  return w;
+}
+
+size_t amq_lm_sequence_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
+  if (E <= 0 || H <= 0 || V <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
+  return carve_lm_seq(nullptr, E, H, V, B, k_a, k_as).total;
+}
+
+int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                    const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                    const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                    const float* bias_s, const int64_t* ids, int64_t steps, float* h, float* c, int64_t B, int k_a,
+                    int k_as, int T, float* logprob, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !c || !logprob || steps <= 0) return AMQ_ERR_INVALID;
+  if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
+  const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
+  const size_t need = sizes_ok ? carve_lm_seq(nullptr, E, H, V, B, k_a, k_as).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, ids, h, B, k_a, T, h, workspace, workspace_bytes,
+                      need);
   if (st != AMQ_OK) return st;
-  st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, bias, w.xp, w.beta_x, w.hp, w.beta_h, c, B, k_a,
-                         h, c, nullptr, s);
-  if (st < 0) {
-    amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, E, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
-    st = run_product(gx, s);
-    if (st != AMQ_OK) return st;
-    amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
-    st = run_product(gh, s);
-    if (st != AMQ_OK) return st;
-    st = hip_status(amq::launch_lstm_pointwise(w.pre0, c, h, c, nullptr, B, H, s));
+  if (!aligned(Wsp, 16) || !aligned(Ep, 16)) return AMQ_ERR_INVALID;
+  if (V > (1LL << 31) || steps >= (1 << 30)) return AMQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LmSeqWs lw = carve_lm_seq(workspace, E, H, V, B, k_a, k_as);
+  StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
+  char* soft_base = static_cast<char*>(workspace) + lw.soft_off;
+  if (B == 1 && amq::lstm_seqg_supported(E, H, B, k_w, k_a) && grid_fits_device()) {
+    // batch 1: per piece of at most kSeqGMaxSteps steps, look all inputs up (the table the sequence
+    // kernel reads its input codes from), run the recurrence in one launch over the chip, then put
+    // every h_t of the piece through the output layer together, as a batch
+    for (int64_t t0 = 0; t0 < steps; t0 += amq::kSeqGMaxSteps) {
+      const int n = (int)(steps - t0 < amq::kSeqGMaxSteps ? steps - t0 : amq::kSeqGMaxSteps);
+      amq::QuantArgs q{};
+      q.mode = amq::kQuantFull;
+      q.gather = amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids + t0), (int)E, n, w.xq,
+                                w.xbeta};
+      st = hip_status(amq::launch_quantize(q, k_a, s));
+      if (st != AMQ_OK) return st;
+      amq::SeqGArgs g{Wxp, alpha_x, Whp, alpha_h, (int)E, (int)H, bias, nullptr, n, h, c, lw.hs, T, 0, w.sync, w.hbuf,
+                      w.xq, w.xbeta};
+      st = hip_status(amq::launch_lstm_seqg(g, k_w, k_a, s));
+      if (st != AMQ_OK) return st;
+      SoftmaxWs sw = carve_softmax(soft_base, V, H, n, k_as);
+      st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, n, k_as, T, logprob + t0 * V, sw, s);
+      if (st != AMQ_OK) return st;
+    }
+    return AMQ_OK;
   }
-  if (st != AMQ_OK) return st;
-  return softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, h, B, k_as, T, logprob, sw, s);
+  SoftmaxWs sw = carve_softmax(soft_base, V, H, B, k_as);
+  for (int64_t t = 0; t < steps; ++t) {
+    st = lm_step_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
+                        ids + t * B, h, c, B, k_a, k_as, T, logprob + t * B * V, w, sw, s);
+    if (st != AMQ_OK) return st;
+  }
+  return AMQ_OK;
 }
 
 }  // extern "C"

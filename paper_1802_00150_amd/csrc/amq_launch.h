@@ -156,7 +156,7 @@ struct SeqGArgs {
   const float* ah;      // [4H][k_w]
   int I, H;
   const float* bias;    // [4H] or null
-  const float* xs;      // [steps][I]
+  const float* xs;      // [steps][I], or null: xq / xbeta already hold the codes of the inputs
   int steps;            // at most kSeqGMaxSteps
   float* h;             // [H] in: h_0, out: h_steps
   float* c;             // [H] in: c_0, out: c_steps
@@ -166,8 +166,8 @@ struct SeqGArgs {
   // scratch in global memory (the caller's workspace)
   unsigned* sync;       // give-up flag (left non-zero if the launch was abandoned), then kSeqGMaxGrid arrival bytes
   unsigned long long* hbuf;  // [2][H]: h_t as published by the grid, {value, step tag} pairs, double-buffered
-  uint32_t* xq;         // [steps][k_a][wpr(I)]: codes of the inputs
-  float* xbeta;         // [steps][4]: their coefficients
+  uint32_t* xq;         // [k_a][steps][wpr(I)]: codes of the inputs (operand layout)
+  float* xbeta;         // [steps][k_a]: their coefficients
 };
 bool lstm_seqg_supported(long long I, long long H, long long B, int k_w, int k_a);
 hipError_t launch_lstm_seqg(SeqGArgs a, int k_w, int k_a, hipStream_t s);

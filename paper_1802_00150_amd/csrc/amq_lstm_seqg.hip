@@ -243,21 +243,24 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
   }
 
   // ---- inputs of all time steps of this launch, quantized ahead by the workgroups in turn
-  for (int t = blockIdx.x; t < a.steps; t += gridDim.x) {
+  // (with a.xs null the table has been filled by an earlier launch: the embedding lookup of a
+  // language model, whose inputs arrive already quantized)
+  for (int t = blockIdx.x; a.xs && t < a.steps; t += gridDim.x) {
     quantize_wg<KA, false>(a.xs + (long long)t * I, 0, a.sync, I, a.T, xq, bx, sh, phase);
     __syncthreads();
-    for (int i = tid; i < KA * wprI; i += 64 * kGWaves) put_u(a.xq + (long long)t * KA * wprI + i, xq[i]);
-    if (tid < KA) put_f(a.xbeta + t * 4 + tid, bx[tid]);
+    for (int i = tid; i < KA * wprI; i += 64 * kGWaves)
+      put_u(a.xq + ((long long)(i / wprI) * a.steps + t) * wprI + i % wprI, xq[i]);
+    if (tid < KA) put_f(a.xbeta + t * KA + tid, bx[tid]);
     __syncthreads();
   }
-  bool alive = grid_barrier(a.sync, 1);
+  bool alive = a.xs ? grid_barrier(a.sync, 1) : true;
 
   // codes of x_0 (KA * wpr(I) <= 128 words: one per thread); those of x_{t+1} are requested while
   // the grid is still working on step t
   uint32_t xnext = 0;
   float bxnext = 0.0f;
   if (alive) {
-    if (tid < KA * wprI) xnext = get_u(a.xq + tid);
+    if (tid < KA * wprI) xnext = get_u(a.xq + (long long)(tid / wprI) * a.steps * wprI + tid % wprI);
     if (tid < KA) bxnext = get_f(a.xbeta + tid);
   }
   for (int t = 0; t < a.steps && alive; ++t) {
@@ -312,8 +315,8 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
       if (a.hs) a.hs[(long long)t * H + unit] = hlast;
     }
     if (t + 1 < a.steps) {
-      if (tid < KA * wprI) xnext = get_u(a.xq + (long long)(t + 1) * KA * wprI + tid);
-      if (tid < KA) bxnext = get_f(a.xbeta + (t + 1) * 4 + tid);
+      if (tid < KA * wprI) xnext = get_u(a.xq + ((long long)(tid / wprI) * a.steps + t + 1) * wprI + tid % wprI);
+      if (tid < KA) bxnext = get_f(a.xbeta + (t + 1) * KA + tid);
     }
     __syncthreads();  // xq / hq / bx / bh are rewritten at the top of the next step
   }

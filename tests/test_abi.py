@@ -118,6 +118,13 @@ def test_validation_rejects_before_touching_the_device(L):
     assert lm(vocab=0) == INVALID
     assert lm(k_ws=5) == INVALID
     assert lm(k_as=0) == INVALID
+    need_q = L.amq_lm_sequence_workspace_bytes(8, 8, 16, 1, 2, 3)
+    assert need_q > need_l
+    lmq = lambda **kw: L.amq_lm_sequence(p, p, 10, 8, p, p, p, p, 8, 2, None, p, p, 16, 2, None, kw.get("ids", p),
+                                         kw.get("steps", 3), p, p, 1, 2, 3, 2, p, ws, kw.get("bytes", need_q), None)
+    assert lmq(bytes=need_q - 1) == INVALID
+    assert lmq(steps=0) == INVALID
+    assert lmq(ids=null) == INVALID
 
 
 def test_binding_refuses_cpu_tensors():

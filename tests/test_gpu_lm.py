@@ -160,3 +160,33 @@ def test_lm_step_full_size(amq, B):
         assert_vec_close(host(dh), h1, "h")
         assert_vec_close(host(got), lp, "logprob")
         h, c = h1, c1
+
+
+@pytest.mark.parametrize("E,H,V,B,k,k_ws,k_as,steps", [(300, 300, 10000, 1, 2, 2, 3, 5), (128, 256, 1000, 1, 3, 3, 3, 70),
+                                                       (40, 24, 130, 3, 2, 2, 2, 4), (200, 136, 555, 20, 2, 3, 2, 3),
+                                                       (1024, 1024, 42000, 1, 2, 2, 2, 3)])
+def test_lm_sequence(amq, E, H, V, B, k, k_ws, k_as, steps):
+    """Whole sequences through one call (batch 1: the recurrence in one launch over the chip, the
+    output layer on all steps of a piece together) against the oracle's step-by-step loop."""
+    import torch
+    cfg = inputs.language_model(trial=E + B + steps, steps=steps, B=B, H=H, E=E, vocab=V, k=k)
+    q = lm_setup(cfg, k_ws)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    ref = []
+    for t in range(steps):
+        h, c, lp = lm_oracle_step(q, cfg["ids"][t], h, c, k_as)
+        ref.append(lp)
+    say("lm sequence E=%d H=%d V=%d B=%d steps=%d" % (E, H, V, B, steps))
+    dh = torch.zeros((B, H), device="cuda:0")
+    dc = torch.zeros((B, H), device="cuda:0")
+    out = torch.full((steps, B, V), float("nan"), device="cuda:0")
+    amq.lm_sequence(dq["Ep"], dq["ae"], E, dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], H, dq["bias"], dq["Wsp"],
+                    dq["as"], dq["bs"], torch.from_numpy(np.ascontiguousarray(cfg["ids"])).to("cuda:0"), dh, dc, k,
+                    k_as, 2, logprob=out)
+    got = host(out)
+    for t in range(steps):
+        assert_vec_close(got[t], ref[t], "logprob step %d" % t)
+    assert_vec_close(host(dh), h, "h final")
+    assert_vec_close(host(dc), c, "c final")
