@@ -31,8 +31,8 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T integer lane-ops/s: 256 C
 FP4_MFMA_PEAK_TFLOPS = 10100.0               # dense fp4 matrix cores
 # HBM bytes per launch of the streamed W2/A2 GEMV from the rocprofv3 counter runs summarised in
 # profiles/gemv_streamed_4096x1024.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (scale factors from a plain
-# 512 MiB device copy) = (2 x 270909.0 + 8192.4) KiB
-GEMV_TRAFFIC_BYTES = (2 * 270909.0 + 8192.4) * 1024
+# 512 MiB device copy) = (2 x 270913.6 + 8192.6) KiB
+GEMV_TRAFFIC_BYTES = (2 * 270913.6 + 8192.6) * 1024
 
 
 def dv(a, dev):
