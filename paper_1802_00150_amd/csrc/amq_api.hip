@@ -108,9 +108,12 @@ amq::GemmArgs gemm_args(const uint32_t* Wp, const float* alpha, int64_t m, int64
   return g;
 }
 
-// Matrix-core product: fp4 kernel when the vectors fit one 1024-entry chunk, int8 kernel otherwise.
+// Matrix-core product: fp4 kernel when the vectors fit one 1024-entry chunk (its several-tiles-per-wave
+// form for large plain products), int8 kernel otherwise.
 hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, hipStream_t s,
                               int* lse_slots = nullptr) {
+  if (epi == amq::kEpiStore && amq::mfma4w_supported(b, k_w, k_a))
+    return amq::launch_mfma4w(b, k_w, k_a, s, lse_slots);
   if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s, lse_slots);
   if (lse_slots) *lse_slots = 0;
   return amq::launch_mfma(b, k_w, k_a, epi, s);

@@ -137,6 +137,10 @@ hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t 
 // fp4 matrix-core kernel for vectors of at most 1024 entries (the fast path)
 bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
+// the same instruction with several batch tiles per wave: plain products with many rows and
+// at least 32 columns (store mode only)
+bool mfma4w_supported(const BmvArgs& a, int k_w, int k_a);
+hipError_t launch_mfma4w(const BmvArgs& a, int k_w, int k_a, hipStream_t s, int* lse_slots = nullptr);
 
 // ---- output layer -----------------------------------------------------------------------
 // out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])); out may alias Y.

@@ -1,0 +1,429 @@
+// Large batched binary matrix products on the fp4 matrix cores of gfx950 (Fig. 3 right), plain
+// outputs only: Y = (sum_i alpha_i B_i)(sum_j beta_j x_j) for many rows and 32 or more columns.
+//
+// Same arithmetic and operand formats as the kernel in amq_mfma4.hip ({0, 1} codes as E2M1 nibbles,
+// v_mfma_scale_f32_16x16x128_f8f6f4, +-1 dot products recovered from popcounts), different work
+// split.  There a wave owns one 16 x 16 output tile per pass, and per pass it spends about 350
+// vector instructions (1400 cycles) on addressing, expanding the weight words, popcounts and the
+// coefficient epilogue against k_w k_a 8 matrix instructions (900 cycles at W2/A3): the vector
+// unit, not the matrix core, bounds it.  Here a wave owns 16 rows x NBT batch tiles, so that
+// everything on the weight side (loads, expansion, popcounts, row coefficients) is paid once per
+// NBT tiles and only the per-output epilogue grows with the tile count.  A workgroup of 8 waves
+// stages NBT * 16 batch entries (all planes) in LDS once and its waves walk over row blocks.
+#include "amq_device.h"
+#include "amq_launch.h"
+
+namespace amq {
+
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kTileB = 16;   // batch entries per tile
+constexpr int kSteps = 8;    // 1024 entries / 128 per MFMA
+constexpr int kWaves = 8;
+constexpr unsigned kNib = 0x22222222u;
+constexpr int kScaleOne = 0x7f7f7f7f;  // E8M0 exponent 127 = 2^0 in every byte
+constexpr int kPlaneBytes = kSteps * kTileB * 64;  // 8 KiB: [step][batch entry][k-block][16 B]
+
+// bit p of a packed word -> nibble 0b0010 (1.0 in E2M1) or 0; nibble q of dword s is bit 4q + s
+__device__ __forceinline__ uint4 expand4(uint32_t w) {
+  return make_uint4((w << 1) & kNib, w & kNib, (w >> 1) & kNib, (w >> 2) & kNib);
+}
+// fp4 operands occupy the first four of the eight operand registers
+__device__ __forceinline__ v8i as_operand(uint4 e) {
+  const v4i lo = {(int)e.x, (int)e.y, (int)e.z, (int)e.w};
+  return __builtin_shufflevector(lo, lo, 0, 1, 2, 3, -1, -1, -1, -1);
+}
+__device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
+  const uint4 v = q[t >> 2];
+  return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
+}
+
+template <int KW, int KA, int NBT>
+__global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_per_wg, int rowblocks) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int kGroupB = NBT * kTileB;               // batch entries per workgroup
+  constexpr int kItems = NBT * KA * kTileB * 8;       // 16-byte groups of packed activation words
+  constexpr int kIter = (kItems + 64 * kWaves - 1) / (64 * kWaves);
+  unsigned char* btile = smem;                                           // [tile][plane][kPlaneBytes]
+  int* pops = reinterpret_cast<int*>(smem + NBT * KA * kPlaneBytes);     // [tile][plane][kTileB]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, l4 = lane >> 4;
+  const int bg0 = blockIdx.y * kGroupB;
+  const int batch = a.batch;
+  const int m = (int)a.m;
+  const int nlen = a.blk[0].n;
+  const int wq = (nlen + 127) >> 7;  // 16-byte groups per row
+  const uint4* Wp4 = reinterpret_cast<const uint4*>(a.blk[0].Wp);
+  const float* alpha = a.blk[0].alpha;
+  const int rb_first = blockIdx.x * rb_per_wg;
+  int rb_end = rb_first + rb_per_wg;
+  if (rb_end > rowblocks) rb_end = rowblocks;
+
+  // ---- prologue: packed activation words, 16 bytes per thread and round, coalesced.  Item e:
+  // group q = e % 8 of the row of batch entry (e / 8) % kGroupB of plane e / (8 kGroupB).
+  {
+    const uint4* Xp4 = reinterpret_cast<const uint4*>(a.blk[0].Xp);
+    uint4 xw[kIter];
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+      const int e = tid + it * 64 * kWaves;
+      const int q = e & 7, nn = (e >> 3) % kGroupB, j = (e >> 3) / kGroupB;
+      const bool valid = e < kItems && bg0 + nn < batch && q < wq;
+      const int bb = bg0 + nn < batch ? bg0 + nn : batch - 1;
+      const uint4 v = Xp4[((e < kItems ? j : 0) * batch + bb) * wq + (q < wq ? q : 0)];
+      xw[it] = valid ? v : make_uint4(0, 0, 0, 0);
+    }
+    if (tid < NBT * KA * kTileB) pops[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+      const int e = tid + it * 64 * kWaves;
+      if (e < kItems) {
+        const int q = e & 7, nn = (e >> 3) % kGroupB, j = (e >> 3) / kGroupB;
+        const int bt = nn >> 4, n16 = nn & 15;
+        const uint4 w4 = xw[it];
+        const int pc = __popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w);
+        if (pc) atomicAdd(&pops[(bt * KA + j) * kTileB + n16], pc);
+        // words 4q .. 4q+3 of the row: k-block q >> 1, steps 4 * (q & 1) + 0..3
+        uint4* dst = reinterpret_cast<uint4*>(btile + (bt * KA + j) * kPlaneBytes +
+                                              ((4 * (q & 1)) * kTileB + n16) * 64 + (q >> 1) * 16);
+        dst[0 * kTileB * 4] = expand4(w4.x);
+        dst[1 * kTileB * 4] = expand4(w4.y);
+        dst[2 * kTileB * 4] = expand4(w4.z);
+        dst[3 * kTileB * 4] = expand4(w4.w);
+      }
+    }
+    __syncthreads();
+  }
+
+  // per batch column of this lane (one per tile): sum_j beta_j and sum_j beta_j (n - 2 popc(x_j)),
+  // and the separate beta_j for the contraction part
+  int bcol[NBT];
+  bool bok[NBT];
+  float btv[NBT][KA], sb[NBT], sbcx[NBT];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt) {
+    bcol[bt] = bg0 + bt * kTileB + l16;
+    bok[bt] = bcol[bt] < batch;
+    const int bc = bok[bt] ? bcol[bt] : batch - 1;
+    sb[bt] = 0.0f;
+    sbcx[bt] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < KA; ++j) {
+      btv[bt][j] = a.blk[0].beta[bc * KA + j];
+      const float cx = (float)(nlen - 2 * pops[(bt * KA + j) * kTileB + l16]);
+      sb[bt] += btv[bt][j];
+      sbcx[bt] = fmaf(btv[bt][j], cx, sbcx[bt]);
+    }
+  }
+
+  float lse_m[NBT], lse_s[NBT];  // running (max, sum exp) of this lane's outputs, per tile
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt) {
+    lse_m[bt] = kLseLow;
+    lse_s[bt] = 0.0f;
+  }
+  float* const lse_part = a.lse_part;
+  const unsigned char* tile = btile + l16 * 64 + l4 * 16;
+
+  for (int rb = rb_first + wv; rb < rb_end; rb += kWaves) {
+    // ---- weight side of the row block, shared by all tiles
+    // A-operand view: lane = (tile row l16, k-block l4)
+    const int wrow_a = rb * 16 + l16;
+    const bool wok = wrow_a < m;
+    uint4 araw[KW][2];
+    {
+      const int base = (wok ? wrow_a : 0) * wq;
+      const int plane = m * wq;
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+          const int g = 2 * l4 + v;
+          const uint4 t4 = Wp4[base + i * plane + (g < wq ? g : 0)];
+          araw[i][v] = (wok && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // C view: rows 4 * l4 + r
+    int crow0 = rb * 16 + 4 * l4;
+    bool cok[4];
+    float alr[4][KW], bias[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      cok[r] = crow0 + r < m;
+      const int cr = cok[r] ? crow0 + r : 0;
+#pragma unroll
+      for (int i = 0; i < KW; ++i) alr[r][i] = alpha[cr * KW + i];
+      bias[r] = a.bias0 ? a.bias0[cr] : 0.0f;
+    }
+    // 2 popc of every weight row plane: this lane's 8 words, the four k-blocks of the row (lanes
+    // 16 apart), then fetched for the rows of the C view; folded with the row coefficients into
+    // pa = sum_i alpha_i 2 popc(w_i) and sa = sum_i alpha_i
+    float pa[4], sa[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      pa[r] = 0.0f;
+      sa[r] = 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < KW; ++i) {
+      int pc = 0;
+#pragma unroll
+      for (int v = 0; v < 2; ++v)
+        pc += __popc(araw[i][v].x) + __popc(araw[i][v].y) + __popc(araw[i][v].z) + __popc(araw[i][v].w);
+      pc += __shfl_xor(pc, 16, kWave);
+      pc += __shfl_xor(pc, 32, kWave);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float pw2 = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
+        pa[r] = fmaf(alr[r][i], pw2, pa[r]);
+        sa[r] += alr[r][i];
+      }
+    }
+
+    // ---- contraction: units u = (k-step t, tile bt); the LDS reads (and, when the step changes,
+    // the weight expansion) of unit u + 1 are issued under the matrix instructions of unit u
+    v4f acc[NBT][KW][KA];
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) acc[bt][i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+    uint4 bop[KA], bnx[KA], aop[KW], anx[KW];
+#pragma unroll
+    for (int j = 0; j < KA; ++j) bop[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes);
+#pragma unroll
+    for (int i = 0; i < KW; ++i) aop[i] = expand4(word_of(araw[i], 0));
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < kSteps * NBT; ++u) {
+      const int t = u / NBT, bt = u % NBT;
+      const int tn = (u + 1) / NBT, bn = (u + 1) % NBT;
+      if (u + 1 < kSteps * NBT) {
+#pragma unroll
+        for (int j = 0; j < KA; ++j)
+          bnx[j] = *reinterpret_cast<const uint4*>(tile + (bn * KA + j) * kPlaneBytes + tn * kTileB * 64);
+        if (bn == 0) {
+#pragma unroll
+          for (int i = 0; i < KW; ++i) anx[i] = expand4(word_of(araw[i], tn));
+        }
+      }
+      (void)t;
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j)
+          acc[bt][i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(aop[i]), as_operand(bop[j]),
+                                                                           acc[bt][i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
+      __builtin_amdgcn_sched_group_barrier(0x100, KA, 0);
+#pragma unroll
+      for (int g = 0; g < KW * KA; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < KA; ++j) bop[j] = bnx[j];
+      if (bn == 0) {
+#pragma unroll
+        for (int i = 0; i < KW; ++i) aop[i] = anx[i];
+      }
+    }
+    // An MFMA reads its operands from all 64 lanes, but the compiler treats it as lane-local and
+    // would sink it into the divergent branches that guard the stores below, where lanes of padded
+    // batch columns -- which still supply weight rows -- are masked off.  Pin the accumulators
+    // here, in uniform control flow.
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[bt][i][j]));
+
+    // ---- epilogue per tile, lane = (batch column l16, row quad l4):
+    //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j)),  y = sum_i alpha_i sum_j beta_j d_ij
+    //     = 4 sum_i alpha_i (sum_j beta_j acc_ij) - pa sb + sa sbcx
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt) {
+      float yv[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float y = 0.0f;
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          float inner = 0.0f;
+#pragma unroll
+          for (int j = 0; j < KA; ++j) inner = fmaf(btv[bt][j], acc[bt][i][j][r], inner);
+          y = fmaf(alr[r][i], inner, y);
+        }
+        yv[r] = fmaf(4.0f, y, fmaf(sa[r], sbcx[bt], -pa[r] * sb[bt])) + bias[r];
+      }
+      if (bok[bt]) {
+        float* yp = a.Y + (long long)bcol[bt] * m + crow0;
+        if (a.accumulate) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (cok[r]) yv[r] += yp[r];
+        }
+        if ((m & 3) == 0 && cok[3]) {
+          // the four rows of this lane are consecutive in Y[b][.]: one aligned 16-byte store
+          *reinterpret_cast<float4*>(yp) = make_float4(yv[0], yv[1], yv[2], yv[3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (cok[r]) yp[r] = yv[r];
+        }
+      }
+      if (lse_part) {  // uniform: fold this row block's outputs into the running (max, sum)
+        float mx = lse_m[bt];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, cok[r] ? yv[r] : kLseLow);
+        float sm = lse_s[bt] * __expf(lse_m[bt] - mx);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm += cok[r] ? __expf(yv[r] - mx) : 0.0f;
+        lse_m[bt] = mx;
+        lse_s[bt] = sm;
+      }
+    }
+  }
+
+  if (lse_part) {  // uniform
+    // One slot per workgroup and batch column: every wave merges its four row quads (lanes 16
+    // apart) and leaves the pair in LDS (the staged activations are no longer needed once all
+    // waves are past their contractions); wave 0 merges the eight and writes.  A wave that had
+    // no row block contributes the neutral pair.
+    float2* xch = reinterpret_cast<float2*>(smem);  // [wave][tile][column]
+    __syncthreads();
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt) {
+      float mm = lse_m[bt], ss = lse_s[bt];
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float m2 = __shfl_xor(mm, o, kWave), s2 = __shfl_xor(ss, o, kWave);
+        lse_merge(mm, ss, m2, s2);
+      }
+      if (l4 == 0) xch[(wv * NBT + bt) * kTileB + l16] = make_float2(mm, ss);
+    }
+    __syncthreads();
+    if (tid < NBT * kTileB) {
+      const int b = bg0 + tid;  // tid = tile * 16 + column
+      float mm = kLseLow, ss = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float2 p = xch[w * NBT * kTileB + tid];
+        lse_merge(mm, ss, p.x, p.y);
+      }
+      if (b < batch) {
+        float* dst = lse_part + ((long long)b * a.lse_slots + blockIdx.x) * 2;
+        dst[0] = mm;
+        dst[1] = ss;
+      }
+    }
+  }
+}
+
+// Tiles per wave: as many as keep the accumulators within about 100 registers.
+constexpr int max_tiles(int kw, int ka) { return 24 / (kw * ka) > 4 ? 4 : 24 / (kw * ka); }
+
+template <int KW, int KA, int NBT>
+hipError_t launch_one(BmvArgs a, hipStream_t s, int* lse_slots) {
+  if constexpr (NBT > max_tiles(KW, KA) || NBT < 2) {
+    return hipErrorInvalidValue;
+  } else {
+    const int rowblocks = (int)((a.m + 15) / 16);
+    const int groups = (a.batch + NBT * kTileB - 1) / (NBT * kTileB);
+    // about one workgroup per compute unit (registers and the staged activations allow no second
+    // one); row blocks per workgroup in multiples of 4, so that its four SIMDs (waves w and w + 4
+    // share one) get the same number of passes
+    int splits = 256 / groups;
+    if (splits < 1) splits = 1;
+    int per = (rowblocks + splits - 1) / splits;
+    per = (per + 3) / 4 * 4;
+    if (per < kWaves) per = kWaves;
+    const size_t lds = (size_t)NBT * KA * kPlaneBytes + sizeof(int) * NBT * KA * kTileB;
+    static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
+    if (!configured) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4w_kernel<KW, KA, NBT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      configured = true;
+    }
+    dim3 grid((unsigned)((rowblocks + per - 1) / per), (unsigned)groups);
+    const long long slots = grid.x;  // one per workgroup of a batch group
+    if (slots > kLseMaxSlots || slots > a.lse_cap) a.lse_part = nullptr;
+    a.lse_slots = (int)slots;
+    if (lse_slots) *lse_slots = a.lse_part ? (int)slots : 0;
+    hipLaunchKernelGGL((mfma4w_kernel<KW, KA, NBT>), grid, dim3(64 * kWaves), lds, s, a, per, rowblocks);
+    return hipGetLastError();
+  }
+}
+
+template <int KW, int KA>
+hipError_t launch_tiles(const BmvArgs& a, int nbt, hipStream_t s, int* lse_slots) {
+  switch (nbt) {
+    case 2: return launch_one<KW, KA, 2>(a, s, lse_slots);
+    case 3: return launch_one<KW, KA, 3>(a, s, lse_slots);
+    case 4: return launch_one<KW, KA, 4>(a, s, lse_slots);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int KW>
+hipError_t launch_ka(const BmvArgs& a, int k_a, int nbt, hipStream_t s, int* lse_slots) {
+  switch (k_a) {
+    case 1: return launch_tiles<KW, 1>(a, nbt, s, lse_slots);
+    case 2: return launch_tiles<KW, 2>(a, nbt, s, lse_slots);
+    case 3: return launch_tiles<KW, 3>(a, nbt, s, lse_slots);
+    case 4: return launch_tiles<KW, 4>(a, nbt, s, lse_slots);
+  }
+  return hipErrorInvalidValue;
+}
+
+// Batch tiles per wave for this product: the register budget's maximum, lowered so that the
+// batch groups come out even (5 tiles -> 3 + 2 rather than 4 + 1).
+int tiles_per_wave(int k_w, int k_a, int batch) {
+  const int cap = max_tiles(k_w, k_a);
+  if (cap < 2) return 0;
+  const int tiles = (batch + kTileB - 1) / kTileB;
+  const int groups = (tiles + cap - 1) / cap;
+  const int nbt = (tiles + groups - 1) / groups;
+  return nbt < 2 ? 0 : nbt;
+}
+
+}  // namespace
+
+// Plain products (no integer hook) with vectors of at most 1024 entries, at least two batch tiles,
+// and enough row-block tasks to give every SIMD of the chip two of them; sizes whose element
+// offsets fit 32 bits.
+bool mfma4w_supported(const BmvArgs& a, int k_w, int k_a) {
+  if (a.D || a.groups > 1 || a.blk[0].n > 1024 || !a.Y) return false;
+  const int nbt = tiles_per_wave(k_w, k_a, a.batch);
+  if (nbt == 0) return false;
+  if (a.batch > 65535 * nbt * kTileB) return false;
+  if (a.m * 8 * k_w >= (1LL << 31)) return false;  // weight offsets in 16-byte units
+  if ((long long)a.batch * a.m >= (1LL << 31)) return false;
+  const long long rowblocks = (a.m + 15) / 16;
+  const long long groups = (a.batch + nbt * kTileB - 1) / (nbt * kTileB);
+  return rowblocks * groups >= 2048;
+}
+
+hipError_t launch_mfma4w(const BmvArgs& a, int k_w, int k_a, hipStream_t s, int* lse_slots) {
+  if (lse_slots) *lse_slots = 0;
+  const int nbt = tiles_per_wave(k_w, k_a, a.batch);
+  switch (k_w) {
+    case 1: return launch_ka<1>(a, k_a, nbt, s, lse_slots);
+    case 2: return launch_ka<2>(a, k_a, nbt, s, lse_slots);
+    case 3: return launch_ka<3>(a, k_a, nbt, s, lse_slots);
+    case 4: return launch_ka<4>(a, k_a, nbt, s, lse_slots);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace amq

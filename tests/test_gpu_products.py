@@ -68,6 +68,33 @@ def test_gemm_and_gemv(amq, k_w, k_a):
                 assert_vec_close(host(amq.binary_gemv(dW, dA, n, dX, dB, bias=dbias, Y=to_dev(Y0))), refa)
 
 
+@pytest.mark.parametrize("k_w,k_a,m,n,batch", [
+    (2, 2, 10930, 200, 130),    # 9 batch tiles in 3 groups of 3; rows ragged against 16 and against 4
+    (2, 3, 8500, 1024, 256),    # the projection's shape class: 4 groups of 4 tiles, last row block partial
+    (3, 3, 16404, 256, 100),    # 7 tiles in 4 groups of 2, last group half empty
+    (1, 4, 32770, 130, 33),     # one group of 3 tiles, the last with a single entry
+    (4, 2, 11000, 1000, 97),    # 7 tiles in 3 groups of 3
+])
+def test_gemm_many_rows_wide_batch(amq, k_w, k_a, m, n, batch):
+    # Plain products with thousands of row blocks and 32 or more columns take the matrix-core kernel
+    # that gives each wave several batch tiles; every output is checked, with bias and accumulation.
+    g = np.random.default_rng(7000 + 100 * k_w + 10 * k_a + batch)
+    say("wide gemm kw=%d ka=%d m=%d n=%d B=%d" % (k_w, k_a, m, n, batch))
+    Wp = rand_planes(g, k_w, m, n)
+    Xp = rand_planes(g, k_a, batch, n)
+    alpha = (np.abs(g.standard_normal((m, k_w))) * 0.02).astype(np.float32)
+    beta = np.abs(g.standard_normal((batch, k_a))).astype(np.float32)
+    bias = (g.standard_normal(m) * 0.1).astype(np.float32)
+    Y0 = g.standard_normal((batch, m)).astype(np.float32)
+    dW, dA, dX, dB, dbias = to_dev(Wp), to_dev(alpha), to_dev(Xp), to_dev(beta), to_dev(bias)
+    oracle.set_threads(oracle.host_threads())
+    ref = oracle.binary_gemm(Wp, alpha, n, Xp, beta)
+    refa = oracle.binary_gemm(Wp, alpha, n, Xp, beta, bias=bias, Y=Y0)
+    oracle.set_threads(1)
+    assert_vec_close(host(amq.binary_gemm(dW, dA, n, dX, dB)), ref)
+    assert_vec_close(host(amq.binary_gemm(dW, dA, n, dX, dB, bias=dbias, Y=to_dev(Y0))), refa)
+
+
 @pytest.mark.parametrize("batch", [1, 8, 64])
 @pytest.mark.parametrize("k", [2, 3])
 def test_config2_full_pipeline(amq, k, batch):
