@@ -432,6 +432,11 @@ def main():
         ms = bench_gemm_kernel(amq, dev, 10000, 1024, 2, 3, 256)
         also["projection_10000x1024_w2a3_b256_us"] = ms * 1e3
         also["projection_10000x1024_w2a3_b256_TFLOPs"] = 2.0 * 10000 * 1024 * 6 * 256 / (ms * 1e-3) / 1e12
+        # the same kernel where issue rate rather than the latency of one launch decides: batch 1024
+        for (m, k) in ((42000, 2), (16384, 3)):
+            ms = bench_gemm_kernel(amq, dev, m, 1024, k, k, 1024, iters=50)
+            also["gemm_%dx1024_w%da%d_b1024_us" % (m, k, k)] = ms * 1e3
+            also["gemm_%dx1024_w%da%d_b1024_TFLOPs" % (m, k, k)] = 2.0 * m * 1024 * k * k * 1024 / (ms * 1e-3) / 1e12
 
     if "gru" in sections:
         also["gru_b256_with_projection_steps_per_s"] = 1e3 / bench_gru(amq, dev, 100, 10)
