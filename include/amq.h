@@ -294,7 +294,10 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
  * arithmetic as `steps` calls of amq_lm_step.  For B = 1 (with E, H <= 1024 and 2- or 3-bit codes)
  * the recurrence runs in one launch per 64 steps (see amq_lstm_sequence, including its residency
  * requirement and its flag word: amq_lstm_sequence_flag_offset(E, H, 1, k_a) applies to this
- * workspace too) and the output layer then takes all h_t of those steps as one batch.
+ * workspace too) and the output layer then takes all h_t of those steps as one batch.  For larger
+ * B the recurrent halves of the steps run one after the other and the output layer takes the
+ * hidden states of about 4096 / B steps at a time (the inputs are given, so only the recurrence
+ * is serial); the workspace holds those hidden states.
  *   workspace: at least amq_lm_sequence_workspace_bytes(E, H, V, B, k_a, k_as) bytes, 256-byte aligned.
  */
 size_t amq_lm_sequence_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as);

@@ -584,7 +584,12 @@ static SoftmaxWs carve_softmax(void* ws, int64_t V, int64_t H, int64_t B, int k_
   w.beta = reinterpret_cast<float*>(base ? base + off : nullptr);
   off += up256(sizeof(float) * (size_t)B * k_a);
   w.lse_part = reinterpret_cast<float*>(base ? base + off : nullptr);
-  w.lse_cap = (int)(V + 64 < amq::kLseMaxSlots ? V + 64 : amq::kLseMaxSlots);
+  // pairs per batch entry: the small-batch kernel leaves one per wave (up to kLseMaxSlots), the
+  // matrix-core kernels one per wave or workgroup of a batch tile's share of the grid (fewer the
+  // more tiles there are); a launch that would need more leaves none and the stand-alone
+  // log-softmax runs instead
+  const int64_t cap = B <= amq::kBmvMaxBatch ? amq::kLseMaxSlots : B <= 64 ? 4096 : 1024;
+  w.lse_cap = (int)(V + 64 < cap ? V + 64 : cap);
   off += up256(sizeof(float) * 2 * (size_t)B * w.lse_cap);
   w.total = off;
   return w;
@@ -627,12 +632,12 @@ int amq_softmax_layer(const uint32_t* Wsp, const float* alpha_s, int64_t V, int6
                               static_cast<hipStream_t>(stream));
 }
 
-// The launches of one language-model step on carved workspaces (arguments already validated).
-static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
-                          const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
-                          const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
-                          const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as,
-                          int T, float* logprob, const StepWs& w, const SoftmaxWs& sw, hipStream_t s) {
+// The recurrent half of a language-model step: lookup + on-line quantization (one launch), then the
+// LSTM step; h and c are updated in place, hs_out (nullable) receives a copy of the new h.
+static int lm_recurrent_launch(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E,
+                               const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                               int64_t H, int k_w, const float* bias, const int64_t* ids, float* h, float* c,
+                               int64_t B, int k_a, int T, float* hs_out, const StepWs& w, hipStream_t s) {
   int st;
   // h_{t-1} quantized on line and x_t looked up in the quantized embedding, one launch
   amq::QuantArgs q{};
@@ -644,7 +649,7 @@ static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t voca
   st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
   st = lstm_fused_launch(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, bias, w.xp, w.beta_x, w.hp, w.beta_h, c, B, k_a,
-                         h, c, nullptr, s);
+                         h, c, hs_out, s);
   if (st < 0) {
     amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 4 * H, E, k_w, w.xp, w.beta_x, B, k_a, bias, 0, w.pre0);
     st = run_product(gx, s);
@@ -652,8 +657,19 @@ static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t voca
     amq::GemmArgs gh = gemm_args(Whp, alpha_h, 4 * H, H, k_w, w.hp, w.beta_h, B, k_a, nullptr, 1, w.pre0);
     st = run_product(gh, s);
     if (st != AMQ_OK) return st;
-    st = hip_status(amq::launch_lstm_pointwise(w.pre0, c, h, c, nullptr, B, H, s));
+    st = hip_status(amq::launch_lstm_pointwise(w.pre0, c, h, c, hs_out, B, H, s));
   }
+  return st;
+}
+
+// The launches of one language-model step on carved workspaces (arguments already validated).
+static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                          const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                          const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                          const float* bias_s, const int64_t* ids, float* h, float* c, int64_t B, int k_a, int k_as,
+                          int T, float* logprob, const StepWs& w, const SoftmaxWs& sw, hipStream_t s) {
+  int st = lm_recurrent_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, ids, h, c, B, k_a, T,
+                               nullptr, w, s);
   if (st != AMQ_OK) return st;
   return softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, h, B, k_as, T, logprob, sw, s);
 }
@@ -686,9 +702,15 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
                         ids, h, c, B, k_a, k_as, T, logprob, w, sw, s);
 }
 
+// Steps of a sequence whose hidden states go through the output layer together: as many as the
+// batch-1 sequence kernel takes per launch, otherwise as many as give about 4096 rows.
+static int64_t lm_piece_steps(int64_t B) {
+  if (B == 1) return amq::kSeqGMaxSteps;
+  return B >= 4096 ? 1 : 4096 / B;
+}
+
 // Workspace of amq_lm_sequence: that of a step, then every h_t of a piece of the sequence and the
-// output layer's workspace for as many rows (batch 1: pieces of kSeqGMaxSteps steps go through the
-// output layer together).
+// output layer's workspace for as many rows.
 struct LmSeqWs {
   size_t step_bytes;
   float* hs;
@@ -702,8 +724,8 @@ static LmSeqWs carve_lm_seq(void* ws, int64_t E, int64_t H, int64_t V, int64_t B
   w.step_bytes = carve(nullptr, E, H, B, k_a, 4, 1).total;
   size_t off = w.step_bytes;
   w.hs = reinterpret_cast<float*>(base ? base + off : nullptr);
-  w.soft_batch = (int)(B == 1 ? amq::kSeqGMaxSteps : B);
-  if (B == 1) off += up256(sizeof(float) * amq::kSeqGMaxSteps * (size_t)H);
+  w.soft_batch = (int)(lm_piece_steps(B) * B);
+  off += up256(sizeof(float) * (size_t)w.soft_batch * H);
   w.soft_off = off;
   off += carve_softmax(nullptr, V, H, w.soft_batch, k_as).total;
   w.total = off;
@@ -750,15 +772,27 @@ int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int
       st = hip_status(amq::launch_lstm_seqg(g, k_w, k_a, s));
       if (st != AMQ_OK) return st;
       SoftmaxWs sw = carve_softmax(soft_base, V, H, n, k_as);
+      if (lw.soft_off + sw.total > workspace_bytes) return AMQ_ERR_INVALID;  // (cannot happen: fewer rows need less)
       st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, n, k_as, T, logprob + t0 * V, sw, s);
       if (st != AMQ_OK) return st;
     }
     return AMQ_OK;
   }
-  SoftmaxWs sw = carve_softmax(soft_base, V, H, B, k_as);
-  for (int64_t t = 0; t < steps; ++t) {
-    st = lm_step_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
-                        ids + t * B, h, c, B, k_a, k_as, T, logprob + t * B * V, w, sw, s);
+  // The inputs are given (no step feeds on the outputs), so only the recurrence is serial: per
+  // piece, the recurrent halves of its steps one after the other, every h_t kept, then one pass
+  // of the output layer over all (step, batch entry) rows of the piece, which reads W_s once per
+  // piece instead of once per step and runs its product at a shape the matrix cores fill.
+  const int64_t piece = lm_piece_steps(B);
+  for (int64_t t0 = 0; t0 < steps; t0 += piece) {
+    const int64_t n = steps - t0 < piece ? steps - t0 : piece;
+    for (int64_t t = 0; t < n; ++t) {
+      st = lm_recurrent_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, ids + (t0 + t) * B, h,
+                               c, B, k_a, T, lw.hs + t * B * H, w, s);
+      if (st != AMQ_OK) return st;
+    }
+    SoftmaxWs sw = carve_softmax(soft_base, V, H, n * B, k_as);
+    if (lw.soft_off + sw.total > workspace_bytes) return AMQ_ERR_INVALID;  // (cannot happen: fewer rows need less)
+    st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, n * B, k_as, T, logprob + t0 * B * V, sw, s);
     if (st != AMQ_OK) return st;
   }
   return AMQ_OK;
