@@ -33,6 +33,9 @@ FP4_MFMA_PEAK_TFLOPS = 10100.0               # dense fp4 matrix cores
 # profiles/gemv_streamed_4096x1024.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (scale factors from a plain
 # 512 MiB device copy) = (2 x 270913.6 + 8192.6) KiB
 GEMV_TRAFFIC_BYTES = (2 * 270913.6 + 8192.6) * 1024
+# the same for the fused kernel of the primary workload (profiles/lstm_step_1024_b64_w3a3.md):
+# (2 x 2139.5 + 512.0) KiB per launch
+LSTM_FUSED_TRAFFIC_BYTES = (2 * 2139.5 + 512.0) * 1024
 
 
 def dv(a, dev):
@@ -415,7 +418,7 @@ def main():
         achieved = 2.0 * macs / (ms_fused * 1e-3) / 1e12
         out["roofline"] = {"kernel": "mfma4_kernel<3,3,lstm>: fused W3/A3 products (4096x2048, B=64) + cell",
                            "bound": "mfma", "achieved": achieved, "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / FP4_MFMA_PEAK_TFLOPS, "traffic": None, "launch_ms": ms_fused,
+                           "frac": achieved / FP4_MFMA_PEAK_TFLOPS, "traffic": LSTM_FUSED_TRAFFIC_BYTES, "launch_ms": ms_fused,
                            "flops_per_launch": 2.0 * macs}
         also["lstm_b64_fused_kernel_us"] = ms_fused * 1e3
         also["lstm_b64_quantize_kernel_us"] = ms_quant * 1e3
