@@ -167,7 +167,9 @@ def test_lm_step_full_size(amq, B):
                                                        (1024, 1024, 42000, 1, 2, 2, 2, 3),
                                                        # batch above 1: 4096 // 1500 = 2 steps per pass of the
                                                        # output layer, so 5 steps take three passes
-                                                       (40, 24, 130, 1500, 2, 2, 2, 5)])
+                                                       (40, 24, 130, 1500, 2, 2, 2, 5),
+                                                       # full size at batch 64: one 192-row pass of the output layer
+                                                       (1024, 1024, 42000, 64, 2, 2, 2, 3)])
 def test_lm_sequence(amq, E, H, V, B, k, k_ws, k_as, steps):
     """Whole sequences through one call (batch 1: the recurrence in one launch over the chip, the
     output layer on all steps of a piece together) against the oracle's step-by-step loop."""
