@@ -62,6 +62,8 @@ def lib():
         L.amq_oracle_clip.argtypes = [_f32p, _i64, C.c_float, C.c_float]
         L.amq_oracle_refined_greedy.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
         L.amq_oracle_refined_greedy_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p]
+        L.amq_oracle_ternary.argtypes = [_f32p, _i64, _int, _u8p, _f32p]
+        L.amq_oracle_ternary_rows.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p]
         L.amq_oracle_relative_mse.argtypes = [_f32p, _i64, _i64, _i64, _int, _u32p, _f32p, _f64p, _f64p]
         L.amq_oracle_relative_mse.restype = C.c_double
         L.amq_oracle_gru_step_rb.argtypes = [_u32p, _f32p, _u32p, _f32p, _i64, _i64, _int, C.c_void_p,
@@ -318,6 +320,26 @@ def refined_greedy_rows(W, k):
     planes = np.zeros((k, rows, wpr(cols)), np.uint32)
     alpha = np.zeros((rows, k), np.float32)
     lib().amq_oracle_refined_greedy_rows(W, rows, cols, cols, k, planes, alpha)
+    return planes, alpha
+
+
+def ternary(w, T):
+    """Ternary quantization of one vector as constrained 2-bit codes: code [2, n] uint8 (1 = +1), alpha [2]
+    with alpha[0] == alpha[1]; the ternary value of an entry is (alpha[0] + alpha[1]) * t."""
+    w = _f32(w)
+    n = w.shape[0]
+    code = np.zeros((2, n), np.uint8)
+    alpha = np.zeros(2, np.float32)
+    lib().amq_oracle_ternary(w, n, T, code, alpha)
+    return code, alpha
+
+
+def ternary_rows(W, T):
+    W = _f32(W)
+    rows, cols = W.shape
+    planes = np.zeros((2, rows, wpr(cols)), np.uint32)
+    alpha = np.zeros((rows, 2), np.float32)
+    lib().amq_oracle_ternary_rows(W, rows, cols, cols, T, planes, alpha)
     return planes, alpha
 
 

@@ -679,6 +679,73 @@ void amq_oracle_refined_greedy_rows(const float* W, int64_t rows, int64_t cols, 
 }
 
 /* ------------------------------------------------------------------ *
+ * Ternary quantization as the constrained 2-bit case (Sec. 2): w ~ a t
+ * with t in {-1, 0, +1}^n, i.e. alpha_1 = alpha_2 = a / 2 and
+ * t = (b_1 + b_2) / 2.
+ *   initial codes: the threshold rule cited there -- entries with
+ *     |w_l| <= (0.7 / n) ||w||_1 become 0, the others sign(w_l);
+ *   coefficient with the codes fixed: the least-squares a = t^T w / t^T t,
+ *     which is the mean of |w_l| over the non-zero entries (t_l w_l = |w_l|);
+ *   codes with the coefficient fixed: the nearest of {-a, 0, +a}, i.e.
+ *     t_l = sign(w_l) if |w_l| > a / 2, else 0.
+ * T alternating cycles {coefficient, codes} follow the initial codes, in
+ * the order of Alg. 2; with T = 0 the result is the threshold rule with its
+ * own least-squares coefficient.  A set of codes with no non-zero entry
+ * leaves the coefficient as it is (0 at the start).
+ * Precision: sums in binary64, a and the two thresholds rounded to
+ * binary32 ((0.7 * l1) / n evaluated in binary64; a / 2 is exact), every
+ * comparison |w_l| > threshold in binary32.
+ * Output: t as two code planes (+1 -> 1,1; -1 -> 0,0; 0 -> 1,0) and
+ * alpha = {a / 2, a / 2}, the format of the 2-bit quantizer.
+ * ------------------------------------------------------------------ */
+void amq_oracle_ternary(const float* w, int64_t n, int T, uint8_t* code, float* alpha) {
+  double l1 = 0.0;
+  for (int64_t l = 0; l < n; ++l) l1 += fabs((double)w[l]);
+  float thr = (float)((0.7 * l1) / (double)n);
+  float a = 0.0f;
+  for (int cycle = 0; cycle <= T; ++cycle) {
+    /* codes for the current threshold, and the least-squares coefficient of those codes */
+    double s = 0.0;
+    int64_t kept = 0;
+    for (int64_t l = 0; l < n; ++l) {
+      int nz = fabsf(w[l]) > thr;
+      code[l] = (uint8_t)(nz ? (w[l] > 0.0f) : 1);
+      code[(size_t)n + l] = (uint8_t)(nz ? (w[l] > 0.0f) : 0);
+      if (nz) { s += fabs((double)w[l]); ++kept; }
+    }
+    if (cycle == T) break;              /* the last cycle ends with its codes */
+    if (kept > 0) a = (float)(s / (double)kept);
+    thr = 0.5f * a;
+  }
+  /* T = 0: the coefficient that belongs to the initial codes */
+  if (T == 0) {
+    double s = 0.0;
+    int64_t kept = 0;
+    for (int64_t l = 0; l < n; ++l)
+      if (code[l] == code[(size_t)n + l]) { s += fabs((double)w[l]); ++kept; }
+    if (kept > 0) a = (float)(s / (double)kept);
+  }
+  alpha[0] = 0.5f * a;
+  alpha[1] = 0.5f * a;
+}
+
+/* Row-wise ternary quantization of a matrix, packed output as amq_oracle_quantize_rows (k = 2). */
+void amq_oracle_ternary_rows(const float* W, int64_t rows, int64_t cols, int64_t ld, int T,
+                             uint32_t* planes, float* alpha) {
+  int64_t wpr = amq_oracle_wpr(cols);
+#ifdef _OPENMP
+#pragma omp parallel for num_threads(amq_oracle_get_threads()) schedule(static)
+#endif
+  for (int64_t r = 0; r < rows; ++r) {
+    uint8_t* code = (uint8_t*)malloc((size_t)2 * (size_t)cols);
+    amq_oracle_ternary(W + r * ld, cols, T, code, alpha + r * 2);
+    for (int i = 0; i < 2; ++i)
+      amq_oracle_pack(code + (size_t)i * cols, cols, planes + ((size_t)i * rows + r) * wpr);
+    free(code);
+  }
+}
+
+/* ------------------------------------------------------------------ *
  * Relative mean squared error of a row-wise quantization (the measure of
  * Tables 1-2): sum over the matrix of (W - sum_i alpha_i B_i)^2 divided by
  * the sum of W^2, in binary64.  row_err / row_norm (nullable) receive the
