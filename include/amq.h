@@ -236,6 +236,21 @@ int amq_quantize_refined_greedy(const float* W, int64_t rows, int64_t cols, int6
                                 uint32_t* planes, float* alpha, void* stream);
 
 /*
+ * Ternary quantization written as the 2-bit case with alpha_1 = alpha_2 (Sec. 2), every row on its
+ * own: w ~ a t with t in {-1, 0, +1}.  Initial codes by the threshold rule cited there (entries
+ * with |w| <= (0.7 / cols) ||w||_1 become 0, the others their sign), then T alternating cycles
+ * { a = least-squares coefficient of the codes = mean of |w| over the non-zero entries;
+ *   t = nearest of {-a, 0, +a}, i.e. sign(w) where |w| > a / 2 }; T = 0 returns the threshold rule
+ * with its own least-squares coefficient.
+ *   planes [2][rows][wpr] (device, out): t as two code planes (+1 -> 1,1; -1 -> 0,0; 0 -> 1,0),
+ *   alpha [rows][2] (device, out): {a / 2, a / 2} -- the format of amq_quantize_weights with k = 2,
+ *   so every product entry point takes the result as it is.  Other arguments and errors as
+ *   amq_quantize_weights.
+ */
+int amq_quantize_ternary(const float* W, int64_t rows, int64_t cols, int64_t ld, int T, uint32_t* planes,
+                         float* alpha, void* stream);
+
+/*
  * Relative mean squared error of a row-wise quantization (the measure of Tables 1-2):
  *   result[0] = sum over the matrix of (W - sum_i alpha_i B_i)^2,  result[1] = sum of W^2,
  *   result[2] = result[0] / result[1];  row_err [rows], row_norm [rows] receive the two sums of

@@ -22,7 +22,7 @@ EXPORTS = [
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
-    "amq_quantize_refined_greedy", "amq_relative_mse",
+    "amq_quantize_refined_greedy", "amq_quantize_ternary", "amq_relative_mse",
     "amq_quantize_weights_ex", "amq_dequantize", "amq_clip",
     "amq_gru_reset_before_workspace_bytes", "amq_gru_step_reset_before",
 ]
@@ -80,6 +80,7 @@ def lib():
         L.amq_lm_sequence.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
                                       _p, _i64, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
+        L.amq_quantize_ternary.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
         L.amq_relative_mse.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p, _p, _p, _p]
         L.amq_gru_reset_before_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.amq_gru_reset_before_workspace_bytes.restype = _sz
@@ -423,6 +424,19 @@ def quantize_refined_greedy(W, k):
     alpha = _empty((rows, k), torch.float32, W)
     _check(lib().amq_quantize_refined_greedy(W.data_ptr(), rows, cols, W.stride(0), k, planes.data_ptr(),
                                              alpha.data_ptr(), _stream()))
+    return planes, alpha
+
+
+def quantize_ternary(W, T):
+    """Ternary quantization of every row of W [rows, cols] as 2-bit codes with equal coefficients
+    -> planes [2, rows, wpr], alpha [rows, 2]."""
+    if W.dim() != 2 or W.stride(1) != 1 or W.dtype != torch.float32 or not W.is_cuda:
+        raise AmqError("expected a 2-D float32 GPU tensor with unit column stride")
+    rows, cols = W.shape
+    planes = _empty((2, rows, wpr(cols)), torch.int32, W)
+    alpha = _empty((rows, 2), torch.float32, W)
+    _check(lib().amq_quantize_ternary(W.data_ptr(), rows, cols, W.stride(0), T, planes.data_ptr(),
+                                      alpha.data_ptr(), _stream()))
     return planes, alpha
 
 

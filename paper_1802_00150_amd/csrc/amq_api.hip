@@ -540,6 +540,16 @@ int amq_quantize_refined_greedy(const float* W, int64_t rows, int64_t cols, int6
                                                static_cast<hipStream_t>(stream)));
 }
 
+int amq_quantize_ternary(const float* W, int64_t rows, int64_t cols, int64_t ld, int T, uint32_t* planes,
+                         float* alpha, void* stream) {
+  if (!W || !planes || !alpha) return AMQ_ERR_INVALID;
+  if (T < 0 || rows <= 0 || cols <= 0 || ld < cols) return AMQ_ERR_INVALID;
+  if (!aligned(planes, 16)) return AMQ_ERR_INVALID;
+  if (cols > AMQ_MAX_QUANT_N || rows > 0x7fffffffLL) return AMQ_ERR_UNSUPPORTED;
+  return hip_status(amq::launch_ternary(W, ld, (int)cols, (int)rows, T, planes, alpha,
+                                        static_cast<hipStream_t>(stream)));
+}
+
 int amq_relative_mse(const float* W, int64_t rows, int64_t cols, int64_t ld, int k, const uint32_t* planes,
                      const float* alpha, double* row_err, double* row_norm, double* result, void* stream) {
   if (!W || !planes || !alpha || !row_err || !row_norm || !result) return AMQ_ERR_INVALID;

@@ -161,6 +161,86 @@ hipError_t launch_refined_k(const float* X, long long ld, int n, int count, uint
   return hipGetLastError();
 }
 
+// ---- ternary quantization as the 2-bit case with alpha_1 = alpha_2 (Sec. 2) -------------------
+// w ~ a t, t in {-1, 0, +1}: initial codes by the threshold (0.7 / n) ||w||_1, then T cycles of
+// { a = mean of |w| over the non-zero entries (the least-squares coefficient of the codes),
+//   t = sign(w) where |w| > a / 2, else 0 (the nearest of the three levels) }.
+// Sums in binary64, thresholds and a in binary32, comparisons in binary32.  Stored as two planes
+// (+1 -> 1,1; -1 -> 0,0; 0 -> 1,0) and alpha = {a / 2, a / 2}.
+template <int NJ, int NW>
+__global__ __launch_bounds__(64 * NW) void ternary_kernel(const float* X, long long ld, int n, int count, int T,
+                                                          uint32_t* planes, float* coef) {
+  __shared__ double sh[2][16 * kMaxRed];
+  int phase = 0;
+  const int lane = lane_id(), wv = wave_id();
+  const int vec = blockIdx.x;
+  const int wpr = 4 * ((n + 127) >> 7);
+  const int nslots = wpr >> 1;
+  const int nj = (nslots + NW - 1) / NW;  // host guarantees nj <= NJ
+  const int base = wv * nj;
+  const float* x = X + (long long)vec * ld;
+  float w[NJ];
+  double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int e = (base + j) * 64 + lane;
+    w[j] = (j < nj && e < n) ? x[e] : 0.0f;   // entries past the end are 0: never above a threshold
+    if (j & 1) s1 += (double)fabsf(w[j]); else s0 += (double)fabsf(w[j]);
+  }
+  double l1[1] = {s0 + s1};
+  block_totals<NW, 1>(l1, sh, phase);
+  float thr = (float)((0.7 * l1[0]) / (double)n);
+  float a = 0.0f;
+  for (int cycle = 0; cycle <= T; ++cycle) {
+    // the least-squares coefficient of the codes that `thr` defines (also needed after the last
+    // codes when T = 0: then it is the coefficient that belongs to the initial codes)
+    if (cycle == T && T > 0) break;
+    double q0 = 0.0, q1 = 0.0;
+    int kept = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      if (j < nj) {
+        const float m = fabsf(w[j]);
+        const bool nz = m > thr;
+        kept += nz ? 1 : 0;
+        if (j & 1) q1 += nz ? (double)m : 0.0; else q0 += nz ? (double)m : 0.0;
+      }
+    }
+    double red[2] = {q0 + q1, (double)kept};   // (counts are exact in binary64)
+    block_totals<NW, 2>(red, sh, phase);
+    if (red[1] > 0.0) a = (float)(red[0] / red[1]);
+    if (cycle == T) break;   // T = 0
+    thr = 0.5f * a;
+  }
+  // final codes: lane j of a wave keeps the ballot of its slot j
+  unsigned long long m0 = 0ull, m1 = 0ull;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    if (j < nj) {
+      const bool valid = (base + j) * 64 + lane < n;
+      const bool nz = fabsf(w[j]) > thr;
+      const bool pos = w[j] > 0.0f;
+      const unsigned long long b0 = __ballot(valid && (nz ? pos : true));
+      const unsigned long long b1 = __ballot(valid && nz && pos);
+      if (lane == j) { m0 = b0; m1 = b1; }
+    }
+  }
+  if (lane < nj && base + lane < nslots) {
+    reinterpret_cast<unsigned long long*>(planes + ((long long)0 * count + vec) * wpr)[base + lane] = m0;
+    reinterpret_cast<unsigned long long*>(planes + ((long long)1 * count + vec) * wpr)[base + lane] = m1;
+  }
+  if (threadIdx.x == 0) {
+    coef[(long long)vec * 2 + 0] = 0.5f * a;
+    coef[(long long)vec * 2 + 1] = 0.5f * a;
+  }
+}
+
+template <int NJ, int NW>
+void launch_ternary_one(const float* X, long long ld, int n, int count, int T, uint32_t* planes, float* coef,
+                        hipStream_t s) {
+  hipLaunchKernelGGL((ternary_kernel<NJ, NW>), dim3(count), dim3(64 * NW), 0, s, X, ld, n, count, T, planes, coef);
+}
+
 // ---- relative mean squared error ------------------------------------------------------------
 // One wavefront per row: sum over the row of (w - sum_i +-alpha_i)^2 and of w^2, binary64.
 template <int K>
@@ -281,6 +361,26 @@ hipError_t launch_refined_greedy(const float* X, long long ld, int n, int count,
     case 4: return launch_refined_k<4>(X, ld, n, count, planes, coef, s);
   }
   return hipErrorInvalidValue;
+}
+
+hipError_t launch_ternary(const float* X, long long ld, int n, int count, int T, uint32_t* planes, float* coef,
+                          hipStream_t s) {
+  const int nslots = 2 * ((n + 127) / 128);
+  if (nslots > 256) return hipErrorInvalidValue;
+  // one wave per vector up to 4096 entries when there are many vectors, four waves otherwise
+  int nw = (count >= 1024 && nslots <= 64) ? 1 : 4;
+  if (nw > nslots) nw = 1;
+  const int nj = (nslots + nw - 1) / nw;
+  if (nw == 1) {
+    if (nj <= 4) launch_ternary_one<4, 1>(X, ld, n, count, T, planes, coef, s);
+    else if (nj <= 16) launch_ternary_one<16, 1>(X, ld, n, count, T, planes, coef, s);
+    else launch_ternary_one<64, 1>(X, ld, n, count, T, planes, coef, s);
+  } else {
+    if (nj <= 4) launch_ternary_one<4, 4>(X, ld, n, count, T, planes, coef, s);
+    else if (nj <= 16) launch_ternary_one<16, 4>(X, ld, n, count, T, planes, coef, s);
+    else launch_ternary_one<64, 4>(X, ld, n, count, T, planes, coef, s);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_relative_mse(const float* W, long long rows, int cols, long long ld, int k, const uint32_t* planes,

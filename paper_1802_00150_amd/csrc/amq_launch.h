@@ -49,6 +49,9 @@ hipError_t launch_quantize(const QuantArgs& a, int k, hipStream_t s);
 hipError_t launch_refined_greedy(const float* X, long long ld, int n, int count, int k, uint32_t* planes, float* coef,
                                  hipStream_t s);
 // Sums of squared error and squared norm of every row, then result = {error, norm, error / norm}.
+// ternary quantization as 2-bit codes with equal coefficients (Sec. 2)
+hipError_t launch_ternary(const float* X, long long ld, int n, int count, int T, uint32_t* planes, float* coef,
+                          hipStream_t s);
 hipError_t launch_relative_mse(const float* W, long long rows, int cols, long long ld, int k, const uint32_t* planes,
                                const float* alpha, double* row_err, double* row_norm, double* result,
                                hipStream_t s);

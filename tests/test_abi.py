@@ -81,6 +81,10 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_quantize_refined_greedy(p, 4, 8, 4, 2, p, p, None) == INVALID
     assert L.amq_quantize_refined_greedy(p, 4, 4, 4, 5, p, p, None) == INVALID
     assert L.amq_quantize_refined_greedy(p, 4, 16385, 16385, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_quantize_ternary(null, 4, 4, 4, 2, p, p, None) == INVALID
+    assert L.amq_quantize_ternary(p, 4, 8, 4, 2, p, p, None) == INVALID
+    assert L.amq_quantize_ternary(p, 4, 4, 4, -1, p, p, None) == INVALID
+    assert L.amq_quantize_ternary(p, 4, 16385, 16385, 2, p, p, None) == UNSUPPORTED
     assert L.amq_relative_mse(p, 4, 4, 4, 2, p, p, p, p, null, None) == INVALID
     assert L.amq_relative_mse(p, 0, 4, 4, 2, p, p, p, p, p, None) == INVALID
     assert L.amq_relative_mse(p, 4, 4, 2, 2, p, p, p, p, p, None) == INVALID
