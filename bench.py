@@ -325,6 +325,8 @@ def bench_relative_mse(amq, dev):
                                      ("alternating", amq.quantize_weights(d, k, 2))):
                 row[method] = float(amq.relative_mse(d, pl, al)[0][2].item())
             tab["k%d" % k] = row
+        pl, al = amq.quantize_ternary(d, 2)   # the 2-bit case with equal coefficients
+        tab["ternary"] = float(amq.relative_mse(d, pl, al)[0][2].item())
         out[name] = tab
     return out
 
