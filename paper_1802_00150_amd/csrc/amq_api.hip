@@ -114,6 +114,10 @@ hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, 
                               int* lse_slots = nullptr) {
   if (epi == amq::kEpiStore && amq::mfma4w_supported(b, k_w, k_a))
     return amq::launch_mfma4w(b, k_w, k_a, s, lse_slots);
+  if (epi != amq::kEpiStore && amq::mfma4w_cell_supported(b, k_w, k_a, epi)) {
+    if (lse_slots) *lse_slots = 0;
+    return amq::launch_mfma4w_cell(b, k_w, k_a, epi, s);
+  }
   if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s, lse_slots);
   if (lse_slots) *lse_slots = 0;
   return amq::launch_mfma(b, k_w, k_a, epi, s);

@@ -144,6 +144,9 @@ hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int
 // at least 32 columns (store mode only)
 bool mfma4w_supported(const BmvArgs& a, int k_w, int k_a);
 hipError_t launch_mfma4w(const BmvArgs& a, int k_w, int k_a, hipStream_t s, int* lse_slots = nullptr);
+// and the recurrent steps in the same work split, for batches of 128 and more
+bool mfma4w_cell_supported(const BmvArgs& a, int k_w, int k_a, int epi);
+hipError_t launch_mfma4w_cell(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 
 // ---- output layer -----------------------------------------------------------------------
 // out[b][v] = Y[b][v] - log(sum_u exp(Y[b][u])); out may alias Y.
