@@ -525,7 +525,8 @@ hipError_t launch_mode(const BmvArgs& a, hipStream_t s, int* lse_slots) {
   int per = (rowblocks + splits - 1) / splits;
   if (per < 4) per = 4;
   // 8 waves (two per SIMD) when there is work for them and 256 registers per wave suffice
-  if (per >= 16 && KW * KA <= (EPI == kEpiStore ? 9 : 4)) return launch_one<KW, KA, EPI, 8>(a, rowblocks, per, s, lse_slots);
+  if constexpr (KW * KA <= (EPI == kEpiStore ? 9 : 4))
+    if (per >= 16) return launch_one<KW, KA, EPI, 8>(a, rowblocks, per, s, lse_slots);
   return launch_one<KW, KA, EPI, 4>(a, rowblocks, per, s, lse_slots);
 }
 
