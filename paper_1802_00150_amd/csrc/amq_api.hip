@@ -31,6 +31,7 @@ struct StepWs {
   unsigned long long* hbuf;
   uint32_t* xq;
   float* xbeta;
+  size_t sync_off;  // byte offset of `sync` in the workspace (SIZE_MAX when the region is absent)
   size_t total;
 };
 
@@ -50,7 +51,9 @@ StepWs carve(void* ws, int64_t I, int64_t H, int64_t B, int k_a, int gates, int 
   w.pre0 = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H));
   w.pre1 = n_pre > 1 ? reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * gates * H)) : nullptr;
   w.sync = nullptr; w.hbuf = nullptr; w.xq = nullptr; w.xbeta = nullptr;
+  w.sync_off = SIZE_MAX;
   if (B == 1 && gates == 4) {
+    w.sync_off = off;
     w.sync = reinterpret_cast<unsigned*>(take(sizeof(unsigned) * (1 + amq::kSeqGMaxGrid)));
     w.hbuf = reinterpret_cast<unsigned long long*>(take(sizeof(unsigned long long) * 2 * (size_t)H));
     w.xq = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * amq::kSeqGMaxSteps * (size_t)k_a * amq_wpr(I)));
@@ -353,9 +356,7 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
 
 size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a) {
   if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return SIZE_MAX;
-  char base[1];  // any non-null address: only the offset of the region is of interest
-  StepWs w = carve(base, I, H, B, k_a, 4, 1);
-  return w.sync ? (size_t)(reinterpret_cast<char*>(w.sync) - base) : SIZE_MAX;
+  return carve(nullptr, I, H, B, k_a, 4, 1).sync_off;
 }
 
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
