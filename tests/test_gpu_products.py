@@ -95,6 +95,33 @@ def test_gemm_many_rows_wide_batch(amq, k_w, k_a, m, n, batch):
     assert_vec_close(host(amq.binary_gemm(dW, dA, n, dX, dB, bias=dbias, Y=to_dev(Y0))), refa)
 
 
+@pytest.mark.parametrize("k_w,k_a,m,batch", [(2, 2, 42000, 1024), (3, 3, 16384, 1024), (2, 3, 10000, 4096)])
+def test_gemm_large_batch_shapes_sampled(amq, k_w, k_a, m, batch):
+    # The large-batch products bench.py times, in the launch configuration it times them in (the
+    # whole product on the GPU); the oracle computes a sample of rows -- the first and last ones, the
+    # rows around the boundaries between workgroups' shares, and random ones -- for every batch entry.
+    n = 1024
+    g = np.random.default_rng(9000 + m + batch)
+    say("large-batch gemm kw=%d ka=%d m=%d B=%d" % (k_w, k_a, m, batch))
+    Wp = rand_planes(g, k_w, m, n)
+    Xp = rand_planes(g, k_a, batch, n)
+    alpha = (np.abs(g.standard_normal((m, k_w))) * 0.02).astype(np.float32)
+    beta = np.abs(g.standard_normal((batch, k_a))).astype(np.float32)
+    bias = (g.standard_normal(m) * 0.1).astype(np.float32)
+    Y = host(amq.binary_gemm(to_dev(Wp), to_dev(alpha), n, to_dev(Xp), to_dev(beta), bias=to_dev(bias)))
+    rows = np.unique(np.concatenate([np.arange(0, 20), np.arange(m - 20, m),
+                                     (np.arange(1, 16) * (m // 16))[:, None].repeat(6, 1).ravel() + np.tile(np.arange(-3, 3), 15),
+                                     g.integers(0, m, 40)]))
+    oracle.set_threads(oracle.host_threads())
+    ref = oracle.binary_gemm(np.ascontiguousarray(Wp[:, rows]), np.ascontiguousarray(alpha[rows]), n, Xp, beta,
+                             bias=np.ascontiguousarray(bias[rows]))
+    oracle.set_threads(1)
+    got = Y[:, rows]
+    tol = 1e-4 * np.abs(ref) + 1e-4 * np.sqrt((ref.astype(np.float64) ** 2).mean()) + 1e-30
+    bad = ~(np.abs(got.astype(np.float64) - ref) <= tol)
+    assert not bad.any(), "%d mismatches" % bad.sum()
+
+
 @pytest.mark.parametrize("batch", [1, 8, 64])
 @pytest.mark.parametrize("k", [2, 3])
 def test_config2_full_pipeline(amq, k, batch):
