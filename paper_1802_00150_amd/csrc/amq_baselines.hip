@@ -1,5 +1,6 @@
-// The comparison quantizer of Sec. 2 (refined greedy approximation), the relative mean squared
-// error of Tables 1-2, and the training-side helpers of Sec. 4 (reconstruction of the quantized
+// The comparison quantizers of Sec. 2 (refined greedy approximation; ternary quantization as the
+// 2-bit case with equal coefficients), the relative mean squared error of Tables 1-2, and the
+// training-side helpers of Sec. 4 (reconstruction of the quantized
 // weights for the forward pass, clipping of the full-precision weights), on gfx950.  Same vector layout and reductions as the alternating quantizer
 // (amq_quantize_core.h): one wavefront or one 4-wave workgroup per vector, the vector in registers.
 #include "amq_launch.h"

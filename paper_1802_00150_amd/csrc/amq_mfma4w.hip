@@ -1,5 +1,6 @@
-// Large batched binary matrix products on the fp4 matrix cores of gfx950 (Fig. 3 right), plain
-// outputs only: Y = (sum_i alpha_i B_i)(sum_j beta_j x_j) for many rows and 32 or more columns.
+// Large batched binary matrix products on the fp4 matrix cores of gfx950 (Fig. 3 right):
+// Y = (sum_i alpha_i B_i)(sum_j beta_j x_j) for many rows and 32 or more columns (mfma4w_kernel),
+// and the recurrent steps for batches of 128 and more (mfma4wc_kernel, further down).
 //
 // Same arithmetic and operand formats as the kernel in amq_mfma4.hip ({0, 1} codes as E2M1 nibbles,
 // v_mfma_scale_f32_16x16x128_f8f6f4, +-1 dot products recovered from popcounts), different work
