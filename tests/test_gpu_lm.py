@@ -74,7 +74,11 @@ def test_log_softmax(amq, B, V):
 
 
 @pytest.mark.parametrize("V,H,B,k_w,k_a", [(130, 72, 3, 2, 2), (1000, 300, 1, 2, 3), (777, 256, 20, 3, 3),
-                                           (10000, 1024, 37, 2, 3), (4100, 1500, 18, 2, 2), (300, 2100, 5, 4, 4)])
+                                           (10000, 1024, 37, 2, 3), (4100, 1500, 18, 2, 2), (300, 2100, 5, 4, 4),
+                                           # vocabularies above 32768 with 32 or more rows: the product with several
+                                           # batch tiles per wave and one (max, sum) pair per workgroup; V ragged
+                                           # against 16 and against 4, last batch group partly empty
+                                           (33001, 64, 40, 2, 2), (40003, 200, 100, 2, 2), (35002, 130, 33, 3, 3)])
 def test_softmax_layer(amq, V, H, B, k_w, k_a):
     g = np.random.default_rng(V + H + B)
     Ws = (g.standard_normal((V, H)) * 0.05).astype(np.float32)
