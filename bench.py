@@ -301,10 +301,17 @@ def bench_lm(amq, dev, B, steps, warmup):
     lp35 = torch.empty((35, B, V), device=dev)
     ms_seq = wall_time_ms(lambda: amq.lm_sequence(Ep, ae, E, Wxp, ax, Whp, ah, H, None, Wsp, as_, bs, ids35, h, c, k, k,
                                                   T, ws=wsq, logprob=lp35), 10, 2) / 35
+    # scoring: only the log-probability of a given next word per step and batch entry
+    tg35 = torch.randint(0, V, (35, B), dtype=torch.int64, generator=torch.Generator().manual_seed(7)).to(dev)
+    wss = torch.empty(int(amq.binding.lib().amq_lm_sequence_score_workspace_bytes(E, H, V, B, k, k)), dtype=torch.uint8,
+                      device=dev)
+    sc35 = torch.empty((35, B), device=dev)
+    ms_score = wall_time_ms(lambda: amq.lm_sequence_score(Ep, ae, E, Wxp, ax, Whp, ah, H, None, Wsp, as_, bs, ids35, tg35,
+                                                          h, c, k, k, T, ws=wss, out=sc35), 10, 2) / 35
     ws2 = amq.softmax_layer_workspace(V, H, B, k, dev)
     ms_layer = event_time_ms(lambda: amq.softmax_layer(Wsp, as_, H, bs, h, k, T, ws=ws2, logprob=logprob), 200, 20)
     ms_lsm = event_time_ms(lambda: amq.log_softmax(logprob, out=logprob), 200, 20)
-    return ms, ms_layer, ms_lsm, ms_seq
+    return ms, ms_layer, ms_lsm, ms_seq, ms_score
 
 
 def bench_relative_mse(amq, dev):
@@ -474,9 +481,10 @@ def main():
         # full language-model step at the paper's large shape: embedding lookup, LSTM 1024, output layer
         # 42000 x 1024 with log-softmax, W2/A2
         for b in (1, 64):
-            ms, ms_layer, ms_lsm, ms_seq = bench_lm(amq, dev, b, 300, 30)
+            ms, ms_layer, ms_lsm, ms_seq, ms_score = bench_lm(amq, dev, b, 300, 30)
             also["lm_h1024_v42000_w2a2_b%d_steps_per_s" % b] = 1e3 / ms
             also["lm_h1024_v42000_w2a2_b%d_sequence_call_steps_per_s" % b] = 1e3 / ms_seq
+            also["lm_h1024_v42000_w2a2_b%d_sequence_score_steps_per_s" % b] = 1e3 / ms_score
             also["lm_output_layer_42000x1024_b%d_us" % b] = ms_layer * 1e3
             also["lm_log_softmax_42000_b%d_us" % b] = ms_lsm * 1e3
 

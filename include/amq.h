@@ -323,6 +323,25 @@ int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int
                     float* c, int64_t B, int k_a, int k_as, int T, float* logprob, void* workspace,
                     size_t workspace_bytes, void* stream);
 
+/*
+ * Scoring a given continuation (the quantity behind the perplexities of Sec. 5): the same steps as
+ * amq_lm_sequence, but only the log-probability of one given word per step and batch entry is
+ * returned: target_logprob[t][b] = logprob[t][b][targets[t][b]] (device, [steps][B]).  targets
+ * [steps][B] (device) are row indices of W_s; an index outside [0, V) gives NaN.  Where the output
+ * layer is large enough for the matrix-core kernel with several batch tiles per wave, the logits
+ * are never written to memory (the kernel leaves the chosen logit and the partial log-sum-exp);
+ * otherwise 64 rows at a time go through the ordinary layer.  Same arithmetic as amq_lm_sequence.
+ *   workspace: at least amq_lm_sequence_score_workspace_bytes(E, H, V, B, k_a, k_as) bytes, 256-byte
+ *   aligned (the flag word of the batch-1 recurrence sits at the same offset as in amq_lm_sequence).
+ */
+size_t amq_lm_sequence_score_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as);
+int amq_lm_sequence_score(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E,
+                          const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                          int64_t H, int k_w, const float* bias, const uint32_t* Wsp, const float* alpha_s,
+                          int64_t V, int k_ws, const float* bias_s, const int64_t* ids, const int64_t* targets,
+                          int64_t steps, float* h, float* c, int64_t B, int k_a, int k_as, int T,
+                          float* target_logprob, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@ EXPORTS = [
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
+    "amq_lm_sequence_score_workspace_bytes", "amq_lm_sequence_score",
     "amq_quantize_refined_greedy", "amq_quantize_ternary", "amq_relative_mse",
     "amq_quantize_weights_ex", "amq_dequantize", "amq_clip",
     "amq_gru_reset_before_workspace_bytes", "amq_gru_step_reset_before",
@@ -77,6 +78,10 @@ def lib():
                                   _p, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_lm_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int]
         L.amq_lm_sequence_workspace_bytes.restype = _sz
+        L.amq_lm_sequence_score_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int]
+        L.amq_lm_sequence_score_workspace_bytes.restype = _sz
+        L.amq_lm_sequence_score.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
+                                            _p, _p, _i64, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_lm_sequence.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, _p, _i64, _int, _p, _p, _p, _i64, _int, _p,
                                       _p, _i64, _p, _p, _i64, _int, _int, _int, _p, _p, _sz, _p]
         L.amq_quantize_refined_greedy.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, _p]
@@ -413,6 +418,30 @@ def lm_sequence(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_
                                  _dev(h, torch.float32), _dev(c, torch.float32), B, k_a, k_as, T,
                                  _dev(logprob, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
     return logprob
+
+
+def lm_sequence_score(Ep, alpha_e, E, Wxp, alpha_x, Whp, alpha_h, H, bias, Wsp, alpha_s, bias_s, ids, targets, h, c,
+                      k_a, k_as, T, ws=None, out=None):
+    """ids, targets [steps, B] -> log-probability of targets[t, b] at step t, [steps, B]; h, c updated in place."""
+    vocab = Ep.shape[1]
+    k_w = Wxp.shape[0]
+    k_ws, V, _ = Wsp.shape
+    steps, B = ids.shape
+    if tuple(targets.shape) != (steps, B):
+        raise AmqError("targets must have the shape of ids")
+    if ws is None:
+        ws = torch.empty(int(lib().amq_lm_sequence_score_workspace_bytes(E, H, V, B, k_a, k_as)), dtype=torch.uint8,
+                         device=h.device)
+    if out is None:
+        out = _empty((steps, B), torch.float32, h)
+    _check(lib().amq_lm_sequence_score(_dev(Ep, torch.int32), _dev(alpha_e, torch.float32), vocab, E,
+                                       _dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                                       _dev(alpha_h, torch.float32), H, k_w, _opt(bias), _dev(Wsp, torch.int32),
+                                       _dev(alpha_s, torch.float32), V, k_ws, _opt(bias_s), _dev(ids, torch.int64),
+                                       _dev(targets, torch.int64), steps, _dev(h, torch.float32),
+                                       _dev(c, torch.float32), B, k_a, k_as, T, _dev(out, torch.float32),
+                                       ws.data_ptr(), ws.numel(), _stream()))
+    return out
 
 
 def quantize_refined_greedy(W, k):

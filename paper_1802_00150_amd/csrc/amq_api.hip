@@ -752,15 +752,89 @@ size_t amq_lm_sequence_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t 
   return carve_lm_seq(nullptr, E, H, V, B, k_a, k_as).total;
 }
 
-int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
-                    const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
-                    const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
-                    const float* bias_s, const int64_t* ids, int64_t steps, float* h, float* c, int64_t B, int k_a,
-                    int k_as, int T, float* logprob, void* workspace, size_t workspace_bytes, void* stream) {
-  if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !c || !logprob || steps <= 0) return AMQ_ERR_INVALID;
-  if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
-  const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
-  const size_t need = sizes_ok ? carve_lm_seq(nullptr, E, H, V, B, k_a, k_as).total : 0;
+// Output side of a piece of a sequence: either log-probabilities of every word, or (scoring) the
+// log-probability of one given word per row.
+struct LmOutput {
+  float* logprob;            // [steps][B][V], or null when scoring
+  const int64_t* targets;    // [steps][B] when scoring
+  float* target_logprob;     // [steps][B] when scoring
+  float* tlogit;             // scoring scratch: the chosen logit of every row of a piece
+  float* chunk_logprob;      // scoring scratch: log-probabilities of up to chunk_rows rows
+  int64_t chunk_rows;
+};
+
+// Scoring pass of the output layer over `rows` hidden states: where the several-tiles product takes the
+// shape, the logits are never written -- the kernel leaves the chosen logit of every row and the
+// (max, sum) pairs, and a small kernel forms logit - log-sum-exp; otherwise chunks of rows go through the
+// ordinary layer into a small buffer from which the chosen entries are gathered.
+static int score_layer_launch(const uint32_t* Wsp, const float* alpha_s, int64_t V, int64_t H, int k_ws,
+                              const float* bias_s, const float* hs, int64_t rows, int k_as, int T,
+                              const int64_t* targets, float* out, char* soft_base, const LmOutput& o,
+                              hipStream_t s) {
+  const long long* tg = reinterpret_cast<const long long*>(targets);
+  SoftmaxWs sw = carve_softmax(soft_base, V, H, rows, k_as);
+  amq::BmvArgs b{};
+  b.blk[0] = amq::BmvBlock{Wsp, alpha_s, sw.hp, sw.beta, (int)H};
+  b.m = V;
+  b.batch = (int)rows;
+  b.bias0 = bias_s;
+  b.lse_part = sw.lse_part;
+  b.lse_cap = sw.lse_cap;
+  b.tgt = tg;
+  b.tgt_out = o.tlogit;
+  b.groups = 1;
+  if (rows > amq::kBmvMaxBatch && amq::mfma4w_supported(b, k_ws, k_as)) {
+    amq::QuantArgs q{};
+    q.seg[0] = amq::QuantSeg{hs, H, (int)H, (int)rows, sw.hp, sw.beta};
+    q.T = T;
+    q.mode = amq::kQuantFull;
+    int st = hip_status(amq::launch_quantize(q, k_as, s));
+    if (st != AMQ_OK) return st;
+    int slots = 0;
+    st = hip_status(amq::launch_mfma4w(b, k_ws, k_as, s, &slots));
+    if (st != AMQ_OK) return st;
+    if (slots > 0)
+      return hip_status(amq::launch_score_finish(o.tlogit, tg, rows, V, sw.lse_part, slots, out, s));
+  }
+  for (int64_t r0 = 0; r0 < rows; r0 += o.chunk_rows) {
+    const int64_t n = rows - r0 < o.chunk_rows ? rows - r0 : o.chunk_rows;
+    SoftmaxWs swc = carve_softmax(soft_base, V, H, n, k_as);
+    int st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, hs + r0 * H, n, k_as, T, o.chunk_logprob, swc, s);
+    if (st != AMQ_OK) return st;
+    st = hip_status(amq::launch_gather_columns(o.chunk_logprob, n, V, tg + r0, out + r0, s));
+    if (st != AMQ_OK) return st;
+  }
+  return AMQ_OK;
+}
+
+// Workspace of amq_lm_sequence_score: that of amq_lm_sequence, then one float per row of a piece and
+// room for the log-probabilities of 64 rows.
+struct LmScoreWs {
+  float* tlogit;
+  float* chunk_logprob;
+  int64_t chunk_rows;
+  size_t total;
+};
+static LmScoreWs carve_lm_score(void* ws, int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
+  LmScoreWs w;
+  char* base = static_cast<char*>(ws);
+  const LmSeqWs lw = carve_lm_seq(nullptr, E, H, V, B, k_a, k_as);
+  size_t off = lw.total;
+  w.tlogit = reinterpret_cast<float*>(base ? base + off : nullptr);
+  off += up256(sizeof(float) * (size_t)lw.soft_batch);
+  w.chunk_rows = lw.soft_batch < 64 ? lw.soft_batch : 64;
+  w.chunk_logprob = reinterpret_cast<float*>(base ? base + off : nullptr);
+  off += up256(sizeof(float) * (size_t)w.chunk_rows * V);
+  w.total = off;
+  return w;
+}
+
+static int lm_sequence_impl(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                            const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                            const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                            const float* bias_s, const int64_t* ids, int64_t steps, float* h, float* c, int64_t B,
+                            int k_a, int k_as, int T, LmOutput o, void* workspace, size_t workspace_bytes,
+                            size_t need, void* stream) {
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, ids, h, B, k_a, T, h, workspace, workspace_bytes,
                       need);
   if (st != AMQ_OK) return st;
@@ -770,10 +844,21 @@ int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int
   LmSeqWs lw = carve_lm_seq(workspace, E, H, V, B, k_a, k_as);
   StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
   char* soft_base = static_cast<char*>(workspace) + lw.soft_off;
+  // every h_t of a piece of the sequence goes through the output layer together, as a batch of rows
+  auto output_layer = [&](int64_t row0, int64_t rows) -> int {
+    if (lw.soft_off + carve_softmax(nullptr, V, H, rows, k_as).total > workspace_bytes)
+      return AMQ_ERR_INVALID;  // (cannot happen: fewer rows need less)
+    if (o.logprob) {
+      SoftmaxWs sw = carve_softmax(soft_base, V, H, rows, k_as);
+      return softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, rows, k_as, T, o.logprob + row0 * V, sw, s);
+    }
+    return score_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, rows, k_as, T, o.targets + row0,
+                              o.target_logprob + row0, soft_base, o, s);
+  };
   if (B == 1 && amq::lstm_seqg_supported(E, H, B, k_w, k_a) && grid_fits_device()) {
     // batch 1: per piece of at most kSeqGMaxSteps steps, look all inputs up (the table the sequence
-    // kernel reads its input codes from), run the recurrence in one launch over the chip, then put
-    // every h_t of the piece through the output layer together, as a batch
+    // kernel reads its input codes from), run the recurrence in one launch over the chip, then the
+    // output layer
     for (int64_t t0 = 0; t0 < steps; t0 += amq::kSeqGMaxSteps) {
       const int n = (int)(steps - t0 < amq::kSeqGMaxSteps ? steps - t0 : amq::kSeqGMaxSteps);
       amq::QuantArgs q{};
@@ -786,9 +871,7 @@ int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int
                       w.xq, w.xbeta};
       st = hip_status(amq::launch_lstm_seqg(g, k_w, k_a, s));
       if (st != AMQ_OK) return st;
-      SoftmaxWs sw = carve_softmax(soft_base, V, H, n, k_as);
-      if (lw.soft_off + sw.total > workspace_bytes) return AMQ_ERR_INVALID;  // (cannot happen: fewer rows need less)
-      st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, n, k_as, T, logprob + t0 * V, sw, s);
+      st = output_layer(t0, n);
       if (st != AMQ_OK) return st;
     }
     return AMQ_OK;
@@ -805,12 +888,52 @@ int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int
                                c, B, k_a, T, lw.hs + t * B * H, w, s);
       if (st != AMQ_OK) return st;
     }
-    SoftmaxWs sw = carve_softmax(soft_base, V, H, n * B, k_as);
-    if (lw.soft_off + sw.total > workspace_bytes) return AMQ_ERR_INVALID;  // (cannot happen: fewer rows need less)
-    st = softmax_layer_launch(Wsp, alpha_s, V, H, k_ws, bias_s, lw.hs, n * B, k_as, T, logprob + t0 * B * V, sw, s);
+    st = output_layer(t0 * B, n * B);
     if (st != AMQ_OK) return st;
   }
   return AMQ_OK;
+}
+
+int amq_lm_sequence(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                    const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                    const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                    const float* bias_s, const int64_t* ids, int64_t steps, float* h, float* c, int64_t B, int k_a,
+                    int k_as, int T, float* logprob, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !c || !logprob || steps <= 0) return AMQ_ERR_INVALID;
+  if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
+  const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
+  const size_t need = sizes_ok ? carve_lm_seq(nullptr, E, H, V, B, k_a, k_as).total : 0;
+  LmOutput o{logprob, nullptr, nullptr, nullptr, nullptr, 0};
+  return lm_sequence_impl(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
+                          ids, steps, h, c, B, k_a, k_as, T, o, workspace, workspace_bytes, need, stream);
+}
+
+size_t amq_lm_sequence_score_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
+  if (E <= 0 || H <= 0 || V <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
+  return carve_lm_score(nullptr, E, H, V, B, k_a, k_as).total;
+}
+
+int amq_lm_sequence_score(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
+                          const float* alpha_x, const uint32_t* Whp, const float* alpha_h, int64_t H, int k_w,
+                          const float* bias, const uint32_t* Wsp, const float* alpha_s, int64_t V, int k_ws,
+                          const float* bias_s, const int64_t* ids, const int64_t* targets, int64_t steps, float* h,
+                          float* c, int64_t B, int k_a, int k_as, int T, float* target_logprob, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !targets || !c || !target_logprob || steps <= 0)
+    return AMQ_ERR_INVALID;
+  if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
+  const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
+  if (sizes_ok && V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
+  const size_t need = sizes_ok ? carve_lm_score(nullptr, E, H, V, B, k_a, k_as).total : 0;
+  LmOutput o{nullptr, targets, target_logprob, nullptr, nullptr, 0};
+  if (sizes_ok && workspace) {
+    const LmScoreWs sw = carve_lm_score(workspace, E, H, V, B, k_a, k_as);
+    o.tlogit = sw.tlogit;
+    o.chunk_logprob = sw.chunk_logprob;
+    o.chunk_rows = sw.chunk_rows;
+  }
+  return lm_sequence_impl(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
+                          ids, steps, h, c, B, k_a, k_as, T, o, workspace, workspace_bytes, need, stream);
 }
 
 }  // extern "C"

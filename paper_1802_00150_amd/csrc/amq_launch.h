@@ -120,6 +120,8 @@ struct BmvArgs {
                         // the outputs one wave produced, [batch][lse_slots][2]
   int lse_slots;        // filled by the launcher: slots per batch entry
   int lse_cap;          // slots per batch entry the buffer has room for
+  const long long* tgt; // several-tiles store kernel only, nullable: one output row index per batch entry ...
+  float* tgt_out;       // ... whose output value is also written here, [batch] (Y may then be null)
   int lg;               // filled by launch_bmv
   int groups;           // store mode: independent products in one launch (1 otherwise)
   long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
@@ -154,6 +156,13 @@ hipError_t launch_log_softmax(const float* Y, long long B, long long V, float* o
 // The same when a product kernel has already reduced its outputs to `slots` (max, sum) pairs per row.
 hipError_t launch_log_softmax_finish(const float* Y, long long B, long long V, const float* part, int slots,
                                      float* out, hipStream_t s);
+// out[b] = value[b] - log(sum_u exp(Y[b][u])) from the (max, sum) pairs alone; an index outside [0, V)
+// gives NaN
+hipError_t launch_score_finish(const float* value, const long long* index, long long B, long long V, const float* part,
+                               int slots, float* out, hipStream_t s);
+// out[b] = logprob[b][index[b]] (NaN for an index outside [0, V))
+hipError_t launch_gather_columns(const float* logprob, long long B, long long V, const long long* index, float* out,
+                                 hipStream_t s);
 
 // ---- whole batch-1 LSTM sequences in one launch spread over the chip (weights resident in
 // registers, one grid barrier per time step) ------------------------------------------------

@@ -152,6 +152,33 @@ __global__ __launch_bounds__(kFinThreads) void log_softmax_finish_kernel(const f
   }
 }
 
+// Scoring: one wave per row merges the row's (max, sum) pairs and writes value - log-sum-exp.
+__global__ __launch_bounds__(256) void score_finish_kernel(const float* value, const long long* index, long long B,
+                                                           long long V, const float* part, int slots, float* out) {
+  const long long row = (long long)blockIdx.x * 4 + wave_id();
+  if (row >= B) return;
+  const int lane = lane_id();
+  const float2* pr = reinterpret_cast<const float2*>(part) + row * slots;
+  float m = kLseLow, s = 0.0f;
+  for (int i = lane; i < slots; i += kWave) {
+    const float2 p = pr[i];
+    lse_merge(m, s, p.x, p.y);
+  }
+  lse_wave_merge(m, s);
+  if (lane == 0) {
+    const long long ix = index[row];
+    out[row] = (ix >= 0 && ix < V) ? value[row] - (m + logf(s)) : __int_as_float(0x7fc00000);
+  }
+}
+
+__global__ __launch_bounds__(256) void gather_columns_kernel(const float* logprob, long long B, long long V,
+                                                             const long long* index, float* out) {
+  const long long row = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (row >= B) return;
+  const long long ix = index[row];
+  out[row] = (ix >= 0 && ix < V) ? logprob[row * V + ix] : __int_as_float(0x7fc00000);
+}
+
 template <int NV>
 void launch_lsm(const float* Y, long long B, long long V, float* out, hipStream_t s) {
   hipLaunchKernelGGL((log_softmax_kernel<NV>), dim3((unsigned)B), dim3(kLsmThreads), 0, s, Y, V, out);
@@ -176,6 +203,22 @@ hipError_t launch_log_softmax_finish(const float* Y, long long B, long long V, c
   if (B > 65535 || chunks > 0x7fffffffLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(log_softmax_finish_kernel, dim3((unsigned)chunks, (unsigned)B), dim3(kFinThreads), 0, s, Y, V,
                      part, slots, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_finish(const float* value, const long long* index, long long B, long long V, const float* part,
+                               int slots, float* out, hipStream_t s) {
+  if (B <= 0 || B > (1LL << 31) || slots <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(score_finish_kernel, dim3((unsigned)((B + 3) / 4)), dim3(256), 0, s, value, index, B, V, part,
+                     slots, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_columns(const float* logprob, long long B, long long V, const long long* index, float* out,
+                                 hipStream_t s) {
+  if (B <= 0 || B > (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_columns_kernel, dim3((unsigned)((B + 255) / 256)), dim3(256), 0, s, logprob, B, V, index,
+                     out);
   return hipGetLastError();
 }
 

@@ -207,6 +207,11 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
     }
   }
 
+  // optional: the output row whose value is wanted on its own, per batch column
+  long long tg[NBT];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt) tg[bt] = (a.tgt && bok[bt]) ? a.tgt[bcol[bt]] : -1;
+
   float lse_m[NBT], lse_s[NBT];  // running (max, sum exp) of this lane's outputs, per tile
 #pragma unroll
   for (int bt = 0; bt < NBT; ++bt) {
@@ -293,7 +298,14 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
         }
         yv[r] = fmaf(4.0f, y, fmaf(sa[r], sbcx[bt], -pa[r] * sb[bt])) + bias[r];
       }
-      if (bok[bt]) {
+      if (a.tgt_out && bok[bt]) {  // (no accumulation in this use)
+        const long long d = tg[bt] - crow0;
+        if (d >= 0 && d < 4) {
+          const float yt = d == 0 ? yv[0] : d == 1 ? yv[1] : d == 2 ? yv[2] : yv[3];
+          if (crow0 + d < m) a.tgt_out[bcol[bt]] = yt;
+        }
+      }
+      if (a.Y && bok[bt]) {
         float* yp = a.Y + (long long)bcol[bt] * m + crow0;
         if (a.accumulate) {
 #pragma unroll
@@ -683,7 +695,7 @@ hipError_t launch_cell_kw(const BmvArgs& a, int k_w, int k_a, int nbt, hipStream
 // and enough row-block tasks to give every SIMD of the chip two of them; sizes whose element
 // offsets fit 32 bits.
 bool mfma4w_supported(const BmvArgs& a, int k_w, int k_a) {
-  if (a.D || a.groups > 1 || a.blk[0].n > 1024 || !a.Y) return false;
+  if (a.D || a.groups > 1 || a.blk[0].n > 1024 || (!a.Y && !(a.tgt && a.tgt_out))) return false;
   const int nbt = tiles_per_wave(k_w, k_a, a.batch);
   if (nbt == 0) return false;
   if (a.batch > 65535 * nbt * kTileB) return false;

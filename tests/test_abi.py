@@ -129,6 +129,16 @@ def test_validation_rejects_before_touching_the_device(L):
     assert lmq(bytes=need_q - 1) == INVALID
     assert lmq(steps=0) == INVALID
     assert lmq(ids=null) == INVALID
+    need_s = L.amq_lm_sequence_score_workspace_bytes(8, 8, 16, 1, 2, 3)
+    assert need_s > need_q
+    lms = lambda **kw: L.amq_lm_sequence_score(p, p, 10, 8, p, p, p, p, 8, 2, None, p, p, 16, 2, None, p,
+                                               kw.get("targets", p), kw.get("steps", 3), p, p, 1, 2, 3, 2,
+                                               kw.get("out", p), ws, kw.get("bytes", need_s), None)
+    assert lms(bytes=need_s - 1) == INVALID
+    assert lms(steps=0) == INVALID
+    assert lms(targets=null) == INVALID
+    assert lms(out=null) == INVALID
+    assert L.amq_lm_sequence_score_workspace_bytes(8, 8, 16, 0, 2, 3) == 0
 
 
 def test_binding_refuses_cpu_tensors():

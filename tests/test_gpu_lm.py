@@ -199,3 +199,66 @@ def test_lm_sequence(amq, E, H, V, B, k, k_ws, k_as, steps):
         assert_vec_close(got[t], ref[t], "logprob step %d" % t)
     assert_vec_close(host(dh), h, "h final")
     assert_vec_close(host(dc), c, "c final")
+
+
+@pytest.mark.parametrize("E,H,V,B,k,k_ws,k_as,steps", [
+    (300, 300, 10000, 1, 2, 2, 3, 5),         # batch 1, few rows: 64 rows at a time through the ordinary layer
+    (128, 256, 1000, 1, 3, 3, 3, 70),         # two pieces of the batch-1 recurrence
+    (200, 136, 555, 20, 2, 3, 2, 3),
+    (40, 24, 130, 1500, 2, 2, 2, 5),          # three passes of 3000, 3000 and 1500 rows, 64 rows at a time
+    (1024, 1024, 42000, 1, 2, 2, 2, 35),      # the 35 rows of a batch-1 sequence: logits never written
+    (1024, 1024, 42000, 64, 2, 2, 2, 3),      # 192 rows, logits never written
+    (64, 40, 33001, 40, 2, 2, 2, 2),          # ragged vocabulary above 32768, 80 rows
+])
+def test_lm_sequence_score(amq, E, H, V, B, k, k_ws, k_as, steps):
+    """Log-probability of given next words only, against the oracle's full log-probabilities."""
+    import torch
+    cfg = inputs.language_model(trial=E + B + steps + 1, steps=steps, B=B, H=H, E=E, vocab=V, k=k)
+    q = lm_setup(cfg, k_ws)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    g = np.random.default_rng(steps + B)
+    targets = g.integers(0, V, size=(steps, B)).astype(np.int64)
+    targets[0, 0] = 0
+    targets[-1, -1] = V - 1
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    ref = np.zeros((steps, B), np.float64)
+    for t in range(steps):
+        h, c, lp = lm_oracle_step(q, cfg["ids"][t], h, c, k_as)
+        ref[t] = lp[np.arange(B), targets[t]]
+    say("lm score E=%d H=%d V=%d B=%d steps=%d" % (E, H, V, B, steps))
+    dh = torch.zeros((B, H), device="cuda:0")
+    dc = torch.zeros((B, H), device="cuda:0")
+    out = torch.full((steps, B), float("nan"), device="cuda:0")
+    amq.lm_sequence_score(dq["Ep"], dq["ae"], E, dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], H, dq["bias"], dq["Wsp"],
+                          dq["as"], dq["bs"], torch.from_numpy(np.ascontiguousarray(cfg["ids"])).to("cuda:0"),
+                          torch.from_numpy(targets).to("cuda:0"), dh, dc, k, k_as, 2, out=out)
+    got = host(out).astype(np.float64)
+    # the bar of the full log-probabilities: 1e-4 relative plus 1e-4 of the row's r.m.s. (about log V)
+    tol = 1e-4 * np.abs(ref) + 1e-4 * np.log(V)
+    bad = ~(np.abs(got - ref) <= tol)
+    assert not bad.any(), "%d mismatches, worst %g" % (bad.sum(), np.abs(got - ref).max())
+    assert_vec_close(host(dh), h, "h final")
+    assert_vec_close(host(dc), c, "c final")
+
+
+def test_lm_sequence_score_index_outside_vocabulary(amq):
+    import torch
+    E, H, V, B, steps = 64, 40, 33001, 40, 1
+    cfg = inputs.language_model(trial=5, steps=steps, B=B, H=H, E=E, vocab=V, k=2)
+    q = lm_setup(cfg, 2)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    targets = np.full((steps, B), 7, np.int64)
+    targets[0, 3] = V
+    targets[0, 5] = -1
+    for Bsel in (B, 2):   # both forms of the output pass
+        dh = torch.zeros((Bsel, H), device="cuda:0")
+        dc = torch.zeros((Bsel, H), device="cuda:0")
+        ids = torch.from_numpy(np.ascontiguousarray(cfg["ids"][:, :Bsel])).to("cuda:0")
+        tg = targets[:, :Bsel].copy()
+        tg[0, 1] = V + 5
+        out = host(amq.lm_sequence_score(dq["Ep"], dq["ae"], E, dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], H, dq["bias"],
+                                         dq["Wsp"], dq["as"], dq["bs"], ids, torch.from_numpy(tg).to("cuda:0"), dh, dc, 2,
+                                         2, 2))
+        bad = (tg < 0) | (tg >= V)
+        assert np.isnan(out[bad]).all() and np.isfinite(out[~bad]).all()
