@@ -6,8 +6,10 @@
  * Conventions (all entry points):
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
  *   - The caller owns every buffer, including workspaces.  The library
- *     allocates nothing and keeps no state between calls.  Inputs are never
- *     modified.  Outputs must not alias inputs unless stated.
+ *     allocates nothing and keeps no results between calls (it remembers, per
+ *     device, which kernels it has configured and where its static scratch
+ *     lies).  Inputs are never modified.  Outputs must not alias inputs unless
+ *     stated.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise the host.
  *   - Return value: AMQ_OK, or an error code.  Arguments are validated on the
@@ -135,6 +137,23 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
                   const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
                   int T, float* h_out, float* c_out, void* workspace, size_t workspace_bytes,
                   void* stream);
+
+/*
+ * amq_lstm_step for callers that cannot allocate or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the
+ * workspace, same arithmetic and results.  The scratch memory is a static device array of
+ * AMQ_STATIC_SCRATCH_BYTES inside the library (every GPU the library runs on holds its own copy
+ * until the process ends); the call itself allocates nothing.  Shapes whose
+ * amq_lstm_workspace_bytes(I, H, B, k_a) exceeds AMQ_STATIC_SCRATCH_BYTES return
+ * AMQ_ERR_UNSUPPORTED.  All calls on one GPU share that GPU's array: calls that may overlap in
+ * time on one GPU (different streams, different host threads) race and must be serialised by
+ * the caller.  Nothing in the array is carried from one call to the next.
+ */
+#define AMQ_STATIC_SCRATCH_BYTES (4u << 20)
+int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                         const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                         const float* x, const float* h_prev, const float* c_prev, int64_t B, int k_a,
+                         int T, float* h_out, float* c_out, void* stream);
 
 /*
  * The same LSTM step on operands that are already quantized: x_t as packed planes Xp

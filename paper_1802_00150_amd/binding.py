@@ -17,7 +17,7 @@ EXPORTS = [
     "amq_wpr", "amq_version", "amq_status_string", "amq_last_hip_error",
     "amq_quantize_weights", "amq_quantize_activations", "amq_ls_update", "amq_bst_assign",
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
-    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_packed", "amq_lstm_sequence",
+    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed", "amq_lstm_sequence",
     "amq_lstm_sequence_flag_offset",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
@@ -62,6 +62,8 @@ def lib():
         L.amq_lstm_sequence_flag_offset.restype = _sz
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
                                     _p, _sz, _p]
+        L.amq_lstm_step_static.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
+                                           _p]
         L.amq_lstm_step_packed.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _i64, _int,
                                            _p, _p, _p]
         L.amq_lstm_sequence.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _i64, _p, _p, _i64, _int,
@@ -256,6 +258,20 @@ def lstm_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias, x, h_prev, c_prev, k_a, T,
                                _dev(h_prev, torch.float32), _dev(c_prev, torch.float32), B, k_a, T,
                                _dev(h_out, torch.float32), _dev(c_out, torch.float32), ws.data_ptr(),
                                ws.numel(), _stream()))
+    return h_out, c_out
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def lstm_step_static(Wxp, alpha_x, Whp, alpha_h, I, H, bias, x, h_prev, c_prev, k_a, T, h_out, c_out):
+    """lstm_step on the library's static scratch: the call allocates nothing, so the outputs are
+    arguments too."""
+    _check(lib().amq_lstm_step_static(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
+                                      _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, Wxp.shape[0],
+                                      _opt(bias), _dev(x, torch.float32), _dev(h_prev, torch.float32),
+                                      _dev(c_prev, torch.float32), x.shape[0], k_a, T,
+                                      _dev(h_out, torch.float32), _dev(c_out, torch.float32), _stream()))
     return h_out, c_out
 
 

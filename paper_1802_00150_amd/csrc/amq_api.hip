@@ -2,7 +2,14 @@
 // kernel launches on the caller's stream.  Nothing here allocates or synchronises.
 #include "../../include/amq.h"
 
+#include <mutex>
+
 #include "amq_launch.h"
+
+// Scratch memory of amq_lstm_step_static, part of the code object: one copy per GPU the library
+// runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and host calls take the per-device address it returns.
+static __device__ __align__(256) unsigned char scratch[AMQ_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -12,6 +19,28 @@ int hip_status(hipError_t e) {
   if (e == hipSuccess) return AMQ_OK;
   g_last_hip = (int)e;
   return AMQ_ERR_HIP;
+}
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_status(e);
+  if (dev < 0 || dev >= kMaxDevices) return AMQ_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_status(e);
+    if (!p) return AMQ_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AMQ_OK;
 }
 
 bool bits_ok(int k) { return k >= 1 && k <= AMQ_MAX_BITS; }
@@ -350,6 +379,26 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
                       workspace_bytes, need);
   if (st != AMQ_OK) return st;
   StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
+  return lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, x, h_prev, c_prev, B, k_a, T, h_out,
+                          c_out, nullptr, w, static_cast<hipStream_t>(stream));
+}
+
+int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                         int64_t I, int64_t H, int k_w, const float* bias, const float* x, const float* h_prev,
+                         const float* c_prev, int64_t B, int k_a, int T, float* h_out, float* c_out, void* stream) {
+  if (!c_prev || !c_out) return AMQ_ERR_INVALID;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
+  // (validated against a stand-in workspace address: the real one is looked up only for sizes that fit)
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out,
+                      reinterpret_cast<const void*>(uintptr_t(256)), need, need);
+  if (st != AMQ_OK) return st;
+  if (need > AMQ_STATIC_SCRATCH_BYTES) return AMQ_ERR_UNSUPPORTED;
+  void* ws = nullptr;
+  st = scratch_of_current_device(&ws);
+  if (st != AMQ_OK) return st;
+  // every region of the scratch that a step reads is written earlier in the same step (codes and
+  // coefficients by the quantizer, pre-activations by the first product), so nothing is cleared
+  StepWs w = carve(ws, I, H, B, k_a, 4, 1);
   return lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, x, h_prev, c_prev, B, k_a, T, h_out,
                           c_out, nullptr, w, static_cast<hipStream_t>(stream));
 }
