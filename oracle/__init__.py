@@ -28,7 +28,9 @@ _int = C.c_int
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build()
+        # AMQ_ORACLE_SANITIZE=1 (set by the sanitizer test for its child process) selects the build
+        # under AddressSanitizer / UndefinedBehaviorSanitizer
+        path = _build.build(sanitize=os.environ.get("AMQ_ORACLE_SANITIZE") == "1")
         L = C.CDLL(path)
         L.amq_oracle_set_threads.argtypes = [_int]
         L.amq_oracle_get_threads.restype = _int

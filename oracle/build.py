@@ -15,14 +15,28 @@ FLAGS = ["-O3", "-std=gnu99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
          "-Wall", "-Wextra"]
 
 
-def build(force: bool = False) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
-        return LIB
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    subprocess.check_call(["gcc", *FLAGS, SRC, "-o", tmp, "-lm"])
-    os.replace(tmp, LIB)
-    return LIB
+# The same source under AddressSanitizer and UndefinedBehaviorSanitizer (a second library, used only by
+# the sanitizer test: a process that loads it must have the sanitizer run-time preloaded).
+LIB_SANITIZED = os.path.join(HERE, "libamq_oracle_san.so")
+SANITIZE_FLAGS = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                  "-fno-sanitize-recover=undefined"]
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    lib = LIB_SANITIZED if sanitize else LIB
+    if not force and os.path.exists(lib) and os.path.getmtime(lib) >= os.path.getmtime(SRC):
+        return lib
+    flags = [f for f in FLAGS if f != "-O3"] + SANITIZE_FLAGS if sanitize else FLAGS
+    tmp = lib + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", *flags, SRC, "-o", tmp, "-lm"])
+    os.replace(tmp, lib)
+    return lib
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer run-time (to preload into a process that loads the sanitized library)."""
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    print(build(force="--force" in sys.argv, sanitize="--sanitize" in sys.argv))

@@ -47,6 +47,15 @@ def assert_vec_close(got, ref, what="y"):
     assert not bad.any(), "%s: %d mismatches, worst ratio %g" % (what, bad.sum(), (np.abs(got - ref) / tol).max())
 
 
+def worst_ratio(got, ref):
+    """Largest |got - ref| in units of the tolerance of assert_vec_close (1.0 = at the bar)."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    tol = 1e-4 * np.abs(ref) + 1e-4 * rms + 1e-30
+    return float((np.abs(got - ref) / tol).max())
+
+
 def unpack_bits(planes, n):
     k, rows, wpr = planes.shape
     b = np.unpackbits(np.ascontiguousarray(planes).view(np.uint8).reshape(k, rows, wpr * 4), axis=2,

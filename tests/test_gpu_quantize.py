@@ -144,24 +144,25 @@ def test_quantize_weights_strided_rows(amq):
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
-def test_weight_quantizer_heavy_tailed_full_size_sampled(amq, k):
+def test_weight_quantizer_heavy_tailed_full_size(amq, k):
     # Config 5 at full size (16384 x 4096, heavy tails) in the launch the benchmark times; the
-    # oracle recomputes a sample of rows (first, last, and a spread in between).
+    # oracle recomputes every row.
     W = heavy()
     say("weights 16384x4096 k=%d" % k)
     pg, ag = amq.quantize_weights(to_dev(W), k, 2)
-    rows = np.unique(np.concatenate([[0, 1, 16383], np.random.default_rng(k).integers(0, 16384, 96)]))
-    pr, ar = oracle.quantize_rows(W[rows], k, 2)
-    pgh = planes_host(pg)[:, rows]
-    flips, nrows = compare_codes(W[rows], pgh, pr, ar)
+    oracle.set_threads(oracle.host_threads())
+    pr, ar = oracle.quantize_rows(W, k, 2)
+    oracle.set_threads(1)
+    pgh = planes_host(pg)
+    flips, nrows = compare_codes(W, pgh, pr, ar)
     ok = ~(pgh != pr).any(axis=(0, 2))
-    assert_coef_close(host(ag)[rows][ok], ar[ok])
-    say("flips %d in %d rows" % (flips, nrows))
-    assert flips <= 2
+    assert_coef_close(host(ag)[ok], ar[ok])
+    say("config 5 k=%d: %d flipped entries (all near-ties) in %d of 16384 rows" % (k, flips, nrows))
+    assert flips <= 8
     # property that holds at any size: reconstruction error per row never above the greedy one
-    sel = rows[:16]
+    sel = np.unique(np.concatenate([[0, 1, 16383], np.random.default_rng(k).integers(0, 16384, 13)]))
     Wd = W[sel].astype(np.float64)
-    bits = np.unpackbits(pgh[:, :16].view(np.uint8), axis=2, bitorder="little")[:, :, :4096].astype(np.float64) * 2 - 1
+    bits = np.unpackbits(np.ascontiguousarray(pgh[:, sel]).view(np.uint8), axis=2, bitorder="little")[:, :, :4096].astype(np.float64) * 2 - 1
     rec = np.einsum("irn,ri->rn", bits, host(ag)[sel].astype(np.float64))
     err = ((Wd - rec) ** 2).sum(1)
     for t, r in enumerate(sel):
