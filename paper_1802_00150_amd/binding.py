@@ -11,7 +11,9 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libamq.so")
+# AMQ_LIBRARY (read once, at load) names another build of the same library, e.g. the profiling build
+# libamq_phases.so with in-kernel phase timers
+LIB_PATH = os.environ.get("AMQ_LIBRARY") or os.path.join(_HERE, "libamq.so")
 
 EXPORTS = [
     "amq_wpr", "amq_version", "amq_status_string", "amq_last_hip_error",

@@ -8,8 +8,43 @@ namespace amq {
 
 constexpr int kWave = 64;
 
+// Phase timers of the profiling build (-DAMQ_PHASE_TIMING, a separate library; see build.py): lane 0
+// of every wave of workgroup (0, 0) stores the shader clock at mark `id` in buf[wave * 32 + id].  In the
+// ordinary build the marks expand to nothing.
+#ifdef AMQ_PHASE_TIMING
+#define AMQ_PHASE(buf, id)                                                                      \
+  do {                                                                                          \
+    if ((buf) && blockIdx.x == 0 && blockIdx.y == 0 && (threadIdx.x & 63) == 0)                 \
+      (buf)[(threadIdx.x >> 6) * 32 + (id)] = __builtin_readcyclecounter();                     \
+  } while (0)
+#else
+#define AMQ_PHASE(buf, id) \
+  do {                     \
+  } while (0)
+#endif
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
+
+// Kernel arguments arrive through scalar loads that the compiler otherwise issues one by one, each
+// just before its first use and each followed by its own wait -- in a latency-bound kernel a chain of
+// memory round trips before the first vector load can be issued.  Naming the arguments in one empty
+// asm statement at the top of the kernel makes all those loads issue back to back behind one wait.
+#define AMQ_ARG(x) "s"(x)
+
+// Workgroup barrier for exchanges through LDS only.  __syncthreads() also orders global memory at
+// workgroup scope, which on this target means waiting until every outstanding global load of the wave
+// has returned; kernels that keep loads in flight across a staging step use this instead.  LDS writes
+// issued before it are visible to the other waves after it; global memory is not ordered by it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Sum over aligned groups of 8 lanes (DPP, no LDS traffic); every lane of a group ends with the total.
+__device__ __forceinline__ int sum8(int v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true);   // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true);   // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+  return v;
+}
 
 // Butterfly sums over the 64 lanes; every lane ends with the total.
 __device__ __forceinline__ double wave_sum(double v) {

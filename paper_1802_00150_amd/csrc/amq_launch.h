@@ -5,7 +5,39 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace amq {
+
+// Raises the dynamic-LDS limit of kernel `fn` to `bytes` the first time it is launched on the current
+// device.  `done` is the kernel instantiation's own mask of devices already configured (thread-safe;
+// devices numbered 64 and above are configured at every launch).
+inline hipError_t ensure_dynamic_lds(const void* fn, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool tracked = dev >= 0 && dev < 64;
+  if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  if (tracked) done.fetch_or(1ull << dev, std::memory_order_release);
+  return hipSuccess;
+}
+
+#ifdef AMQ_PHASE_TIMING
+// Profiling build only: the device buffer the phase timers write to (null: timers off), set through
+// the extra entry point amq_debug_set_phase_buffer of that build.
+unsigned long long* phase_buffer();
+#define AMQ_PHASE_MEMBER unsigned long long* phase;
+#define AMQ_PHASE_ATTACH(args) (args).phase = ::amq::phase_buffer()
+#define AMQ_PHASE_OF(args) (args).phase
+#else
+#define AMQ_PHASE_MEMBER
+#define AMQ_PHASE_ATTACH(args) \
+  do {                         \
+  } while (0)
+#define AMQ_PHASE_OF(args) nullptr
+#endif
 
 // ---- quantizer -------------------------------------------------------------------------
 enum { kQuantFull = 0, kQuantLsOnly = 1, kQuantBstOnly = 2 };
@@ -40,6 +72,7 @@ struct QuantArgs {
   int T;
   int mode;
   GatherSeg gather;
+  AMQ_PHASE_MEMBER
 };
 
 hipError_t launch_quantize(const QuantArgs& a, int k, hipStream_t s);
@@ -116,6 +149,12 @@ struct BmvArgs {
   float* h_out;
   float* c_out;
   float* hs_out;        // LSTM, nullable
+  // Cell modes, pipelined form (fp4 kernel with paired waves only; both null otherwise): the input-side
+  // pre-activations of THIS step are read from pre_in, [batch][H][4] (gate-interleaved, without bias;
+  // null: this launch computes no new state), while blk[0] holds the quantized inputs of the NEXT step
+  // and its pre-activations are written to pre_out in the same layout (null: nothing to prepare).
+  const float* pre_in;
+  float* pre_out;
   float* lse_part;      // store mode, nullable: per batch entry and slot a (max, sum exp(y - max)) pair over
                         // the outputs one wave produced, [batch][lse_slots][2]
   int lse_slots;        // filled by the launcher: slots per batch entry
@@ -125,6 +164,7 @@ struct BmvArgs {
   int lg;               // filled by launch_bmv
   int groups;           // store mode: independent products in one launch (1 otherwise)
   long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
+  AMQ_PHASE_MEMBER
 };
 
 // Most (max, sum) slots per batch entry worth merging afterwards; a launch that would need more
@@ -141,6 +181,9 @@ bool mfma_supported(long long batch);
 hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 // fp4 matrix-core kernel for vectors of at most 1024 entries (the fast path)
 bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
+// true if a recurrent step of this shape runs in the paired-wave form, which also has the pipelined
+// mode (pre_in / pre_out above)
+bool mfma4_pipelined_supported(const BmvArgs& a, int k_w, int k_a, int epi);
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 // the same instruction with several batch tiles per wave: plain products with many rows and
 // at least 32 columns (store mode only)

@@ -55,9 +55,10 @@ __device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
   return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
 }
 
-template <int KW, int KA, int EPI, int NWV, bool SPLIT = false>
+template <int KW, int KA, int EPI, int NWV, bool SPLIT = false, bool PIPE = false>
 __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_wg, int rowblocks) {
   static_assert(!SPLIT || (EPI != kEpiStore && NWV % 2 == 0), "SPLIT pairs the waves over the two operand blocks");
+  static_assert(!PIPE || SPLIT, "the pipelined form is a variant of the paired-wave form");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
   constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
@@ -71,6 +72,15 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform to the compiler
   const int l16 = lane & 15, l4 = lane >> 4;
+  // phase timers of the profiling build: 0 start, 1 loads issued, 9 own part of the tile staged, 2 barrier passed,
+  // 3 column coefficients read, 4 row coefficients spread, 10 weight words used, 5 contraction, 6 epilogue, 7 exchange, 8 cell
+  AMQ_PHASE(AMQ_PHASE_OF(a), 0);
+  asm volatile("" ::AMQ_ARG(a.blk[0].Wp), AMQ_ARG(a.blk[0].alpha), AMQ_ARG(a.blk[0].Xp), AMQ_ARG(a.blk[0].beta),
+               AMQ_ARG(a.blk[0].n), AMQ_ARG(a.blk[NBLK - 1].Wp), AMQ_ARG(a.blk[NBLK - 1].alpha),
+               AMQ_ARG(a.blk[NBLK - 1].Xp), AMQ_ARG(a.blk[NBLK - 1].beta), AMQ_ARG(a.blk[NBLK - 1].n), AMQ_ARG(a.m),
+               AMQ_ARG(a.H), AMQ_ARG(a.batch), AMQ_ARG(a.bias0), AMQ_ARG(a.bias1), AMQ_ARG(a.c_prev), AMQ_ARG(a.h_prev),
+               AMQ_ARG(a.h_out), AMQ_ARG(a.c_out), AMQ_ARG(a.hs_out), AMQ_ARG(a.pre_in), AMQ_ARG(a.pre_out), AMQ_ARG(a.Y),
+               AMQ_ARG(a.accumulate), AMQ_ARG(rb_per_wg), AMQ_ARG(rowblocks));
   const int b0 = blockIdx.y * kTileB;
   const int batch = a.batch;
   const int m = (int)a.m, H = (int)a.H;
@@ -95,9 +105,18 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   // SPLIT (cell modes): the two operand blocks of a row block go to two waves (kb = 0: x block and
   // the cell, kb = 1: h block), which halves the dependent work per wave when there are too few
   // row blocks to give every SIMD more than one wave anyway.  The h-block sums cross through LDS.
+  //
+  // PIPE (sequences): the input side does not depend on the recurrence, so the x waves work one step
+  // ahead -- they form W_x q(x_{t+1}) and leave it in memory (pre_out), while the h waves form
+  // W_h q(h_{t-1}), add the input side of this step that the previous launch left (pre_in) and apply
+  // the cell.  Nothing crosses between the two waves of a pair, and the h waves, which the next
+  // launch waits for, run at raised priority.  Waves w and w + NWV / 2 (same SIMD) form a pair.
   constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;  // row blocks a workgroup has in flight
-  const int wr = SPLIT ? (wv >> 1) : wv;
-  const int kb = SPLIT ? (wv & 1) : 0;
+  const int wr = PIPE ? (wv % NSLOT) : SPLIT ? (wv >> 1) : wv;
+  const int kb = PIPE ? (wv / NSLOT) : SPLIT ? (wv & 1) : 0;
+  if constexpr (PIPE) {
+    if (kb == 1) __builtin_amdgcn_s_setprio(3);
+  }
   float4* xch = reinterpret_cast<float4*>(smem + NBLK * kTileBytes + 16 * ((NBLK * KA * kTileB * 4 + 15) / 16));
 
   // A-operand view of row block rb: lane = (tile row l16, k-block l4)
@@ -145,44 +164,78 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       if (!cok[r]) crow[r] = 0;
     }
   };
-  auto load_alpha = [&](auto kc, const int (&crow)[4], float (&alr)[4][KW]) {
+  // Row coefficients of the C view: the 16 lanes of a row quad (same l4) need the same 4 * KW values,
+  // so lane l16 < 4 * KW requests one of them (one load per wave instead of 4 * KW) and
+  // spread_alpha hands them round through the cross-lane network.
+  auto request_alpha = [&](auto kc, int rb) -> float {
     constexpr int k = decltype(kc)::value;
+    const int r = l16 / KW, i = l16 % KW;
+    int row;
+    bool ok;
+    if constexpr (EPI == kEpiStore) {
+      row = rb * 16 + 4 * l4 + r;
+      ok = r < 4 && row < m;
+    } else {
+      const int unit = rb * 4 + l4;
+      ok = r < NG && unit < H;
+      row = r * H + unit;
+    }
+    return alpha[k][(ok ? row : 0) * KW + i];
+  };
+  auto spread_alpha = [&](float mine, float (&alr)[4][KW]) {
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
-      for (int i = 0; i < KW; ++i) alr[r][i] = alpha[k][crow[r] * KW + i];
+      for (int i = 0; i < KW; ++i) alr[r][i] = __shfl(mine, 16 * l4 + r * KW + i, kWave);
+  };
+  // biases of the C view rows the same way: lanes l16 = 0..3 request bias0, 4..7 bias1
+  auto request_bias = [&](int rb) -> float {
+    const float* src = (l16 & 4) ? ((EPI == kEpiGru) ? a.bias1 : nullptr) : a.bias0;
+    const int r = l16 & 3;
+    int row;
+    bool ok;
+    if constexpr (EPI == kEpiStore) {
+      row = rb * 16 + 4 * l4 + r;
+      ok = row < m;
+    } else {
+      const int unit = rb * 4 + l4;
+      ok = r < NG && unit < H;
+      row = r * H + unit;
+    }
+    return (src && l16 < 8) ? src[ok ? row : 0] : 0.0f;
   };
   using K0 = std::integral_constant<int, 0>;
   using K1 = std::integral_constant<int, NBLK - 1>;
 
-  const int iters = (rb_end - rb_first + NSLOT - 1) / NSLOT;  // SPLIT: the same trip count for every wave
+  // SPLIT workgroups take exactly NSLOT row blocks (one pass: a second request site for the operands
+  // costs more registers than the kernel has); the launcher guarantees it
+  const int iters = SPLIT ? 1 : (rb_end - rb_first + NSLOT - 1) / NSLOT;
 
   // SPLIT: everything a wave's row block needs from memory, requested at the top of the pass
   // (requesting it before the activation tile is staged was measured slower)
   struct Ahead {
     uint4 araw[KW][2];
-    float alr[4][KW];
-    int crow[4];
-    bool cok[4];
-    float bias0[4], bias1[4], prev;
+    float alpha_req, bias_req, prev;
+    float4 pre;  // PIPE: input-side pre-activations of this lane's unit and batch column
   } nx{};
+  constexpr int kCellWave = PIPE ? 1 : 0;  // which wave of a pair applies the cell
   auto fetch_rowblock = [&](int rb) {
     if (rb >= rb_end) return;
-    c_rows(rb, nx.crow, nx.cok);
     if (kb == 0) {
       load_a(K0{}, rb, nx.araw);
-      load_alpha(K0{}, nx.crow, nx.alr);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        nx.bias0[r] = a.bias0 ? a.bias0[nx.crow[r]] : 0.0f;
-        nx.bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[nx.crow[r]] : 0.0f;
-      }
-      nx.prev = 0.0f;
-      if constexpr (EPI == kEpiLstm) nx.prev = a.c_prev[bc * H + nx.crow[0]];
-      if constexpr (EPI == kEpiGru) nx.prev = a.h_prev[bc * H + nx.crow[0]];
+      nx.alpha_req = request_alpha(K0{}, rb);
     } else {
       load_a(K1{}, rb, nx.araw);
-      load_alpha(K1{}, nx.crow, nx.alr);
+      nx.alpha_req = request_alpha(K1{}, rb);
+    }
+    if (kb == kCellWave) {
+      nx.bias_req = request_bias(rb);
+      const int unit = rb * 4 + l4;  // (cell modes: the C view's hidden unit)
+      const int t = bc * H + (unit < H ? unit : 0);
+      nx.prev = 0.0f;
+      if constexpr (EPI == kEpiLstm) nx.prev = a.c_prev[t];
+      if constexpr (EPI == kEpiGru) nx.prev = a.h_prev[t];
+      if constexpr (PIPE) nx.pre = reinterpret_cast<const float4*>(a.pre_in)[t];
     }
   };
 
@@ -201,18 +254,29 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       xw[k][it] = valid ? v : make_uint4(0, 0, 0, 0);
     }
   }
-  if (tid < NBLK * KA * kTileB) pops[tid] = 0;
-  __syncthreads();
+  // column coefficients: lane (l16, l4) requests beta[column l16][plane min(l4, KA - 1)] of every block
+  float beta_req[NBLK];
+#pragma unroll
+  for (int k = 0; k < NBLK; ++k) beta_req[k] = a.blk[k].beta[bc * KA + (l4 < KA ? l4 : KA - 1)];
+  // SPLIT: everything this wave's first row block needs from memory is requested now, behind the
+  // activation words, and arrives while the tile is being staged (the barrier below does not wait for it)
+  // (PIPE: a launch may have only one of the two kinds of waves at work)
+  const bool idle = PIPE && (kb == 0 ? a.pre_out == nullptr : a.pre_in == nullptr);
+  if constexpr (SPLIT) {
+    if (!idle) fetch_rowblock(rb_first + wr);
+  }
+  AMQ_PHASE(AMQ_PHASE_OF(a), 1);
 #pragma unroll
   for (int k = 0; k < NBLK; ++k) {
 #pragma unroll
     for (int it = 0; it < kIter; ++it) {
       const int e = tid + it * 64 * NWV;
+      const int q = e & 7, nn = (e >> 3) & (kTileB - 1), j = e >> 7;
+      const uint4 w4 = xw[k][it];
+      // popcount of the row: its 8 groups sit in 8 consecutive lanes
+      const int pc = sum8(__popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w));
       if (e < kItems) {
-        const int q = e & 7, nn = (e >> 3) & (kTileB - 1), j = e >> 7;
-        const uint4 w4 = xw[k][it];
-        const int pc = __popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w);
-        if (pc) atomicAdd(&pops[(k * KA + j) * kTileB + nn], pc);
+        if (q == 0) pops[(k * KA + j) * kTileB + nn] = pc;
         // words 4q .. 4q+3 of the row: k-block q >> 1, steps 4 * (q & 1) + 0..3
         uint4* dst = reinterpret_cast<uint4*>(btile + k * kTileBytes + j * kPlaneBytes +
                                               ((4 * (q & 1)) * kTileB + nn) * 64 + (q >> 1) * 16);
@@ -223,7 +287,10 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       }
     }
   }
-  __syncthreads();
+  AMQ_PHASE(AMQ_PHASE_OF(a), 9);
+  lds_barrier();
+  AMQ_PHASE(AMQ_PHASE_OF(a), 2);
+  if (idle) return;
 
   float btv[NBLK][KA];
   float cx[NBLK][KA];  // n - 2 * popc(activation plane): the column-only part of the dot product
@@ -231,10 +298,11 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   for (int k = 0; k < NBLK; ++k)
 #pragma unroll
     for (int j = 0; j < KA; ++j) {
-      btv[k][j] = a.blk[k].beta[bc * KA + j];
+      btv[k][j] = __shfl(beta_req[k], 16 * j + l16, kWave);
       cx[k][j] = (float)(nlen[k] - 2 * pops[(k * KA + j) * kTileB + l16]);
     }
 
+  AMQ_PHASE(AMQ_PHASE_OF(a), 3);
   float lse_m = kLseLow, lse_s = 0.0f;  // store mode: running (max, sum exp) of this lane's outputs
   float* const lse_part = (EPI == kEpiStore) ? a.lse_part : nullptr;
 
@@ -257,6 +325,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       for (int r = 0; r < 4; ++r) pw2[i][r] = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
     }
 
+    AMQ_PHASE(AMQ_PHASE_OF(a), 10);
     v4f acc[KW][KA];
 #pragma unroll
     for (int i = 0; i < KW; ++i)
@@ -306,6 +375,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     for (int i = 0; i < KW; ++i)
 #pragma unroll
       for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
+    AMQ_PHASE(AMQ_PHASE_OF(a), 5);
     // block epilogue in the C view: lane = (batch column l16, row quad l4), with
     //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j))   (integers below 2^24: exact in binary32)
     //   y = sum_i alpha_i sum_j beta_j d_ij.
@@ -373,47 +443,66 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     bool cok[4];
     float bias0[4], bias1[4], yold[4], prev = 0.0f;
     if (live) {
-      if constexpr (!SPLIT) c_rows(rb, crow, cok);
       if constexpr (SPLIT) {
-        fetch_rowblock(rb);
-        const Ahead& cur = nx;
+        // (this row block's operands were requested in the prologue)
+        c_rows(rb, crow, cok);
+        float alr[4][KW];
+        spread_alpha(nx.alpha_req, alr);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          crow[r] = cur.crow[r];
-          cok[r] = cur.cok[r];
-          bias0[r] = cur.bias0[r];
-          bias1[r] = cur.bias1[r];
+          bias0[r] = __shfl(nx.bias_req, 16 * l4 + r, kWave);
+          bias1[r] = __shfl(nx.bias_req, 16 * l4 + 4 + r, kWave);
         }
-        prev = cur.prev;
+        prev = nx.prev;
+        AMQ_PHASE(AMQ_PHASE_OF(a), 4 + 8 * it);
         if (kb == 0) {
-          run_block(K0{}, cur.araw, cur.alr, crow, cok, ysum[0]);
+          run_block(K0{}, nx.araw, alr, crow, cok, ysum[0]);
+          if constexpr (PIPE) {
+            // the next step's input side, gate-interleaved: one 16-byte store per lane
+            if (bok && cok[0])
+              reinterpret_cast<float4*>(a.pre_out)[b * H + crow[0]] = make_float4(ysum[0][0], ysum[0][1], ysum[0][2], ysum[0][3]);
+          }
         } else {
-          run_block(K1{}, cur.araw, cur.alr, crow, cok, ysum[NBLK - 1]);
-          xch[((it & 1) * NSLOT + wr) * 64 + lane] = make_float4(ysum[NBLK - 1][0], ysum[NBLK - 1][1],
-                                                                 ysum[NBLK - 1][2], ysum[NBLK - 1][3]);
+          run_block(K1{}, nx.araw, alr, crow, cok, ysum[NBLK - 1]);
+          if constexpr (PIPE) {
+            ysum[0][0] = nx.pre.x; ysum[0][1] = nx.pre.y; ysum[0][2] = nx.pre.z; ysum[0][3] = nx.pre.w;
+          } else {
+            xch[((it & 1) * NSLOT + wr) * 64 + lane] = make_float4(ysum[NBLK - 1][0], ysum[NBLK - 1][1],
+                                                                   ysum[NBLK - 1][2], ysum[NBLK - 1][3]);
+          }
         }
       } else {
+        c_rows(rb, crow, cok);
         uint4 araw[NBLK][KW][2];
         float alr[NBLK][4][KW];
         load_a(K0{}, rb, araw[0]);
         if constexpr (NBLK == 2) load_a(K1{}, rb, araw[NBLK - 1]);
-        load_alpha(K0{}, crow, alr[0]);
-        if constexpr (NBLK == 2) load_alpha(K1{}, crow, alr[NBLK - 1]);
+        const float alpha_req0 = request_alpha(K0{}, rb);
+        const float alpha_req1 = (NBLK == 2) ? request_alpha(K1{}, rb) : 0.0f;
+        const float bias_req = request_bias(rb);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          bias0[r] = a.bias0 ? a.bias0[crow[r]] : 0.0f;
-          bias1[r] = (EPI == kEpiGru && a.bias1) ? a.bias1[crow[r]] : 0.0f;
+        for (int r = 0; r < 4; ++r)
           yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
-        }
         if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
         if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
+        spread_alpha(alpha_req0, alr[0]);
+        if constexpr (NBLK == 2) spread_alpha(alpha_req1, alr[NBLK - 1]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          bias0[r] = __shfl(bias_req, 16 * l4 + r, kWave);
+          bias1[r] = __shfl(bias_req, 16 * l4 + 4 + r, kWave);
+        }
         run_block(K0{}, araw[0], alr[0], crow, cok, ysum[0]);
         if constexpr (NBLK == 2) run_block(K1{}, araw[NBLK - 1], alr[NBLK - 1], crow, cok, ysum[NBLK - 1]);
       }
     }
-    if constexpr (SPLIT) {
-      __syncthreads();  // (alternating exchange buffers: one barrier per iteration suffices)
-      if (!live || kb != 0) continue;
+    AMQ_PHASE(AMQ_PHASE_OF(a), 6 + 8 * it);
+    if constexpr (PIPE) {
+      if (!live || kb != kCellWave) continue;
+    } else if constexpr (SPLIT) {
+      lds_barrier();  // (alternating exchange buffers: one barrier per iteration suffices)
+      AMQ_PHASE(AMQ_PHASE_OF(a), 7 + 8 * it);
+      if (!live || kb != kCellWave) continue;
       const float4 o = xch[((it & 1) * NSLOT + wr) * 64 + lane];
       ysum[NBLK - 1][0] = o.x; ysum[NBLK - 1][1] = o.y; ysum[NBLK - 1][2] = o.z; ysum[NBLK - 1][3] = o.w;
     }
@@ -458,6 +547,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
         a.h_out[t] = h;
         if (a.hs_out) a.hs_out[t] = h;
       }
+      AMQ_PHASE(AMQ_PHASE_OF(a), 8 + 8 * it);
     } else {
       if (bok && cok[0]) {
         const int t = b * H + crow[0];
@@ -486,26 +576,26 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   }
 }
 
-template <int KW, int KA, int EPI, int NWV, bool SPLIT = false>
+template <int KW, int KA, int EPI, int NWV, bool SPLIT = false, bool PIPE = false>
 hipError_t launch_one(BmvArgs a, int rowblocks, int rb_per_wg, hipStream_t s, int* lse_slots) {
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
   constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;
   // activation tiles, their popcounts (padded to 16 bytes), and the exchange buffers of SPLIT
   const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + 16 * ((sizeof(int) * NBLK * KA * kTileB + 15) / 16) +
-                     (SPLIT ? sizeof(float4) * 2 * NSLOT * 64 : 0);
-  static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV, SPLIT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                     (SPLIT && !PIPE ? sizeof(float4) * 2 * NSLOT * 64 : 0);
+  static std::atomic<unsigned long long> configured{0};
+  {
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV, SPLIT, PIPE>), (int)lds, configured);
     if (e != hipSuccess) return e;
-    configured = true;
   }
+  AMQ_PHASE_ATTACH(a);
+  if (SPLIT && rb_per_wg != NSLOT) return hipErrorInvalidValue;  // the paired-wave form is single-pass
   dim3 grid((unsigned)((rowblocks + rb_per_wg - 1) / rb_per_wg), (unsigned)((a.batch + kTileB - 1) / kTileB));
   const long long slots = (long long)grid.x * NWV;  // one per wave of a batch tile's workgroups
   if (EPI != kEpiStore || slots > kLseMaxSlots || slots > a.lse_cap) a.lse_part = nullptr;
   a.lse_slots = (int)slots;
   if (lse_slots) *lse_slots = a.lse_part ? (int)slots : 0;
-  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV, SPLIT>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
+  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV, SPLIT, PIPE>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
   return hipGetLastError();
 }
 
@@ -518,7 +608,11 @@ hipError_t launch_mode(const BmvArgs& a, hipStream_t s, int* lse_slots) {
     // four row blocks per 8-wave workgroup
     // (up to 3 weight planes and 9 plane pairs: beyond that the paired kernel no longer fits 256 registers)
     if constexpr (KW <= 3 && KW * KA <= 9)
-      if ((long long)rowblocks * btiles <= 2048) return launch_one<KW, KA, EPI, 8, true>(a, rowblocks, 4, s, lse_slots);
+      if ((long long)rowblocks * btiles <= 2048) {
+        if (a.pre_in || a.pre_out) return launch_one<KW, KA, EPI, 8, true, true>(a, rowblocks, 4, s, lse_slots);
+        return launch_one<KW, KA, EPI, 8, true>(a, rowblocks, 4, s, lse_slots);
+      }
+    if (a.pre_in || a.pre_out) return hipErrorInvalidValue;  // (callers ask mfma4_pipelined_supported first)
   }
   // about two workgroups per CU; each expands its activation tile once and then walks row blocks
   int splits = (512 + btiles - 1) / btiles;
@@ -562,6 +656,12 @@ bool mfma4_supported(const BmvArgs& a, int k_w, int epi) {
   if (a.m * 8 * k_w >= (1LL << 31)) return false;       // weight offsets in 16-byte units
   if ((long long)a.batch * (a.m > a.H ? a.m : a.H) >= (1LL << 31)) return false;
   return true;
+}
+
+bool mfma4_pipelined_supported(const BmvArgs& a, int k_w, int k_a, int epi) {
+  if (epi == kEpiStore || !mfma4_supported(a, k_w, epi)) return false;
+  const long long rowblocks = (a.H + 3) / 4, btiles = (a.batch + kTileB - 1) / kTileB;
+  return k_w <= 3 && k_w * k_a <= 9 && rowblocks * btiles <= 2048;
 }
 
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots) {

@@ -559,12 +559,10 @@ hipError_t launch_one(BmvArgs a, hipStream_t s, int* lse_slots) {
     per = (per + 3) / 4 * 4;
     if (per < kWaves) per = kWaves;
     const size_t lds = (size_t)NBT * KA * kPlaneBytes + sizeof(int) * NBT * KA * kTileB;
-    static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
-    if (!configured) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4w_kernel<KW, KA, NBT>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<unsigned long long> configured{0};
+    {
+      hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4w_kernel<KW, KA, NBT>), (int)lds, configured);
       if (e != hipSuccess) return e;
-      configured = true;
     }
     dim3 grid((unsigned)((rowblocks + per - 1) / per), (unsigned)groups);
     const long long slots = grid.x;  // one per workgroup of a batch group
@@ -644,12 +642,11 @@ hipError_t launch_cell_one(const BmvArgs& a, hipStream_t s) {
     per = (per + 3) / 4 * 4;
     if (per < NWV) per = NWV;
     const size_t lds = (size_t)2 * NBT * KA * kPlaneBytes + sizeof(int) * 2 * NBT * KA * kTileB;
-    static bool configured = false;  // raise the dynamic-LDS limit of this instantiation once
-    if (!configured) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mfma4wc_kernel<KW, KA, NBT, EPI, NWV>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<unsigned long long> configured{0};
+    {
+      hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4wc_kernel<KW, KA, NBT, EPI, NWV>), (int)lds,
+                                        configured);
       if (e != hipSuccess) return e;
-      configured = true;
     }
     dim3 grid((unsigned)((rowblocks + per - 1) / per), (unsigned)groups);
     hipLaunchKernelGGL((mfma4wc_kernel<KW, KA, NBT, EPI, NWV>), grid, dim3(64 * NWV), lds, s, a, per, rowblocks);

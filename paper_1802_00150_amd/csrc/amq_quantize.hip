@@ -40,6 +40,11 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
   __shared__ double sh[2][16 * kMaxRed];
   int phase = 0;
   const int lane = lane_id(), wv = wave_id();
+  AMQ_PHASE(AMQ_PHASE_OF(a), 0);
+  asm volatile("" ::AMQ_ARG(a.seg[0].X), AMQ_ARG(a.seg[0].ld), AMQ_ARG(a.seg[0].n), AMQ_ARG(a.seg[0].count),
+               AMQ_ARG(a.seg[0].planes), AMQ_ARG(a.seg[0].coef), AMQ_ARG(a.seg[1].X), AMQ_ARG(a.seg[1].ld),
+               AMQ_ARG(a.seg[1].n), AMQ_ARG(a.seg[1].count), AMQ_ARG(a.seg[1].planes), AMQ_ARG(a.seg[1].coef),
+               AMQ_ARG(a.T), AMQ_ARG(a.mode), AMQ_ARG(a.gather.count));
   int vec = blockIdx.x;
   if (vec >= a.seg[0].count + a.seg[1].count) {
     // workgroups past the vectors to quantize copy table rows by index
@@ -102,8 +107,10 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
     for (int i = 0; i < K; ++i) alpha[i] = coef[(long long)vec * K + i];
   }
 
+  AMQ_PHASE(AMQ_PHASE_OF(a), 1);
   quantize_core<K, NJ, NW>(w, n, base, nj, a.mode == kQuantFull, a.mode == kQuantFull ? a.T : 1,
-                           a.mode != kQuantBstOnly, a.mode != kQuantLsOnly, alpha, mym, q, sh, phase);
+                           a.mode != kQuantBstOnly, a.mode != kQuantLsOnly, alpha, mym, q, sh, phase,
+                           AMQ_PHASE_OF(a));
 
   if (a.mode != kQuantLsOnly) {
 #pragma unroll
@@ -115,10 +122,12 @@ __global__ __launch_bounds__(64 * NW) void quantize_kernel(QuantArgs a) {
 #pragma unroll
     for (int i = 0; i < K; ++i) coef[(long long)vec * K + i] = alpha[i];
   }
+  AMQ_PHASE(AMQ_PHASE_OF(a), 31);
 }
 
 template <int K, int NJ, int NW>
-void launch_one(const QuantArgs& a, int total, hipStream_t s) {
+void launch_one(QuantArgs a, int total, hipStream_t s) {
+  AMQ_PHASE_ATTACH(a);
   hipLaunchKernelGGL((quantize_kernel<K, NJ, NW>), dim3(total), dim3(64 * NW), 0, s, a);
 }
 

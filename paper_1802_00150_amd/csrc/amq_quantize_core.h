@@ -95,6 +95,47 @@ __device__ __forceinline__ void ls_solve(const int (&G)[K][K], const double (&q)
   }
 }
 
+// 1 / d for an integer-valued d != 0 far from the ends of the exponent range: hardware estimate
+// and two Newton steps (error below one unit in the last place of binary64, which disappears when
+// the coefficients are rounded to binary32).
+__device__ __forceinline__ double recip_f64(double d) {
+  double r = __builtin_amdgcn_rcp(d);
+  r = __builtin_fma(r, __builtin_fma(-d, r, 1.0), r);
+  r = __builtin_fma(r, __builtin_fma(-d, r, 1.0), r);
+  return r;
+}
+
+// Eq. 5 on the vector unit in binary64 for K <= 3, from the disagreement counts d[t] of the plane
+// pairs (order (0,1), (0,2), (1,2)): G_ij = n - 2 d_ij, cofactors and determinant are integers below
+// 2^45 for n <= 16384 and therefore exact in binary64 (same values as the integer cofactors of
+// ls_solve); alpha_i = (sum_j cof_ji q_j) / det.  A singular G leaves alpha unchanged.
+template <int K>
+__device__ __forceinline__ void ls_solve_f64(int n, const double* d, const double (&q)[K], float (&alpha)[K]) {
+  static_assert(K >= 1 && K <= 3, "binary64 cofactors are exact up to K = 3");
+  const double dn = (double)n;
+  if constexpr (K == 1) {
+    alpha[0] = (float)(q[0] / dn);
+  } else if constexpr (K == 2) {
+    const double a = dn - 2.0 * d[0];
+    const double det = dn * dn - a * a;
+    if (det == 0.0) return;
+    const double inv = recip_f64(det);
+    alpha[0] = (float)((dn * q[0] + (-a) * q[1]) * inv);
+    alpha[1] = (float)(((-a) * q[0] + dn * q[1]) * inv);
+  } else {
+    const double a = dn - 2.0 * d[0], b = dn - 2.0 * d[1], c = dn - 2.0 * d[2];
+    const double nn = dn * dn;
+    const double c00 = nn - c * c, c01 = c * b - a * dn, c02 = a * c - dn * b;
+    const double c11 = nn - b * b, c12 = a * b - dn * c, c22 = nn - a * a;
+    const double det = dn * c00 + a * c01 + b * c02;
+    if (det == 0.0) return;
+    const double inv = recip_f64(det);
+    alpha[0] = (float)((c00 * q[0] + c01 * q[1] + c02 * q[2]) * inv);
+    alpha[1] = (float)((c01 * q[0] + c11 * q[1] + c12 * q[2]) * inv);
+    alpha[2] = (float)((c02 * q[0] + c12 * q[1] + c22 * q[2]) * inv);
+  }
+}
+
 __device__ __forceinline__ float readlane_f(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
@@ -102,8 +143,14 @@ __device__ __forceinline__ float readlane_f(float v, int l) {
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ double dpp_d(double v) {
   int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
-  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+  if constexpr (ROW_MASK == 0xf) {
+    // every lane is written from a valid lane: no previous value to keep, no register to clear
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, true);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, true);
+  } else {
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, ROW_MASK, 0xf, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, ROW_MASK, 0xf, false);
+  }
   return __hiloint2double(hi, lo);
 }
 
@@ -155,6 +202,206 @@ __device__ __forceinline__ void block_totals(double (&v)[NV], double (*sh)[16 * 
   }
 }
 
+// Totals over the workgroup of NQ per-lane doubles q and of NC values c that are already totals of
+// their wave (wave-uniform); results in q and c.  One LDS barrier.
+template <int NW, int NQ, int NC>
+__device__ __forceinline__ void block_totals_mixed(double (&q)[NQ], double (&c)[NC > 0 ? NC : 1],
+                                                   double (*sh)[16 * kMaxRed], int& phase) {
+  wave_totals<NQ>(q);
+  if constexpr (NW > 1) {
+    const int wv = wave_id();
+    if (lane_id() == 0) {
+#pragma unroll
+      for (int i = 0; i < NQ; ++i) sh[phase][wv * (NQ + NC) + i] = q[i];
+#pragma unroll
+      for (int i = 0; i < NC; ++i) sh[phase][wv * (NQ + NC) + NQ + i] = c[i];
+    }
+    lds_barrier();
+#pragma unroll
+    for (int i = 0; i < NQ + NC; ++i) {
+      double t = sh[phase][i];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) t += sh[phase][w * (NQ + NC) + i];
+      if (i < NQ) q[i] = t; else c[i - NQ] = t;
+    }
+    phase ^= 1;
+  }
+}
+
+// Alg. 2 for one vector of at most 4 slots per lane, tuned for the latency of a single vector (the
+// on-line case): the codes of a slot are kept as wave-uniform 64-bit ballots (scalar registers), so
+// the disagreement counts of Eq. 5 are scalar popcounts with no cross-lane reduction, only B^T w
+// travels through the binary64 lane reduction, and the K x K system is solved in binary64 on the
+// vector unit (K <= 3).  Same interface and results as quantize_core below.
+template <int K, int NJ, int NW>
+__device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int n, int base, int nj, bool do_greedy,
+                                                      int iters, bool do_ls, bool do_bst, float (&alpha)[K],
+                                                      unsigned long long (&mym)[K], double (&q)[K],
+                                                      double (*sh)[16 * kMaxRed], int& phase,
+                                                      unsigned long long* marks) {
+  (void)marks;
+  static_assert(NJ <= 4, "ballots of every slot and plane live in scalar registers");
+  constexpr int M = 1 << K;
+  constexpr int NP = K * (K - 1) / 2;
+  const int lane = lane_id();
+  const double dn = (double)n;
+  const bool n_pow2 = (n & (n - 1)) == 0;
+  const double inv_n = 1.0 / dn;  // exact for a power of two, where s / n == s * inv_n bit for bit
+  unsigned long long mk[K][NJ];   // mk[i][j]: plane i of slot j, bit = lane
+#pragma unroll
+  for (int i = 0; i < K; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) mk[i][j] = 0ull;
+  bool valid[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) valid[j] = j < nj && (base + j) * 64 + lane < n;
+
+  if (do_greedy) {
+    // ---- greedy initialisation, Eq. 4 (one pass per stage, as in quantize_core)
+    float r[NJ];
+    double s[1];
+    {
+      double s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        r[j] = w[j];
+        if (j & 1) s1 += (double)fabsf(w[j]); else s0 += (double)fabsf(w[j]);
+      }
+      s[0] = s0 + s1;
+    }
+    block_totals<NW, 1>(s, sh, phase);
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      const float al = n_pow2 ? (float)(s[0] * inv_n) : (float)(s[0] / dn);
+      alpha[i] = al;
+      double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const bool bit = valid[j] && (r[j] >= 0.0f);
+        mk[i][j] = __ballot(bit);
+        const double sw = bit ? (double)w[j] : -(double)w[j];
+        const float rn = valid[j] ? r[j] - (bit ? al : -al) : 0.0f;
+        r[j] = rn;
+        if (j & 1) { q1 += sw; s1 += (double)fabsf(rn); } else { q0 += sw; s0 += (double)fabsf(rn); }
+      }
+      q[i] = q0 + q1;
+      if (i + 1 < K) {
+        s[0] = s0 + s1;
+        block_totals<NW, 1>(s, sh, phase);
+      }
+    }
+  } else if (do_ls) {
+    // codes given by the caller as per-lane masks (lane j holds slot j)
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      const int lo = (int)(mym[i] & 0xffffffffull), hi = (int)(mym[i] >> 32);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        mk[i][j] = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(hi, j) << 32) |
+                   (unsigned)__builtin_amdgcn_readlane(lo, j);
+    }
+  }
+  AMQ_PHASE(marks, 2);
+  for (int it = 0; it < iters; ++it) {
+    if (do_ls) {
+      // ---- Eq. 5: B^T w through the lane reduction, the disagreement counts of the plane pairs
+      // from the ballots on the scalar unit
+      double cnt[NP > 0 ? NP : 1];
+      {
+        int t = 0;
+#pragma unroll
+        for (int a = 0; a < K; ++a)
+#pragma unroll
+          for (int b = a + 1; b < K; ++b) {
+            int c = 0;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) c += __popcll(mk[a][j] ^ mk[b][j]);
+            cnt[t++] = (double)c;
+          }
+      }
+      block_totals_mixed<NW, K, NP>(q, cnt, sh, phase);
+      AMQ_PHASE(marks, 4 + 4 * it);
+      if constexpr (K <= 3) {
+        ls_solve_f64<K>(n, cnt, q, alpha);
+      } else {
+        int G[K][K];
+        int t = 0;
+#pragma unroll
+        for (int a = 0; a < K; ++a) {
+          G[a][a] = n;
+#pragma unroll
+          for (int b = a + 1; b < K; ++b) {
+            const int d = __builtin_amdgcn_readfirstlane((int)cnt[t++]);
+            G[a][b] = n - 2 * d;
+            G[b][a] = G[a][b];
+          }
+        }
+        ls_solve<K>(G, q, alpha);
+      }
+      AMQ_PHASE(marks, 5 + 4 * it);
+      if (!do_bst) break;
+    }
+
+    // ---- code table in ascending order (Alg. 2), across lanes as in quantize_core
+    const int p = lane & (M - 1);
+    float v = 0.0f;
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      const float term = ((p >> (K - 1 - i)) & 1) ? alpha[i] : -alpha[i];
+      v = (i == 0) ? term : v + term;
+    }
+    int rank = 0;
+#pragma unroll
+    for (int o = 0; o < M; ++o) {
+      const float vo = readlane_f(v, o);
+      rank += (vo < v || (vo == v && o < p)) ? 1 : 0;
+    }
+    if (lane >= M) rank = lane;
+    const float sv = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(v)));
+    const int sp = __builtin_amdgcn_ds_permute(rank << 2, p);
+    float thr[M - 1];
+#pragma unroll
+    for (int j = 0; j < M - 1; ++j) thr[j] = 0.5f * (readlane_f(sv, j) + readlane_f(sv, j + 1));
+    unsigned bm[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) bm[i] = (unsigned)__ballot(lane < M && ((sp >> (K - 1 - i)) & 1));
+    AMQ_PHASE(marks, 6 + 4 * it);
+
+    // ---- codes with the coefficients fixed (Alg. 1)
+    const bool more = do_ls && (it + 1 < iters);
+    double qa[K], qb[K];
+#pragma unroll
+    for (int i = 0; i < K; ++i) { qa[i] = 0.0; qb[i] = 0.0; }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      int pos = 0;
+#pragma unroll
+      for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
+      const double wd = (double)w[j];
+#pragma unroll
+      for (int i = 0; i < K; ++i) {
+        const bool bit = valid[j] && ((bm[i] >> pos) & 1u);
+        mk[i][j] = __ballot(bit);
+        if (more) {
+          if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < K; ++i) q[i] = qa[i] + qb[i];
+    AMQ_PHASE(marks, 7 + 4 * it);
+  }
+  // lane j takes the ballots of slot j (the layout the callers store)
+#pragma unroll
+  for (int i = 0; i < K; ++i) {
+    unsigned long long mine = 0ull;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      if (lane == j) mine = mk[i][j];
+    mym[i] = mine;
+  }
+}
+
 // The arithmetic of Alg. 2 for one vector held in registers: `w[j]` of lane L is entry
 // (base + j) * 64 + L (0 beyond n); NW waves cooperate (nj slots each).  On return alpha holds the
 // coefficients and lane j of each wave holds in mym[i] the 64 packed codes of its slot j of
@@ -165,7 +412,13 @@ template <int K, int NJ, int NW>
 __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int base, int nj, bool do_greedy,
                                               int iters, bool do_ls, bool do_bst, float (&alpha)[K],
                                               unsigned long long (&mym)[K], double (&q)[K],
-                                              double (*sh)[16 * kMaxRed], int& phase) {
+                                              double (*sh)[16 * kMaxRed], int& phase,
+                                              unsigned long long* marks = nullptr) {
+  (void)marks;  // phase timers of the profiling build: 2 = greedy done, 4 + 4 * cycle + {0: reduction, 1: solve, 2: table, 3: assignment}
+  if constexpr (NJ <= 4 && K <= 3) {  // (K = 4 would need more scalar registers than a wave has)
+    quantize_core_uniform<K, NJ, NW>(w, n, base, nj, do_greedy, iters, do_ls, do_bst, alpha, mym, q, sh, phase, marks);
+    return;
+  }
   constexpr int M = 1 << K;
   constexpr int NP = K * (K - 1) / 2;
   const int lane = lane_id();
@@ -212,6 +465,7 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
       }
     }
   }
+  AMQ_PHASE(marks, 2);
   for (int it = 0; it < iters; ++it) {
     if (do_ls) {
       // ---- coefficients with the codes fixed, Eq. 5: B^T w and the disagreement counts of
@@ -227,6 +481,7 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
           for (int j = i + 1; j < K; ++j) red[t++] = (double)__popcll(mym[i] ^ mym[j]);
       }
       block_totals<NW, K + NP>(red, sh, phase);
+      AMQ_PHASE(marks, 4 + 4 * it);
       int G[K][K];
       double qq[K];
       {
@@ -244,6 +499,7 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
         }
       }
       ls_solve<K>(G, qq, alpha);
+      AMQ_PHASE(marks, 5 + 4 * it);
       if (!do_bst) break;
     }
 
@@ -272,6 +528,7 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
     unsigned bm[K];  // bit `pos` of bm[i]: plane i is +1 for the code at sorted position pos
 #pragma unroll
     for (int i = 0; i < K; ++i) bm[i] = (unsigned)__ballot(lane < M && ((sp >> (K - 1 - i)) & 1));
+    AMQ_PHASE(marks, 6 + 4 * it);
 
     // ---- codes with the coefficients fixed (Alg. 1); the position in the sorted table is the
     // number of midpoints <= w, which is where the k-comparison tree walk ends.
@@ -301,6 +558,7 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
     }
 #pragma unroll
     for (int i = 0; i < K; ++i) { mym[i] = mine[i]; q[i] = qa[i] + qb[i]; }
+    AMQ_PHASE(marks, 7 + 4 * it);
   }
 
 }
