@@ -161,6 +161,10 @@ hipError_t launch_matrix_core(const amq::BmvArgs& b, int k_w, int k_a, int epi, 
     if (lse_slots) *lse_slots = 0;
     return amq::launch_mfma4w_cell(b, k_w, k_a, epi, s);
   }
+  if (epi != amq::kEpiStore && amq::mfma4_pair_supported(b, k_w, k_a, epi)) {
+    if (lse_slots) *lse_slots = 0;
+    return amq::launch_mfma4_pair(b, k_w, k_a, epi, s);
+  }
   if (amq::mfma4_supported(b, k_w, epi)) return amq::launch_mfma4(b, k_w, k_a, epi, s, lse_slots);
   if (lse_slots) *lse_slots = 0;
   return amq::launch_mfma(b, k_w, k_a, epi, s);
@@ -308,7 +312,7 @@ int amq_binary_gemv_grouped(int64_t groups, const uint32_t* Wp, const float* alp
 
 size_t amq_lstm_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
   if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
-  return carve(nullptr, I, H, B, k_a, 4, 2).total;
+  return carve(nullptr, I, H, B, k_a, 4, 1).total;
 }
 
 size_t amq_gru_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
@@ -385,11 +389,11 @@ int amq_lstm_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp
                   const float* c_prev, int64_t B, int k_a, int T, float* h_out, float* c_out,
                   void* workspace, size_t workspace_bytes, void* stream) {
   if (!c_prev || !c_out) return AMQ_ERR_INVALID;
-  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 2).total : 0;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out, workspace,
                       workspace_bytes, need);
   if (st != AMQ_OK) return st;
-  StepWs w = carve(workspace, I, H, B, k_a, 4, 2);
+  StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
   return lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, x, h_prev, c_prev, B, k_a, T, h_out,
                           c_out, nullptr, w, static_cast<hipStream_t>(stream));
 }
@@ -398,7 +402,7 @@ int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32
                          int64_t I, int64_t H, int k_w, const float* bias, const float* x, const float* h_prev,
                          const float* c_prev, int64_t B, int k_a, int T, float* h_out, float* c_out, void* stream) {
   if (!c_prev || !c_out) return AMQ_ERR_INVALID;
-  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 2).total : 0;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
   // (validated against a stand-in workspace address: the real one is looked up only for sizes that fit)
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out,
                       reinterpret_cast<const void*>(uintptr_t(256)), need, need);
@@ -409,66 +413,14 @@ int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32
   if (st != AMQ_OK) return st;
   // every region of the scratch that a step reads is written earlier in the same step (codes and
   // coefficients by the quantizer, pre-activations by the first product), so nothing is cleared
-  StepWs w = carve(ws, I, H, B, k_a, 4, 2);
+  StepWs w = carve(ws, I, H, B, k_a, 4, 1);
   return lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, x, h_prev, c_prev, B, k_a, T, h_out,
                           c_out, nullptr, w, static_cast<hipStream_t>(stream));
 }
 
-// A batched sequence in the pipelined form of the paired-wave matrix-core kernel: the launch of step t
-// also forms the input-side pre-activations of step t + 1 (they do not depend on the recurrence), so
-// the chain a step waits for is quantize(h) -> W_h product -> cell.  One extra pair of launches at
-// the start prepares step 0.  Returns -1 if the shape does not take that kernel.
-static int lstm_sequence_pipelined(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
-                                   const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
-                                   const float* xs, int64_t steps, float* h, float* c, int64_t B, int k_a, int T,
-                                   float* hs, const StepWs& w, hipStream_t s) {
-  amq::BmvArgs b{};
-  b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
-  b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
-  b.m = 4 * H;
-  b.H = H;
-  b.batch = (int)B;
-  b.bias0 = bias;
-  b.c_prev = c;
-  b.h_out = h;
-  b.c_out = c;
-  b.groups = 1;
-  if (B <= amq::kBmvMaxBatch || !amq::mfma_supported(B) || amq::mfma4w_cell_supported(b, k_w, k_a, amq::kEpiLstm) ||
-      !amq::mfma4_pipelined_supported(b, k_w, k_a, amq::kEpiLstm) || !w.pre1)
-    return -1;
-  float* pre[2] = {w.pre0, w.pre1};
-  // step 0's input side: quantize x_0, x waves only
-  amq::QuantArgs q{};
-  q.seg[0] = amq::QuantSeg{xs, I, (int)I, (int)B, w.xp, w.beta_x};
-  q.T = T;
-  q.mode = amq::kQuantFull;
-  int st = hip_status(amq::launch_quantize(q, k_a, s));
-  if (st != AMQ_OK) return st;
-  b.pre_in = nullptr;
-  b.pre_out = pre[0];
-  st = hip_status(amq::launch_mfma4(b, k_w, k_a, amq::kEpiLstm, s));
-  if (st != AMQ_OK) return st;
-  for (int64_t t = 0; t < steps; ++t) {
-    const bool more = t + 1 < steps;
-    amq::QuantArgs qt{};
-    qt.seg[0] = amq::QuantSeg{more ? xs + (t + 1) * B * I : nullptr, I, (int)I, more ? (int)B : 0, w.xp, w.beta_x};
-    qt.seg[1] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
-    qt.T = T;
-    qt.mode = amq::kQuantFull;
-    st = hip_status(amq::launch_quantize(qt, k_a, s));
-    if (st != AMQ_OK) return st;
-    b.pre_in = pre[t & 1];
-    b.pre_out = more ? pre[(t + 1) & 1] : nullptr;
-    b.hs_out = hs ? hs + t * B * H : nullptr;
-    st = hip_status(amq::launch_mfma4(b, k_w, k_a, amq::kEpiLstm, s));
-    if (st != AMQ_OK) return st;
-  }
-  return AMQ_OK;
-}
-
 size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a) {
   if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return SIZE_MAX;
-  return carve(nullptr, I, H, B, k_a, 4, 2).sync_off;
+  return carve(nullptr, I, H, B, k_a, 4, 1).sync_off;
 }
 
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
@@ -476,14 +428,14 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
                       float* h, float* c, int64_t B, int k_a, int T, float* hs, void* workspace,
                       size_t workspace_bytes, void* stream) {
   if (!c || steps <= 0) return AMQ_ERR_INVALID;
-  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 2).total : 0;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 4, 1).total : 0;
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, xs, h, B, k_a, T, h, workspace, workspace_bytes,
                       need);
   if (st != AMQ_OK) return st;
   if (steps < (1 << 30) && amq::lstm_seqg_supported(I, H, B, k_w, k_a) && grid_fits_device()) {
     // batch 1: the whole sequence (in pieces of at most kSeqGMaxSteps steps) in one launch over the
     // chip, weights resident in registers
-    StepWs w = carve(workspace, I, H, B, k_a, 4, 2);
+    StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
     for (int64_t t0 = 0; t0 < steps; t0 += amq::kSeqGMaxSteps) {
       const int n = (int)(steps - t0 < amq::kSeqGMaxSteps ? steps - t0 : amq::kSeqGMaxSteps);
       amq::SeqGArgs q{Wxp, alpha_x, Whp, alpha_h, (int)I, (int)H, bias, xs + t0 * I, n, h, c,
@@ -493,12 +445,7 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
     }
     return AMQ_OK;
   }
-  StepWs w = carve(workspace, I, H, B, k_a, 4, 2);
-  if (steps > 1) {
-    st = lstm_sequence_pipelined(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, xs, steps, h, c, B, k_a, T, hs, w,
-                                 static_cast<hipStream_t>(stream));
-    if (st >= 0) return st;
-  }
+  StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
   for (int64_t t = 0; t < steps; ++t) {
     st = lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, xs + t * B * I, h, c, B, k_a, T, h, c,
                           hs ? hs + t * B * H : nullptr, w, static_cast<hipStream_t>(stream));
@@ -808,7 +755,7 @@ static int lm_step_launch(const uint32_t* Ep, const float* alpha_e, int64_t voca
 
 size_t amq_lm_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
   if (E <= 0 || H <= 0 || V <= 0 || B <= 0 || !bits_ok(k_a) || !bits_ok(k_as)) return 0;
-  return carve(nullptr, E, H, B, k_a, 4, 2).total + carve_softmax(nullptr, V, H, B, k_as).total;
+  return carve(nullptr, E, H, B, k_a, 4, 1).total + carve_softmax(nullptr, V, H, B, k_as).total;
 }
 
 int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t E, const uint32_t* Wxp,
@@ -819,7 +766,7 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
   if (!Ep || !alpha_e || !Wsp || !alpha_s || !ids || !c || !logprob) return AMQ_ERR_INVALID;
   if (vocab <= 0 || V <= 0 || !bits_ok(k_ws) || !bits_ok(k_as)) return AMQ_ERR_INVALID;
   const bool sizes_ok = E > 0 && H > 0 && B > 0 && bits_ok(k_a);
-  const size_t need_step = sizes_ok ? carve(nullptr, E, H, B, k_a, 4, 2).total : 0;
+  const size_t need_step = sizes_ok ? carve(nullptr, E, H, B, k_a, 4, 1).total : 0;
   const size_t need = sizes_ok ? need_step + carve_softmax(nullptr, V, H, B, k_as).total : 0;
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, E, H, k_w, ids, h, B, k_a, T, h, workspace, workspace_bytes,
                       need);
@@ -827,7 +774,7 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
   if (!aligned(Wsp, 16) || !aligned(Ep, 16)) return AMQ_ERR_INVALID;
   if (V > (1LL << 31)) return AMQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  StepWs w = carve(workspace, E, H, B, k_a, 4, 2);
+  StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
   SoftmaxWs sw = carve_softmax(static_cast<char*>(workspace) + need_step, V, H, B, k_as);
 
   return lm_step_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, Wsp, alpha_s, V, k_ws, bias_s,
@@ -853,7 +800,7 @@ struct LmSeqWs {
 static LmSeqWs carve_lm_seq(void* ws, int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
   LmSeqWs w;
   char* base = static_cast<char*>(ws);
-  w.step_bytes = carve(nullptr, E, H, B, k_a, 4, 2).total;
+  w.step_bytes = carve(nullptr, E, H, B, k_a, 4, 1).total;
   size_t off = w.step_bytes;
   w.hs = reinterpret_cast<float*>(base ? base + off : nullptr);
   w.soft_batch = (int)(lm_piece_steps(B) * B);
@@ -959,7 +906,7 @@ static int lm_sequence_impl(const uint32_t* Ep, const float* alpha_e, int64_t vo
   if (V > (1LL << 31) || steps >= (1 << 30)) return AMQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
   LmSeqWs lw = carve_lm_seq(workspace, E, H, V, B, k_a, k_as);
-  StepWs w = carve(workspace, E, H, B, k_a, 4, 2);
+  StepWs w = carve(workspace, E, H, B, k_a, 4, 1);
   char* soft_base = static_cast<char*>(workspace) + lw.soft_off;
   // every h_t of a piece of the sequence goes through the output layer together, as a batch of rows
   auto output_layer = [&](int64_t row0, int64_t rows) -> int {

@@ -18,23 +18,6 @@ namespace amq {
 
 namespace {
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
-  return v + __int_as_float(t);
-}
-
-// Sum over aligned groups of 2^lg lanes; every lane of a group ends with the group's total.
-__device__ __forceinline__ float group_sum(float v, int lg) {
-  if (lg >= 1) v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
-  if (lg >= 2) v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
-  if (lg >= 3) v = dpp_add<0x141>(v);  // row_half_mirror
-  if (lg >= 4) v = dpp_add<0x140>(v);  // row_mirror
-  if (lg >= 5) v += __shfl_xor(v, 16, kWave);
-  if (lg >= 6) v += __shfl_xor(v, 32, kWave);
-  return v;
-}
-
 // LSE (store mode only): also leave, per batch entry and wave, the (max, sum of exponentials) of
 // the outputs the wave produced, for a log-softmax over the rows that follows.
 template <int KW, int KA, int NSEG, int NBLK, int EPI, bool LSE = false>

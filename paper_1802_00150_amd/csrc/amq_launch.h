@@ -149,12 +149,6 @@ struct BmvArgs {
   float* h_out;
   float* c_out;
   float* hs_out;        // LSTM, nullable
-  // Cell modes, pipelined form (fp4 kernel with paired waves only; both null otherwise): the input-side
-  // pre-activations of THIS step are read from pre_in, [batch][H][4] (gate-interleaved, without bias;
-  // null: this launch computes no new state), while blk[0] holds the quantized inputs of the NEXT step
-  // and its pre-activations are written to pre_out in the same layout (null: nothing to prepare).
-  const float* pre_in;
-  float* pre_out;
   float* lse_part;      // store mode, nullable: per batch entry and slot a (max, sum exp(y - max)) pair over
                         // the outputs one wave produced, [batch][lse_slots][2]
   int lse_slots;        // filled by the launcher: slots per batch entry
@@ -181,14 +175,15 @@ bool mfma_supported(long long batch);
 hipError_t launch_mfma(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 // fp4 matrix-core kernel for vectors of at most 1024 entries (the fast path)
 bool mfma4_supported(const BmvArgs& a, int k_w, int epi);
-// true if a recurrent step of this shape runs in the paired-wave form, which also has the pipelined
-// mode (pre_in / pre_out above)
-bool mfma4_pipelined_supported(const BmvArgs& a, int k_w, int k_a, int epi);
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 // the same instruction with several batch tiles per wave: plain products with many rows and
 // at least 32 columns (store mode only)
 bool mfma4w_supported(const BmvArgs& a, int k_w, int k_a);
 hipError_t launch_mfma4w(const BmvArgs& a, int k_w, int k_a, hipStream_t s, int* lse_slots = nullptr);
+// the recurrent steps with both operands loaded straight into registers in sign form and the x / h
+// blocks on paired waves (batches of 17 and more while the row-block x tile tasks are few)
+bool mfma4_pair_supported(const BmvArgs& a, int k_w, int k_a, int epi);
+hipError_t launch_mfma4_pair(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);
 // and the recurrent steps in the same work split, for batches of 128 and more
 bool mfma4w_cell_supported(const BmvArgs& a, int k_w, int k_a, int epi);
 hipError_t launch_mfma4w_cell(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s);

@@ -30,20 +30,6 @@ constexpr int kGWaves = 4;
 constexpr int kGNJ = 4;                      // vectors of at most 1024 entries: 16 slots over 4 waves
 constexpr unsigned kSpinLimit = 1u << 19;    // polls of the barrier counter before giving up
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_addg(float v) {
-  const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
-  return v + __int_as_float(t);
-}
-// Sum over aligned groups of 2^lg lanes, lg <= 4; every lane of a group ends with the total.
-__device__ __forceinline__ float group_sumg(float v, int lg) {
-  if (lg >= 1) v = dpp_addg<0xB1>(v);   // quad_perm [1,0,3,2]
-  if (lg >= 2) v = dpp_addg<0x4E>(v);   // quad_perm [2,3,0,1]
-  if (lg >= 3) v = dpp_addg<0x141>(v);  // row_half_mirror
-  if (lg >= 4) v = dpp_addg<0x140>(v);  // row_mirror
-  return v;
-}
-
 // Device-scope accesses to the data the workgroups exchange (see grid_barrier).
 __device__ __forceinline__ void put_f(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -293,7 +279,7 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
       }
     }
     // sum over the chunks of the row and over the two operand blocks: 2 * Gl adjacent lanes
-    const float pre = group_sumg(acc, lg + 1);
+    const float pre = group_sum(acc, lg + 1);
     // the four gates of a unit sit 2 * Gl lanes apart
     const int ubase = lane & ~(8 * Gl - 1);
     const float p0 = __shfl(pre, ubase, kWave) + bs[0];

@@ -23,9 +23,6 @@ namespace amq {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-constexpr int kTileB = 16;        // batch entries per tile
 constexpr int kChunkWords = 32;   // K chunk = 32 words = 1024 entries = 16 MFMA steps
 
 // Values the final step needs besides the products (biases, previous state, old Y), loaded

@@ -29,40 +29,11 @@ namespace amq {
 
 namespace {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kTileB = 16;   // batch entries per tile
-constexpr int kSteps = 8;    // 1024 entries / 128 per MFMA
-constexpr unsigned kNib = 0x22222222u;
-constexpr int kScaleOne = 0x7f7f7f7f;  // E8M0 exponent 127 = 2^0 in every byte
-
-__device__ __forceinline__ uint4 expand4(uint32_t w) {
-  return make_uint4((w << 1) & kNib, w & kNib, (w >> 1) & kNib, (w >> 2) & kNib);
-}
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-// fp4 operands occupy the first four of the eight operand registers; the rest is left undefined
-// so that no registers are spent on it.
-__device__ __forceinline__ v8i as_operand(uint4 e) {
-  const v4i lo = {(int)e.x, (int)e.y, (int)e.z, (int)e.w};
-  return __builtin_shufflevector(lo, lo, 0, 1, 2, 3, -1, -1, -1, -1);
-}
-
-__device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
-  const uint4 v = q[t >> 2];
-  return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
-}
-
-template <int KW, int KA, int EPI, int NWV, bool SPLIT = false, bool PIPE = false>
+template <int KW, int KA, int EPI, int NWV>
 __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_wg, int rowblocks) {
-  static_assert(!SPLIT || (EPI != kEpiStore && NWV % 2 == 0), "SPLIT pairs the waves over the two operand blocks");
-  static_assert(!PIPE || SPLIT, "the pipelined form is a variant of the paired-wave form");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
   constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
-  constexpr int kPlaneBytes = kSteps * kTileB * 64;   // 8 KiB: [step][batch entry][k-block][16 B]
   constexpr int kTileBytes = KA * kPlaneBytes;
   constexpr int kItems = KA * kTileB * 8;             // 16-byte groups of packed words per operand block
   constexpr int kIter = (kItems + 64 * NWV - 1) / (64 * NWV);
@@ -73,13 +44,13 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform to the compiler
   const int l16 = lane & 15, l4 = lane >> 4;
   // phase timers of the profiling build: 0 start, 1 loads issued, 9 own part of the tile staged, 2 barrier passed,
-  // 3 column coefficients read, 4 row coefficients spread, 10 weight words used, 5 contraction, 6 epilogue, 7 exchange, 8 cell
-  AMQ_PHASE(AMQ_PHASE_OF(a), 0);
+  // 3 column coefficients read, 4 row coefficients spread, 10 weight words used, 5 contraction, 6 epilogue, 8 cell
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 0);
   asm volatile("" ::AMQ_ARG(a.blk[0].Wp), AMQ_ARG(a.blk[0].alpha), AMQ_ARG(a.blk[0].Xp), AMQ_ARG(a.blk[0].beta),
                AMQ_ARG(a.blk[0].n), AMQ_ARG(a.blk[NBLK - 1].Wp), AMQ_ARG(a.blk[NBLK - 1].alpha),
                AMQ_ARG(a.blk[NBLK - 1].Xp), AMQ_ARG(a.blk[NBLK - 1].beta), AMQ_ARG(a.blk[NBLK - 1].n), AMQ_ARG(a.m),
                AMQ_ARG(a.H), AMQ_ARG(a.batch), AMQ_ARG(a.bias0), AMQ_ARG(a.bias1), AMQ_ARG(a.c_prev), AMQ_ARG(a.h_prev),
-               AMQ_ARG(a.h_out), AMQ_ARG(a.c_out), AMQ_ARG(a.hs_out), AMQ_ARG(a.pre_in), AMQ_ARG(a.pre_out), AMQ_ARG(a.Y),
+               AMQ_ARG(a.h_out), AMQ_ARG(a.c_out), AMQ_ARG(a.hs_out), AMQ_ARG(a.Y),
                AMQ_ARG(a.accumulate), AMQ_ARG(rb_per_wg), AMQ_ARG(rowblocks));
   const int b0 = blockIdx.y * kTileB;
   const int batch = a.batch;
@@ -101,23 +72,6 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   const int rb_first = blockIdx.x * rb_per_wg;
   int rb_end = rb_first + rb_per_wg;
   if (rb_end > rowblocks) rb_end = rowblocks;
-
-  // SPLIT (cell modes): the two operand blocks of a row block go to two waves (kb = 0: x block and
-  // the cell, kb = 1: h block), which halves the dependent work per wave when there are too few
-  // row blocks to give every SIMD more than one wave anyway.  The h-block sums cross through LDS.
-  //
-  // PIPE (sequences): the input side does not depend on the recurrence, so the x waves work one step
-  // ahead -- they form W_x q(x_{t+1}) and leave it in memory (pre_out), while the h waves form
-  // W_h q(h_{t-1}), add the input side of this step that the previous launch left (pre_in) and apply
-  // the cell.  Nothing crosses between the two waves of a pair, and the h waves, which the next
-  // launch waits for, run at raised priority.  Waves w and w + NWV / 2 (same SIMD) form a pair.
-  constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;  // row blocks a workgroup has in flight
-  const int wr = PIPE ? (wv % NSLOT) : SPLIT ? (wv >> 1) : wv;
-  const int kb = PIPE ? (wv / NSLOT) : SPLIT ? (wv & 1) : 0;
-  if constexpr (PIPE) {
-    if (kb == 1) __builtin_amdgcn_s_setprio(3);
-  }
-  float4* xch = reinterpret_cast<float4*>(smem + NBLK * kTileBytes + 16 * ((NBLK * KA * kTileB * 4 + 15) / 16));
 
   // A-operand view of row block rb: lane = (tile row l16, k-block l4)
   auto a_row = [&](int rb, bool& wok) -> int {
@@ -207,37 +161,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   using K0 = std::integral_constant<int, 0>;
   using K1 = std::integral_constant<int, NBLK - 1>;
 
-  // SPLIT workgroups take exactly NSLOT row blocks (one pass: a second request site for the operands
-  // costs more registers than the kernel has); the launcher guarantees it
-  const int iters = SPLIT ? 1 : (rb_end - rb_first + NSLOT - 1) / NSLOT;
-
-  // SPLIT: everything a wave's row block needs from memory, requested at the top of the pass
-  // (requesting it before the activation tile is staged was measured slower)
-  struct Ahead {
-    uint4 araw[KW][2];
-    float alpha_req, bias_req, prev;
-    float4 pre;  // PIPE: input-side pre-activations of this lane's unit and batch column
-  } nx{};
-  constexpr int kCellWave = PIPE ? 1 : 0;  // which wave of a pair applies the cell
-  auto fetch_rowblock = [&](int rb) {
-    if (rb >= rb_end) return;
-    if (kb == 0) {
-      load_a(K0{}, rb, nx.araw);
-      nx.alpha_req = request_alpha(K0{}, rb);
-    } else {
-      load_a(K1{}, rb, nx.araw);
-      nx.alpha_req = request_alpha(K1{}, rb);
-    }
-    if (kb == kCellWave) {
-      nx.bias_req = request_bias(rb);
-      const int unit = rb * 4 + l4;  // (cell modes: the C view's hidden unit)
-      const int t = bc * H + (unit < H ? unit : 0);
-      nx.prev = 0.0f;
-      if constexpr (EPI == kEpiLstm) nx.prev = a.c_prev[t];
-      if constexpr (EPI == kEpiGru) nx.prev = a.h_prev[t];
-      if constexpr (PIPE) nx.pre = reinterpret_cast<const float4*>(a.pre_in)[t];
-    }
-  };
+  const int iters = (rb_end - rb_first + NWV - 1) / NWV;
 
   // ---- prologue: packed activation words of every operand block, 16 bytes per thread, coalesced
   uint4 xw[NBLK][kIter];
@@ -258,14 +182,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   float beta_req[NBLK];
 #pragma unroll
   for (int k = 0; k < NBLK; ++k) beta_req[k] = a.blk[k].beta[bc * KA + (l4 < KA ? l4 : KA - 1)];
-  // SPLIT: everything this wave's first row block needs from memory is requested now, behind the
-  // activation words, and arrives while the tile is being staged (the barrier below does not wait for it)
-  // (PIPE: a launch may have only one of the two kinds of waves at work)
-  const bool idle = PIPE && (kb == 0 ? a.pre_out == nullptr : a.pre_in == nullptr);
-  if constexpr (SPLIT) {
-    if (!idle) fetch_rowblock(rb_first + wr);
-  }
-  AMQ_PHASE(AMQ_PHASE_OF(a), 1);
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 1);
 #pragma unroll
   for (int k = 0; k < NBLK; ++k) {
 #pragma unroll
@@ -287,10 +204,9 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       }
     }
   }
-  AMQ_PHASE(AMQ_PHASE_OF(a), 9);
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 9);
   lds_barrier();
-  AMQ_PHASE(AMQ_PHASE_OF(a), 2);
-  if (idle) return;
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 2);
 
   float btv[NBLK][KA];
   float cx[NBLK][KA];  // n - 2 * popc(activation plane): the column-only part of the dot product
@@ -302,7 +218,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       cx[k][j] = (float)(nlen[k] - 2 * pops[(k * KA + j) * kTileB + l16]);
     }
 
-  AMQ_PHASE(AMQ_PHASE_OF(a), 3);
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 3);
   float lse_m = kLseLow, lse_s = 0.0f;  // store mode: running (max, sum exp) of this lane's outputs
   float* const lse_part = (EPI == kEpiStore) ? a.lse_part : nullptr;
 
@@ -325,7 +241,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
       for (int r = 0; r < 4; ++r) pw2[i][r] = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
     }
 
-    AMQ_PHASE(AMQ_PHASE_OF(a), 10);
+    AMQ_PHASE_B(AMQ_PHASE_OF(a), 10);
     v4f acc[KW][KA];
 #pragma unroll
     for (int i = 0; i < KW; ++i)
@@ -375,7 +291,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     for (int i = 0; i < KW; ++i)
 #pragma unroll
       for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[i][j]));
-    AMQ_PHASE(AMQ_PHASE_OF(a), 5);
+    AMQ_PHASE_B(AMQ_PHASE_OF(a), 5);
     // block epilogue in the C view: lane = (batch column l16, row quad l4), with
     //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j))   (integers below 2^24: exact in binary32)
     //   y = sum_i alpha_i sum_j beta_j d_ij.
@@ -435,77 +351,38 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
     }
   };
   for (int it = 0; it < iters; ++it) {
-    const int rb = rb_first + it * NSLOT + wr;
-    if (!SPLIT && rb >= rb_end) break;
-    const bool live = rb < rb_end;  // SPLIT: a wave without a row block still meets the barrier
+    const int rb = rb_first + it * NWV + wv;
+    if (rb >= rb_end) break;
     float ysum[NBLK][4];
     int crow[4];
     bool cok[4];
     float bias0[4], bias1[4], yold[4], prev = 0.0f;
-    if (live) {
-      if constexpr (SPLIT) {
-        // (this row block's operands were requested in the prologue)
-        c_rows(rb, crow, cok);
-        float alr[4][KW];
-        spread_alpha(nx.alpha_req, alr);
+    {
+      c_rows(rb, crow, cok);
+      uint4 araw[NBLK][KW][2];
+      float alr[NBLK][4][KW];
+      load_a(K0{}, rb, araw[0]);
+      if constexpr (NBLK == 2) load_a(K1{}, rb, araw[NBLK - 1]);
+      const float alpha_req0 = request_alpha(K0{}, rb);
+      const float alpha_req1 = (NBLK == 2) ? request_alpha(K1{}, rb) : 0.0f;
+      const float bias_req = request_bias(rb);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          bias0[r] = __shfl(nx.bias_req, 16 * l4 + r, kWave);
-          bias1[r] = __shfl(nx.bias_req, 16 * l4 + 4 + r, kWave);
-        }
-        prev = nx.prev;
-        AMQ_PHASE(AMQ_PHASE_OF(a), 4 + 8 * it);
-        if (kb == 0) {
-          run_block(K0{}, nx.araw, alr, crow, cok, ysum[0]);
-          if constexpr (PIPE) {
-            // the next step's input side, gate-interleaved: one 16-byte store per lane
-            if (bok && cok[0])
-              reinterpret_cast<float4*>(a.pre_out)[b * H + crow[0]] = make_float4(ysum[0][0], ysum[0][1], ysum[0][2], ysum[0][3]);
-          }
-        } else {
-          run_block(K1{}, nx.araw, alr, crow, cok, ysum[NBLK - 1]);
-          if constexpr (PIPE) {
-            ysum[0][0] = nx.pre.x; ysum[0][1] = nx.pre.y; ysum[0][2] = nx.pre.z; ysum[0][3] = nx.pre.w;
-          } else {
-            xch[((it & 1) * NSLOT + wr) * 64 + lane] = make_float4(ysum[NBLK - 1][0], ysum[NBLK - 1][1],
-                                                                   ysum[NBLK - 1][2], ysum[NBLK - 1][3]);
-          }
-        }
-      } else {
-        c_rows(rb, crow, cok);
-        uint4 araw[NBLK][KW][2];
-        float alr[NBLK][4][KW];
-        load_a(K0{}, rb, araw[0]);
-        if constexpr (NBLK == 2) load_a(K1{}, rb, araw[NBLK - 1]);
-        const float alpha_req0 = request_alpha(K0{}, rb);
-        const float alpha_req1 = (NBLK == 2) ? request_alpha(K1{}, rb) : 0.0f;
-        const float bias_req = request_bias(rb);
+      for (int r = 0; r < 4; ++r)
+        yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
+      if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
+      if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
+      spread_alpha(alpha_req0, alr[0]);
+      if constexpr (NBLK == 2) spread_alpha(alpha_req1, alr[NBLK - 1]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          yold[r] = (EPI == kEpiStore && a.accumulate && a.Y) ? a.Y[(long long)bc * m + crow[r]] : 0.0f;
-        if constexpr (EPI == kEpiLstm) prev = a.c_prev[bc * H + crow[0]];
-        if constexpr (EPI == kEpiGru) prev = a.h_prev[bc * H + crow[0]];
-        spread_alpha(alpha_req0, alr[0]);
-        if constexpr (NBLK == 2) spread_alpha(alpha_req1, alr[NBLK - 1]);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          bias0[r] = __shfl(bias_req, 16 * l4 + r, kWave);
-          bias1[r] = __shfl(bias_req, 16 * l4 + 4 + r, kWave);
-        }
-        run_block(K0{}, araw[0], alr[0], crow, cok, ysum[0]);
-        if constexpr (NBLK == 2) run_block(K1{}, araw[NBLK - 1], alr[NBLK - 1], crow, cok, ysum[NBLK - 1]);
+      for (int r = 0; r < 4; ++r) {
+        bias0[r] = __shfl(bias_req, 16 * l4 + r, kWave);
+        bias1[r] = __shfl(bias_req, 16 * l4 + 4 + r, kWave);
       }
+      AMQ_PHASE_B(AMQ_PHASE_OF(a), 4);
+      run_block(K0{}, araw[0], alr[0], crow, cok, ysum[0]);
+      if constexpr (NBLK == 2) run_block(K1{}, araw[NBLK - 1], alr[NBLK - 1], crow, cok, ysum[NBLK - 1]);
     }
-    AMQ_PHASE(AMQ_PHASE_OF(a), 6 + 8 * it);
-    if constexpr (PIPE) {
-      if (!live || kb != kCellWave) continue;
-    } else if constexpr (SPLIT) {
-      lds_barrier();  // (alternating exchange buffers: one barrier per iteration suffices)
-      AMQ_PHASE(AMQ_PHASE_OF(a), 7 + 8 * it);
-      if (!live || kb != kCellWave) continue;
-      const float4 o = xch[((it & 1) * NSLOT + wr) * 64 + lane];
-      ysum[NBLK - 1][0] = o.x; ysum[NBLK - 1][1] = o.y; ysum[NBLK - 1][2] = o.z; ysum[NBLK - 1][3] = o.w;
-    }
+    AMQ_PHASE_B(AMQ_PHASE_OF(a), 6);
 
     // (no early exit for padded batch columns: every lane stays active through the loop, the
     // stores below are predicated instead)
@@ -547,7 +424,7 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
         a.h_out[t] = h;
         if (a.hs_out) a.hs_out[t] = h;
       }
-      AMQ_PHASE(AMQ_PHASE_OF(a), 8 + 8 * it);
+      AMQ_PHASE_B(AMQ_PHASE_OF(a), 8 + 8 * it);
     } else {
       if (bok && cok[0]) {
         const int t = b * H + crow[0];
@@ -576,26 +453,23 @@ __global__ __launch_bounds__(64 * NWV) void mfma4_kernel(BmvArgs a, int rb_per_w
   }
 }
 
-template <int KW, int KA, int EPI, int NWV, bool SPLIT = false, bool PIPE = false>
+template <int KW, int KA, int EPI, int NWV>
 hipError_t launch_one(BmvArgs a, int rowblocks, int rb_per_wg, hipStream_t s, int* lse_slots) {
   constexpr int NBLK = (EPI == kEpiStore) ? 1 : 2;
-  constexpr int NSLOT = SPLIT ? NWV / 2 : NWV;
-  // activation tiles, their popcounts (padded to 16 bytes), and the exchange buffers of SPLIT
-  const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + 16 * ((sizeof(int) * NBLK * KA * kTileB + 15) / 16) +
-                     (SPLIT && !PIPE ? sizeof(float4) * 2 * NSLOT * 64 : 0);
+  // activation tiles and their popcounts (padded to 16 bytes)
+  const size_t lds = (size_t)NBLK * KA * kSteps * kTileB * 64 + 16 * ((sizeof(int) * NBLK * KA * kTileB + 15) / 16);
   static std::atomic<unsigned long long> configured{0};
   {
-    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV, SPLIT, PIPE>), (int)lds, configured);
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4_kernel<KW, KA, EPI, NWV>), (int)lds, configured);
     if (e != hipSuccess) return e;
   }
   AMQ_PHASE_ATTACH(a);
-  if (SPLIT && rb_per_wg != NSLOT) return hipErrorInvalidValue;  // the paired-wave form is single-pass
   dim3 grid((unsigned)((rowblocks + rb_per_wg - 1) / rb_per_wg), (unsigned)((a.batch + kTileB - 1) / kTileB));
   const long long slots = (long long)grid.x * NWV;  // one per wave of a batch tile's workgroups
   if (EPI != kEpiStore || slots > kLseMaxSlots || slots > a.lse_cap) a.lse_part = nullptr;
   a.lse_slots = (int)slots;
   if (lse_slots) *lse_slots = a.lse_part ? (int)slots : 0;
-  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV, SPLIT, PIPE>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
+  hipLaunchKernelGGL((mfma4_kernel<KW, KA, EPI, NWV>), grid, dim3(64 * NWV), lds, s, a, rb_per_wg, rowblocks);
   return hipGetLastError();
 }
 
@@ -603,17 +477,6 @@ template <int KW, int KA, int EPI>
 hipError_t launch_mode(const BmvArgs& a, hipStream_t s, int* lse_slots) {
   const int rowblocks = (int)((EPI == kEpiStore) ? (a.m + 15) / 16 : (a.H + 3) / 4);
   const int btiles = (a.batch + kTileB - 1) / kTileB;
-  if constexpr (EPI != kEpiStore) {
-    // few row-block tasks (at most two per SIMD of the chip): pair the waves over the x and h blocks,
-    // four row blocks per 8-wave workgroup
-    // (up to 3 weight planes and 9 plane pairs: beyond that the paired kernel no longer fits 256 registers)
-    if constexpr (KW <= 3 && KW * KA <= 9)
-      if ((long long)rowblocks * btiles <= 2048) {
-        if (a.pre_in || a.pre_out) return launch_one<KW, KA, EPI, 8, true, true>(a, rowblocks, 4, s, lse_slots);
-        return launch_one<KW, KA, EPI, 8, true>(a, rowblocks, 4, s, lse_slots);
-      }
-    if (a.pre_in || a.pre_out) return hipErrorInvalidValue;  // (callers ask mfma4_pipelined_supported first)
-  }
   // about two workgroups per CU; each expands its activation tile once and then walks row blocks
   int splits = (512 + btiles - 1) / btiles;
   int per = (rowblocks + splits - 1) / splits;
@@ -656,12 +519,6 @@ bool mfma4_supported(const BmvArgs& a, int k_w, int epi) {
   if (a.m * 8 * k_w >= (1LL << 31)) return false;       // weight offsets in 16-byte units
   if ((long long)a.batch * (a.m > a.H ? a.m : a.H) >= (1LL << 31)) return false;
   return true;
-}
-
-bool mfma4_pipelined_supported(const BmvArgs& a, int k_w, int k_a, int epi) {
-  if (epi == kEpiStore || !mfma4_supported(a, k_w, epi)) return false;
-  const long long rowblocks = (a.H + 3) / 4, btiles = (a.batch + kTileB - 1) / kTileB;
-  return k_w <= 3 && k_w * k_a <= 9 && rowblocks * btiles <= 2048;
 }
 
 hipError_t launch_mfma4(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots) {

@@ -18,30 +18,7 @@ namespace amq {
 
 namespace {
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kTileB = 16;   // batch entries per tile
-constexpr int kSteps = 8;    // 1024 entries / 128 per MFMA
 constexpr int kWaves = 8;
-constexpr unsigned kNib = 0x22222222u;
-constexpr int kScaleOne = 0x7f7f7f7f;  // E8M0 exponent 127 = 2^0 in every byte
-constexpr int kPlaneBytes = kSteps * kTileB * 64;  // 8 KiB: [step][batch entry][k-block][16 B]
-
-// bit p of a packed word -> nibble 0b0010 (1.0 in E2M1) or 0; nibble q of dword s is bit 4q + s
-__device__ __forceinline__ uint4 expand4(uint32_t w) {
-  return make_uint4((w << 1) & kNib, w & kNib, (w >> 1) & kNib, (w >> 2) & kNib);
-}
-// fp4 operands occupy the first four of the eight operand registers
-__device__ __forceinline__ v8i as_operand(uint4 e) {
-  const v4i lo = {(int)e.x, (int)e.y, (int)e.z, (int)e.w};
-  return __builtin_shufflevector(lo, lo, 0, 1, 2, 3, -1, -1, -1, -1);
-}
-__device__ __forceinline__ uint32_t word_of(const uint4 (&q)[2], int t) {
-  const uint4 v = q[t >> 2];
-  return (t & 3) == 0 ? v.x : (t & 3) == 1 ? v.y : (t & 3) == 2 ? v.z : v.w;
-}
 
 // Contraction of one operand block of a row block with NBT staged batch tiles: units u = (k-step t,
 // tile bt); the LDS reads (and, when the step changes, the weight expansion) of unit u + 1 are
@@ -109,7 +86,7 @@ __device__ __forceinline__ void contract_tiles(const uint4 (&araw)[KW][2], const
 
 // Stages the packed activation words of one operand block (NBT * 16 batch entries from bg0 on,
 // KA planes) into LDS as 4-bit codes, [tile][plane][step][batch entry][k-block][16 B], and adds
-// their popcounts into pops [tile][plane][batch entry] (zeroed by the caller, barrier before).
+// leaves their popcounts in pops [tile][plane][batch entry].
 template <int KA, int NBT, int NTHREADS>
 __device__ __forceinline__ void load_activation_words(const uint32_t* Xp, int batch, int bg0, int wq,
                                                       uint4 (&xw)[(NBT * KA * kTileB * 8 + NTHREADS - 1) / NTHREADS]) {
@@ -136,12 +113,13 @@ __device__ __forceinline__ void stage_activation_words(
 #pragma unroll
   for (int it = 0; it < kIter; ++it) {
     const int e = threadIdx.x + it * NTHREADS;
+    const int q = e & 7, nn = (e >> 3) % kGroupB, j = (e >> 3) / kGroupB;
+    const int bt = nn >> 4, n16 = nn & 15;
+    const uint4 w4 = xw[it];
+    // popcount of the row: its 8 groups sit in 8 consecutive lanes (every lane takes part)
+    const int pc = sum8(__popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w));
     if (e < kItems) {
-      const int q = e & 7, nn = (e >> 3) % kGroupB, j = (e >> 3) / kGroupB;
-      const int bt = nn >> 4, n16 = nn & 15;
-      const uint4 w4 = xw[it];
-      const int pc = __popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w);
-      if (pc) atomicAdd(&pops[(bt * KA + j) * kTileB + n16], pc);
+      if (q == 0) pops[(bt * KA + j) * kTileB + n16] = pc;
       // words 4q .. 4q+3 of the row: k-block q >> 1, steps 4 * (q & 1) + 0..3
       uint4* dst = reinterpret_cast<uint4*>(btile + (bt * KA + j) * kPlaneBytes + ((4 * (q & 1)) * kTileB + n16) * 64 +
                                             (q >> 1) * 16);
@@ -180,8 +158,6 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
   {
     uint4 xw[kIter];
     load_activation_words<KA, NBT, 64 * kWaves>(a.blk[0].Xp, batch, bg0, wq, xw);
-    if (tid < NBT * KA * kTileB) pops[tid] = 0;
-    __syncthreads();
     stage_activation_words<KA, NBT, 64 * kWaves>(xw, btile, pops);
     __syncthreads();
   }
@@ -407,8 +383,6 @@ __global__ __launch_bounds__(64 * NWV) void mfma4wc_kernel(BmvArgs a, int rb_per
     uint4 xw[2][kIter];
 #pragma unroll
     for (int k = 0; k < 2; ++k) load_activation_words<KA, NBT, 64 * NWV>(a.blk[k].Xp, batch, bg0, wq[k], xw[k]);
-    for (int t = tid; t < 2 * NBT * KA * kTileB; t += 64 * NWV) pops[t] = 0;
-    __syncthreads();
 #pragma unroll
     for (int k = 0; k < 2; ++k)
       stage_activation_words<KA, NBT, 64 * NWV>(xw[k], btile + k * kBlockBytes, pops + k * NBT * KA * kTileB);
@@ -538,6 +512,246 @@ __global__ __launch_bounds__(64 * NWV) void mfma4wc_kernel(BmvArgs a, int rb_per
       }
     }
   }
+}
+
+// The recurrent steps when there are too few row-block x batch-tile tasks to give every SIMD more
+// than one wave (config 3's batch of 64: 256 row blocks x 4 tiles).  Such a launch is bound by what one
+// wave issues from start to end, so this form cuts the per-wave path down:
+//   * a wave takes ONE operand block (the x block and the h block of a row block go to two paired
+//     waves; the h-side sums cross through LDS) and NBT batch tiles per set of weight words;
+//   * no staging: the packed activation words of a batch column and k-block are 32 contiguous bytes
+//     in the exchange layout -- exactly what a lane of the B operand needs for the eight k-steps -- so
+//     they are loaded straight into registers like the weight words, all requests issued before the
+//     first wait, no LDS tile and no barrier before the contraction;
+//   * both operands are expanded to {-1, +1} codes (expand4_signed) under the matrix instructions of
+//     the previous k-step, so the accumulators hold the inner products of the codes themselves: no
+//     popcounts.  Positions past the end of a vector are 0 bits in both operands, i.e. (-1)(-1) = +1
+//     each, a constant that the epilogue takes off.
+// Workgroups of NWV waves (NWV / 2 row blocks x 2 operand blocks).  Same arithmetic and summation
+// order as the other cell kernels: results are bit-identical to theirs.
+template <int KW, int KA, int NBT, int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void mfma4p_kernel(BmvArgs a, int rowblocks) {
+  static_assert(EPI == kEpiLstm || EPI == kEpiGru, "cell modes only");
+  __shared__ float4 xch[(NWV / 2) * NBT * 64];  // [pair][tile][lane]: the h-side sums on their way to the x wave
+  constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
+
+  // (phase timers of the profiling build: 0 start, 1 requests issued, 10 operands arrived, 5 contraction,
+  // 6 epilogue, 7 exchange, 8 cell)
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 0);
+  asm volatile("" ::AMQ_ARG(a.blk[0].Wp), AMQ_ARG(a.blk[0].alpha), AMQ_ARG(a.blk[0].Xp), AMQ_ARG(a.blk[0].beta),
+               AMQ_ARG(a.blk[0].n), AMQ_ARG(a.blk[1].Wp), AMQ_ARG(a.blk[1].alpha), AMQ_ARG(a.blk[1].Xp),
+               AMQ_ARG(a.blk[1].beta), AMQ_ARG(a.blk[1].n), AMQ_ARG(a.m), AMQ_ARG(a.H), AMQ_ARG(a.batch), AMQ_ARG(a.bias0),
+               AMQ_ARG(a.bias1), AMQ_ARG(a.c_prev), AMQ_ARG(a.h_prev), AMQ_ARG(a.h_out), AMQ_ARG(a.c_out),
+               AMQ_ARG(a.hs_out), AMQ_ARG(rowblocks));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, l4 = lane >> 4;
+  const int pr = wv >> 1, kb = wv & 1;  // row block of the workgroup, operand block (0: x and the cell, 1: h)
+  const int bg0 = blockIdx.y * NBT * kTileB;
+  const int batch = a.batch;
+  const int m = (int)a.m, H = (int)a.H;
+  const int rb = blockIdx.x * (NWV / 2) + pr;
+  const bool live = rb < rowblocks;  // (a wave without a row block still meets the barrier)
+
+  // ---- requests, all before the first wait.  This wave's operand block:
+  const uint4* Wp4 = reinterpret_cast<const uint4*>(kb ? a.blk[1].Wp : a.blk[0].Wp);
+  const uint4* Xp4 = reinterpret_cast<const uint4*>(kb ? a.blk[1].Xp : a.blk[0].Xp);
+  const float* alpha = kb ? a.blk[1].alpha : a.blk[0].alpha;
+  const float* beta = kb ? a.blk[1].beta : a.blk[0].beta;
+  const int nlen = kb ? a.blk[1].n : a.blk[0].n;
+  const int wq = (nlen + 127) >> 7;  // 16-byte groups per row
+  // weight words, A-operand view: lane = (tile row l16 = 4 * unit + gate, k-block l4), 32 bytes per plane
+  uint4 araw[KW][2];
+  {
+    const int unit_a = rb * 4 + (l16 >> 2), gate_a = l16 & 3;
+    const bool wok = live && unit_a < H && gate_a < NG;
+    const int base = (wok ? gate_a * H + unit_a : 0) * wq;
+    const int plane = m * wq;
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int v = 0; v < 2; ++v) {
+        const int g = 2 * l4 + v;
+        const uint4 t4 = Wp4[base + i * plane + (g < wq ? g : 0)];
+        araw[i][v] = (wok && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
+      }
+  }
+  // activation words, B-operand view: lane = (batch column l16 of every tile, k-block l4)
+  int bcol[NBT];
+  bool bok[NBT];
+  uint4 braw[NBT][KA][2];
+  float beta_req[NBT];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt) {
+    bcol[bt] = bg0 + bt * kTileB + l16;
+    bok[bt] = bcol[bt] < batch;
+    const int bc = bok[bt] ? bcol[bt] : batch - 1;
+#pragma unroll
+    for (int j = 0; j < KA; ++j)
+#pragma unroll
+      for (int v = 0; v < 2; ++v) {
+        const int g = 2 * l4 + v;
+        const uint4 t4 = Xp4[(j * batch + bc) * wq + (g < wq ? g : 0)];
+        braw[bt][j][v] = (bok[bt] && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
+      }
+    // column coefficients: lane (l16, l4) asks for plane min(l4, KA - 1) of its column
+    beta_req[bt] = beta[bc * KA + (l4 < KA ? l4 : KA - 1)];
+  }
+  // row coefficients (lane l16 < 4 * KW asks for one of the 4 * KW values its row quad needs), and for
+  // the wave that applies the cell the biases and the previous state
+  const int unit_c = rb * 4 + l4;
+  const bool uok = live && unit_c < H;
+  float alpha_req = 0.0f, bias_req = 0.0f, prev[NBT];
+  {
+    const int r = l16 / KW, i = l16 % KW;
+    alpha_req = alpha[((uok && r < NG) ? r * H + unit_c : 0) * KW + i];
+    if (kb == 0) {
+      const float* src = (l16 & 4) ? ((EPI == kEpiGru) ? a.bias1 : nullptr) : a.bias0;
+      const int rr = l16 & 3;
+      bias_req = (src && l16 < 8) ? src[(uok && rr < NG) ? rr * H + unit_c : 0] : 0.0f;
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt) {
+        const int t = (bok[bt] ? bcol[bt] : batch - 1) * H + (uok ? unit_c : 0);
+        prev[bt] = (EPI == kEpiLstm) ? a.c_prev[t] : a.h_prev[t];
+      }
+    }
+  }
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 1);
+
+  // ---- contraction: k-step t multiplies the t-th words of this lane's k-block; the operands of step
+  // t + 1 are expanded under the matrix instructions of step t
+  v4f acc[NBT][KW][KA];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int j = 0; j < KA; ++j) acc[bt][i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+  uint4 aop[KW], anx[KW], bop[NBT][KA], bnx[NBT][KA];
+#pragma unroll
+  for (int i = 0; i < KW; ++i) aop[i] = expand4_signed(word_of(araw[i], 0));
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+    for (int j = 0; j < KA; ++j) bop[bt][j] = expand4_signed(word_of(braw[bt][j], 0));
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 10);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int t = 0; t < kSteps; ++t) {
+    if (t + 1 < kSteps) {
+#pragma unroll
+      for (int i = 0; i < KW; ++i) anx[i] = expand4_signed(word_of(araw[i], t + 1));
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+        for (int j = 0; j < KA; ++j) bnx[bt][j] = expand4_signed(word_of(braw[bt][j], t + 1));
+    }
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int j = 0; j < KA; ++j)
+          acc[bt][i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(as_operand(aop[i]), as_operand(bop[bt][j]),
+                                                                           acc[bt][i][j], 4, 4, 0, kScaleOne, 0, kScaleOne);
+    // issue order inside a step: every matrix instruction followed by its share of the vector
+    // instructions that expand the next step's operands
+    if (t + 1 < kSteps) {
+#pragma unroll
+      for (int g = 0; g < NBT * KW * KA; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, (8 * (KW + NBT * KA) + NBT * KW * KA - 1) / (NBT * KW * KA), 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < KW; ++i) aop[i] = anx[i];
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int j = 0; j < KA; ++j) bop[bt][j] = bnx[bt][j];
+  }
+  // An MFMA reads its operands from all 64 lanes, but the compiler treats it as lane-local and
+  // would sink it into the divergent branches that guard the stores of the epilogue, where lanes of
+  // padded batch columns -- which still supply weight rows -- are masked off.  Pin the accumulators
+  // here, in uniform control flow.
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int j = 0; j < KA; ++j) asm volatile("" : "+v"(acc[bt][i][j]));
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 5);
+
+  // ---- epilogue: d_ij = acc_ij - (1024 - n) are the dot products of the codes (integers, exact in
+  // binary32); y = sum_i alpha_i sum_j beta_j d_ij
+  float btv[NBT][KA];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+    for (int j = 0; j < KA; ++j) btv[bt][j] = __shfl(beta_req[bt], 16 * j + l16, kWave);
+  float alr[4][KW];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int i = 0; i < KW; ++i) alr[r][i] = __shfl(alpha_req, 16 * l4 + r * KW + i, kWave);
+  const float pad = (float)(kSteps * 128 - nlen);
+  float ysum[NBT][4];
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float y = 0.0f;
+#pragma unroll
+      for (int i = 0; i < KW; ++i) {
+        float inner = 0.0f;
+#pragma unroll
+        for (int j = 0; j < KA; ++j) inner = fmaf(btv[bt][j], acc[bt][i][j][r] - pad, inner);
+        y = fmaf(alr[r][i], inner, y);
+      }
+      ysum[bt][r] = y;
+    }
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 6);
+  if (kb == 1) {
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+      xch[(pr * NBT + bt) * 64 + lane] = make_float4(ysum[bt][0], ysum[bt][1], ysum[bt][2], ysum[bt][3]);
+  }
+  lds_barrier();
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 7);
+  if (kb != 0) return;
+  float bias0[4], bias1[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    bias0[r] = __shfl(bias_req, 16 * l4 + r, kWave);
+    bias1[r] = __shfl(bias_req, 16 * l4 + 4 + r, kWave);
+  }
+  // (no early exit for padded batch columns or units: every lane stays active, the stores are predicated)
+#pragma unroll
+  for (int bt = 0; bt < NBT; ++bt) {
+    const float4 o = xch[(pr * NBT + bt) * 64 + lane];
+    const float yh[4] = {o.x, o.y, o.z, o.w};
+    const int t = bcol[bt] * H + unit_c;
+    if constexpr (EPI == kEpiLstm) {
+      const float gi = sigmoidf_dev(ysum[bt][0] + yh[0] + bias0[0]);
+      const float gf = sigmoidf_dev(ysum[bt][1] + yh[1] + bias0[1]);
+      const float go = sigmoidf_dev(ysum[bt][2] + yh[2] + bias0[2]);
+      const float gg = tanhf_dev(ysum[bt][3] + yh[3] + bias0[3]);
+      const float c = fmaf(gf, prev[bt], gi * gg);
+      const float h = go * tanhf_dev(c);
+      if (bok[bt] && uok) {
+        a.c_out[t] = c;
+        a.h_out[t] = h;
+        if (a.hs_out) a.hs_out[t] = h;
+      }
+    } else {
+      const float rg = sigmoidf_dev(ysum[bt][0] + yh[0] + bias0[0] + bias1[0]);
+      const float z = sigmoidf_dev(ysum[bt][1] + yh[1] + bias0[1] + bias1[1]);
+      const float nn = tanhf_dev(fmaf(rg, yh[2] + bias1[2], ysum[bt][2] + bias0[2]));
+      if (bok[bt] && uok) a.h_out[t] = fmaf(z, prev[bt] - nn, nn);
+    }
+  }
+  AMQ_PHASE_B(AMQ_PHASE_OF(a), 8);
 }
 
 // Tiles per wave: as many as keep the accumulators within about 100 registers.
@@ -686,7 +900,70 @@ hipError_t launch_cell_kw(const BmvArgs& a, int k_w, int k_a, int nbt, hipStream
   return hipErrorInvalidValue;
 }
 
+// Measured on config 3 (256 row blocks x 4 batch tiles, W3/A3), whole step: one tile per wave in
+// workgroups of 8 waves (two waves per SIMD, the matrix instructions of one under the vector
+// instructions of the other) 13.2 us; two tiles per wave in workgroups of 4 (one wave per SIMD, a
+// wave's matrix and vector instructions do not overlap) 13.5 us; one tile, 4 waves 13.5 us; two
+// tiles, 8 waves (half the compute units) 15.7 us.
+template <int KW, int KA, int EPI>
+hipError_t launch_pair_one(const BmvArgs& a, hipStream_t s) {
+  if constexpr (KW > 3 || KW * KA > 9) {
+    return hipErrorInvalidValue;
+  } else {
+    constexpr int NBT = 1, NWV = 8;
+    const int rowblocks = (int)((a.H + 3) / 4);
+    const int groups = (a.batch + NBT * kTileB - 1) / (NBT * kTileB);
+    dim3 grid((unsigned)((rowblocks + NWV / 2 - 1) / (NWV / 2)), (unsigned)groups);
+    BmvArgs b = a;
+    AMQ_PHASE_ATTACH(b);
+    hipLaunchKernelGGL((mfma4p_kernel<KW, KA, NBT, EPI, NWV>), grid, dim3(64 * NWV), 0, s, b, rowblocks);
+    return hipGetLastError();
+  }
+}
+
+template <int KW, int EPI>
+hipError_t launch_pair_ka(const BmvArgs& a, int k_a, hipStream_t s) {
+  switch (k_a) {
+    case 1: return launch_pair_one<KW, 1, EPI>(a, s);
+    case 2: return launch_pair_one<KW, 2, EPI>(a, s);
+    case 3: return launch_pair_one<KW, 3, EPI>(a, s);
+    case 4: return launch_pair_one<KW, 4, EPI>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int EPI>
+hipError_t launch_pair_kw(const BmvArgs& a, int k_w, int k_a, hipStream_t s) {
+  switch (k_w) {
+    case 1: return launch_pair_ka<1, EPI>(a, k_a, s);
+    case 2: return launch_pair_ka<2, EPI>(a, k_a, s);
+    case 3: return launch_pair_ka<3, EPI>(a, k_a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 }  // namespace
+
+// Recurrent steps with vectors of at most 1024 entries, two or more batch tiles, and at most two
+// row-block x tile tasks per SIMD of the chip (beyond that the several-tiles cell kernel takes over;
+// a single tile stays with the paired form of the one-tile kernel).
+bool mfma4_pair_supported(const BmvArgs& a, int k_w, int k_a, int epi) {
+  if (epi != kEpiLstm && epi != kEpiGru) return false;
+  if (a.blk[0].n > 1024 || a.blk[1].n > 1024) return false;
+  if (k_w > 3 || k_w * k_a > 9) return false;
+  const long long tiles = (a.batch + kTileB - 1) / kTileB;
+  const long long rowblocks = (a.H + 3) / 4;
+  if (tiles < 2 || rowblocks * tiles > 2048) return false;
+  if (a.m * 8 * k_w >= (1LL << 31)) return false;  // weight offsets in 16-byte units
+  if ((long long)a.batch * a.H >= (1LL << 31)) return false;
+  return true;
+}
+
+hipError_t launch_mfma4_pair(const BmvArgs& a, int k_w, int k_a, int epi, hipStream_t s) {
+  if (epi == kEpiLstm) return launch_pair_kw<kEpiLstm>(a, k_w, k_a, s);
+  if (epi == kEpiGru) return launch_pair_kw<kEpiGru>(a, k_w, k_a, s);
+  return hipErrorInvalidValue;
+}
 
 // Plain products (no integer hook) with vectors of at most 1024 entries, at least two batch tiles,
 // and enough row-block tasks to give every SIMD of the chip two of them; sizes whose element

@@ -30,8 +30,8 @@ STEP_MARKS = [(0, "start"), (1, "requests issued (activation words, first row bl
               (6, "coefficient epilogue done"), (7, "x/h exchange (barrier)"), (8, "cell applied, stores issued")]
 
 
-def _report(name, names, samples):
-    samples = np.asarray(samples, np.int64)           # [launch, wave, mark]
+def _report(name, names, samples, row0):
+    samples = np.asarray(samples, np.int64)[:, row0:row0 + 8]   # [launch, wave, mark]
     print(name)
     start = samples[:, 0, names[0][0]]
     nwaves = [w for w in range(samples.shape[1]) if (samples[:, w, names[0][0]] != 0).all()]
@@ -66,32 +66,28 @@ def main():
     Hp, bh = binding.quantize_activations(h, k, 2)
     ho, co = torch.empty_like(c), torch.empty_like(c)
 
-    def quant():
-        L.amq_quantize_activations(h.data_ptr(), B, H, k, 2, P.data_ptr(), be.data_ptr(), s)
+    ws = binding.lstm_workspace(H, H, B, k, dev)
 
-    def step():
-        L.amq_lstm_step_packed(Wxp.data_ptr(), ax.data_ptr(), Whp.data_ptr(), ah.data_ptr(), H, H, k, None,
-                               Xp.data_ptr(), bx.data_ptr(), Hp.data_ptr(), bh.data_ptr(), c.data_ptr(), B, k,
-                               ho.data_ptr(), co.data_ptr(), s)
+    def step():   # one whole step: the quantizer launch (x_t and h_{t-1}), then products + cell
+        L.amq_lstm_step(Wxp.data_ptr(), ax.data_ptr(), Whp.data_ptr(), ah.data_ptr(), H, H, k, None, x.data_ptr(),
+                        h.data_ptr(), c.data_ptr(), B, k, 2, ho.data_ptr(), co.data_ptr(), ws.data_ptr(), ws.numel(), s)
 
-    for name, names, fn in (("on-line quantizer, %d vectors of %d, %d-bit, T=2" % (B, H, k), QUANT_MARKS, quant),
-                            ("fused products + LSTM cell, 4H x 2H = %d x %d, batch %d, W%d/A%d" % (4 * H, 2 * H, B, k, k),
-                             STEP_MARKS, step)):
-        samples = []
-        for it in range(40):
-            L.amq_debug_set_phase_buffer(None)
-            for _ in range(3):     # the launches before the measured one alternate the two kernels, as a sequence does
-                quant()
-                step()
-            buf.zero_()
-            torch.cuda.synchronize()
-            L.amq_debug_set_phase_buffer(buf.data_ptr())
-            fn()
-            torch.cuda.synchronize()
-            if it >= 5:
-                samples.append(buf.cpu().numpy().copy())
+    samples = []
+    for it in range(40):
         L.amq_debug_set_phase_buffer(None)
-        _report(name, names, samples)
+        for _ in range(3):
+            step()
+        buf.zero_()
+        torch.cuda.synchronize()
+        L.amq_debug_set_phase_buffer(buf.data_ptr())
+        step()
+        torch.cuda.synchronize()
+        if it >= 5:
+            samples.append(buf.cpu().numpy().copy())
+    L.amq_debug_set_phase_buffer(None)
+    _report("on-line quantizer, %d vectors of %d, %d-bit, T=2" % (2 * B, H, k), QUANT_MARKS, samples, 0)
+    _report("products + LSTM cell, 4H x 2H = %d x %d, batch %d, W%d/A%d" % (4 * H, 2 * H, B, k, k), STEP_MARKS,
+            samples, 8)
 
 
 if __name__ == "__main__":
