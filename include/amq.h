@@ -169,6 +169,30 @@ int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32
                          float* c_out, void* stream);
 
 /*
+ * `groups` independent batch-1 LSTM steps on quantized operands in one launch (the recurrent
+ * counterpart of amq_binary_gemv_grouped: how the memory-bound batch-1 step -- the case App. A times --
+ * is measured with every weight plane coming from HBM rather than from cache).  Group g uses
+ *   Wxp + g * k_w * 4H * wpr(I), alpha_x + g * 4H * k_w, Whp + g * k_w * 4H * wpr(H), alpha_h + g * 4H * k_w,
+ *   Xp + g * k_a * wpr(I), beta_x + g * k_a, Hp + g * k_a * wpr(H), beta_h + g * k_a,
+ *   c_prev, h_out, c_out + g * H;  bias [4H] (nullable) is shared.
+ * Same arithmetic as amq_lstm_step_packed with B = 1 on every group.  groups <= 65535; I, H <= 8192.
+ */
+int amq_lstm_step_packed_grouped(int64_t groups, const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                                 const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                                 const uint32_t* Xp, const float* beta_x, const uint32_t* Hp,
+                                 const float* beta_h, const float* c_prev, int k_a, float* h_out,
+                                 float* c_out, void* stream);
+
+/*
+ * Bandwidth yardstick (not part of the method): reads buf[0 .. bytes) once with 16-byte loads and
+ * leaves an xor checksum per workgroup in sink (device, AMQ_STREAM_PROBE_SINK_WORDS 64-bit words).
+ * bytes must be a multiple of 16, buf 16-byte aligned.  Timed over a buffer larger than the last-level
+ * cache it gives the read rate this GPU sustains, the practical ceiling next to the nominal HBM peak.
+ */
+#define AMQ_STREAM_PROBE_SINK_WORDS 4096
+int amq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
+/*
  * `steps` consecutive LSTM steps in one call (the recurrence of Eq. 6 over a
  * sequence): xs [steps][B][I]; h and c [B][H] are read as the initial state and
  * overwritten with the final state; hs [steps][B][H] (nullable) receives every

@@ -19,7 +19,8 @@ EXPORTS = [
     "amq_wpr", "amq_version", "amq_status_string", "amq_last_hip_error",
     "amq_quantize_weights", "amq_quantize_activations", "amq_ls_update", "amq_bst_assign",
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
-    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed", "amq_lstm_sequence",
+    "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed",
+    "amq_lstm_step_packed_grouped", "amq_stream_read_probe", "amq_lstm_sequence",
     "amq_lstm_sequence_flag_offset",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
@@ -68,6 +69,9 @@ def lib():
                                            _p]
         L.amq_lstm_step_packed.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _i64, _int,
                                            _p, _p, _p]
+        L.amq_lstm_step_packed_grouped.argtypes = [_i64, _p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _p, _p, _int,
+                                                   _p, _p, _p]
+        L.amq_stream_read_probe.argtypes = [_p, _sz, _p, _p]
         L.amq_lstm_sequence.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _i64, _p, _p, _i64, _int,
                                         _int, _p, _p, _sz, _p]
         L.amq_gru_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
@@ -293,6 +297,38 @@ def lstm_step_packed(Wxp, alpha_x, Whp, alpha_h, I, H, bias, Xp, beta_x, Hp, bet
                                       _dev(c_prev, torch.float32), B, k_a, _dev(h_out, torch.float32),
                                       _dev(c_out, torch.float32), _stream()))
     return h_out, c_out
+
+
+def lstm_step_packed_grouped(Wxp, alpha_x, Whp, alpha_h, I, H, bias, Xp, beta_x, Hp, beta_h, c_prev, h_out=None,
+                             c_out=None):
+    """G independent batch-1 LSTM steps: Wxp [G, k_w, 4H, wpr(I)], alpha_x [G, 4H, k_w], Whp, alpha_h likewise,
+    Xp [G, k_a, wpr(I)], beta_x [G, k_a], Hp, beta_h likewise, c_prev [G, H] -> h_out, c_out [G, H]."""
+    G, k_w = Wxp.shape[0], Wxp.shape[1]
+    k_a = Xp.shape[1]
+    if h_out is None:
+        h_out = torch.empty_like(c_prev)
+    if c_out is None:
+        c_out = torch.empty_like(c_prev)
+    _check(lib().amq_lstm_step_packed_grouped(G, _dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
+                                              _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, k_w,
+                                              _opt(bias), _dev(Xp, torch.int32), _dev(beta_x, torch.float32),
+                                              _dev(Hp, torch.int32), _dev(beta_h, torch.float32),
+                                              _dev(c_prev, torch.float32), k_a, _dev(h_out, torch.float32),
+                                              _dev(c_out, torch.float32), _stream()))
+    return h_out, c_out
+
+
+STREAM_PROBE_SINK_WORDS = 4096
+
+
+def stream_read_probe(buf, sink=None):
+    """Reads the whole tensor `buf` (bytes a multiple of 16) once; returns the per-workgroup checksums."""
+    if sink is None:
+        sink = torch.empty(STREAM_PROBE_SINK_WORDS, dtype=torch.int64, device=buf.device)
+    if not buf.is_cuda or not buf.is_contiguous():
+        raise AmqError("expected a contiguous GPU tensor")
+    _check(lib().amq_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()))
+    return sink
 
 
 def lstm_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias, xs, h, c, k_a, T, ws=None, hs=None):

@@ -370,6 +370,42 @@ static int lstm_step_launch(const uint32_t* Wxp, const float* alpha_x, const uin
   return hip_status(amq::launch_lstm_pointwise(w.pre0, c_prev, h_out, c_out, hs_out, B, H, s));
 }
 
+int amq_lstm_step_packed_grouped(int64_t groups, const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                                 const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                                 const uint32_t* Xp, const float* beta_x, const uint32_t* Hp, const float* beta_h,
+                                 const float* c_prev, int k_a, float* h_out, float* c_out, void* stream) {
+  if (!Wxp || !alpha_x || !Whp || !alpha_h || !Xp || !beta_x || !Hp || !beta_h || !c_prev || !h_out || !c_out)
+    return AMQ_ERR_INVALID;
+  if (!bits_ok(k_w) || !bits_ok(k_a) || I <= 0 || H <= 0 || groups <= 0) return AMQ_ERR_INVALID;
+  if (!aligned(Wxp, 16) || !aligned(Whp, 16) || !aligned(Xp, 16) || !aligned(Hp, 16)) return AMQ_ERR_INVALID;
+  if (groups > 65535 || !amq::bmv_supported((int)I, (int)H, k_a, 1)) return AMQ_ERR_UNSUPPORTED;
+  amq::BmvArgs b{};
+  b.blk[0] = amq::BmvBlock{Wxp, alpha_x, Xp, beta_x, (int)I};
+  b.blk[1] = amq::BmvBlock{Whp, alpha_h, Hp, beta_h, (int)H};
+  b.m = 4 * H;
+  b.H = H;
+  b.batch = 1;
+  b.bias0 = bias;
+  b.c_prev = c_prev;
+  b.h_out = h_out;
+  b.c_out = c_out;
+  b.groups = (int)groups;
+  b.g_Wp = (long long)k_w * 4 * H * amq_wpr(I);
+  b.g_Wp1 = (long long)k_w * 4 * H * amq_wpr(H);
+  b.g_alpha = b.g_alpha1 = 4 * H * k_w;
+  b.g_Xp = (long long)k_a * amq_wpr(I);
+  b.g_Xp1 = (long long)k_a * amq_wpr(H);
+  b.g_beta = b.g_beta1 = k_a;
+  b.g_state = H;
+  return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, static_cast<hipStream_t>(stream)));
+}
+
+int amq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+  if (!buf || !sink || bytes == 0 || (bytes & 15) || !aligned(buf, 16) || !aligned(sink, 8)) return AMQ_ERR_INVALID;
+  return hip_status(amq::launch_stream_read(buf, bytes, static_cast<unsigned long long*>(sink),
+                                            static_cast<hipStream_t>(stream)));
+}
+
 int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
                          int64_t I, int64_t H, int k_w, const float* bias, const uint32_t* Xp,
                          const float* beta_x, const uint32_t* Hp, const float* beta_h, const float* c_prev,

@@ -69,8 +69,8 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
 #pragma unroll
   for (int k = 0; k < NBLK; ++k) {
     const int wpr = cpr[k] * 4;
-    const uint32_t* Wp = a.blk[k].Wp + grp * a.g_Wp;
-    const float* alpha = a.blk[k].alpha + grp * a.g_alpha;
+    const uint32_t* Wp = a.blk[k].Wp + grp * (k ? a.g_Wp1 : a.g_Wp);
+    const float* alpha = a.blk[k].alpha + grp * (k ? a.g_alpha1 : a.g_alpha);
 #pragma unroll
     for (int s = 0; s < NSEG; ++s)
 #pragma unroll
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
 #pragma unroll
   for (int k = 0; k < NBLK; ++k) {
     const int total = KA * batch * cpr[k];
-    const uint4* src = reinterpret_cast<const uint4*>(a.blk[k].Xp + grp * a.g_Xp);
+    const uint4* src = reinterpret_cast<const uint4*>(a.blk[k].Xp + grp * (k ? a.g_Xp1 : a.g_Xp));
     for (int t = threadIdx.x; t < total; t += 256) xs[xoff[k] + t] = src[t];
   }
   __syncthreads();
@@ -116,7 +116,8 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
             if (ok[s]) prev[s] = a.Y[grp * a.g_Y + (long long)b * a.m + row[s]];
         }
       } else if (ok[0]) {
-        prev[0] = (EPI == kEpiLstm) ? a.c_prev[(long long)b * a.H + row[0]] : a.h_prev[(long long)b * a.H + row[0]];
+        prev[0] = (EPI == kEpiLstm) ? a.c_prev[grp * a.g_state + (long long)b * a.H + row[0]]
+                                    : a.h_prev[(long long)b * a.H + row[0]];
       }
     }
     float part[NBLK][NSEG];
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
     for (int k = 0; k < NBLK; ++k) {
       uint4 xq[KA];
       float bt[KA];
-      const float* beta = a.blk[k].beta + grp * a.g_beta;
+      const float* beta = a.blk[k].beta + grp * (k ? a.g_beta1 : a.g_beta);
 #pragma unroll
       for (int j = 0; j < KA; ++j) {
         xq[j] = (sub < cpr[k]) ? xs[xoff[k] + (j * batch + b) * cpr[k] + sub] : make_uint4(0, 0, 0, 0);
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(256) void bmv_kernel(BmvArgs a) {
         const long long u = row[0];
 #pragma unroll
         for (int s = 0; s < 4; ++s) pre[s] += bs0[s];
-        const long long t = (long long)b * a.H + u;
+        const long long t = grp * a.g_state + (long long)b * a.H + u;
         const float gi = sigmoidf_dev(pre[0]);
         const float gf = sigmoidf_dev(pre[1]);
         const float go = sigmoidf_dev(pre[2]);

@@ -98,4 +98,39 @@ hipError_t launch_gru_pointwise(const float* pre_x, const float* pre_h, const fl
   return hipGetLastError();
 }
 
+// Read-only streaming yardstick: every thread walks the buffer with 16-byte loads at a stride of the
+// whole grid (each wave-wide load covers 1 KiB of consecutive memory), folds what it reads with xor
+// so that nothing can be dropped, and the workgroup leaves one 64-bit word.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ buf, long long n16,
+                                                          unsigned long long* __restrict__ sink) {
+  __shared__ unsigned long long part[4];
+  const long long stride = (long long)gridDim.x * 256;
+  uint4 acc = make_uint4(0, 0, 0, 0);
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  // four loads in flight per thread
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
+    acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
+    acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+    acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
+    acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = buf[i];
+    acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
+  }
+  unsigned long long v = ((unsigned long long)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v ^= __shfl_xor(v, o, kWave);
+  if (lane_id() == 0) part[wave_id()] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+hipError_t launch_stream_read(const void* buf, size_t bytes, unsigned long long* sink, hipStream_t s) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(kStreamReadBlocks), dim3(256), 0, s, static_cast<const uint4*>(buf),
+                     (long long)(bytes / 16), sink);
+  return hipGetLastError();
+}
+
 }  // namespace amq

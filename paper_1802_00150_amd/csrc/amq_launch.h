@@ -156,8 +156,11 @@ struct BmvArgs {
   const long long* tgt; // several-tiles store kernel only, nullable: one output row index per batch entry ...
   float* tgt_out;       // ... whose output value is also written here, [batch] (Y may then be null)
   int lg;               // filled by launch_bmv
-  int groups;           // store mode: independent products in one launch (1 otherwise)
+  int groups;           // small-batch kernel: independent products / cells in one launch (1 otherwise)
+  // strides in elements between consecutive groups: operands of the x block, of the h block (LSTM
+  // mode), outputs of store mode, and state vectors (c_prev, h_out, c_out, hs_out) of LSTM mode
   long long g_Wp, g_alpha, g_Xp, g_beta, g_Y;
+  long long g_Wp1, g_alpha1, g_Xp1, g_beta1, g_state;
   AMQ_PHASE_MEMBER
 };
 
@@ -228,6 +231,12 @@ struct SeqGArgs {
 };
 bool lstm_seqg_supported(long long I, long long H, long long B, int k_w, int k_a);
 hipError_t launch_lstm_seqg(SeqGArgs a, int k_w, int k_a, hipStream_t s);
+
+// ---- bandwidth yardstick ------------------------------------------------------------------
+// Reads `bytes` (a multiple of 16) once with 16-byte loads over kStreamReadBlocks workgroups and leaves
+// an xor checksum per workgroup in sink [kStreamReadBlocks].
+constexpr int kStreamReadBlocks = 4096;
+hipError_t launch_stream_read(const void* buf, size_t bytes, unsigned long long* sink, hipStream_t s);
 
 // ---- cells -----------------------------------------------------------------------------
 // pre-activations -> new state, Eq. 6 (LSTM) and the reset-after GRU

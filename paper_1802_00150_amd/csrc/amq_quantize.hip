@@ -143,10 +143,11 @@ hipError_t launch_k(const QuantArgs& a, int max_n, hipStream_t s) {
   if (total == 0) return hipSuccess;
   const int nslots = nvec ? 2 * ((max_n + 127) / 128) : 1;
   int nw = nvec >= 1024 ? 1 : 4;
-  // long rows in the throughput regime: four waves of 16 entries per lane keep ~90 registers and
-  // five waves per SIMD, against ~230 registers and two waves for one wave of 64 entries per
-  // lane (measured +35 / +18 / +9 % at k = 1 / 2 / 3 on 16384 x 4096, -6 % at k = 4)
-  if (nvec >= 1024 && nslots >= 32 && K <= 3) nw = 4;
+  // long rows in the throughput regime: four waves of 16 entries per lane keep about 100 registers
+  // and four to five waves per SIMD, against more than 250 registers for one wave of 64 entries per
+  // lane (measured on 16384 x 4096: 760 -> 513 us at k = 4; two waves of 32 entries per lane:
+  // 206 against 175 us at k = 2, 334 against 297 us at k = 3)
+  if (nvec >= 1024 && nslots >= 32) nw = 4;
   if (nw > nslots) nw = 1;
   if (nw == 1 && nslots > 64) nw = 4;
   if (nslots > 256) return hipErrorInvalidValue;

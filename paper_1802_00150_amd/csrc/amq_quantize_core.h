@@ -11,6 +11,8 @@
 // in binary64 and the k x k system is solved in binary64 with exact integer cofactors, then
 // rounded once.  The comparison "w >= midpoint" that decides a code is binary32.
 #pragma once
+#include <type_traits>
+
 #include "amq_device.h"
 
 namespace amq {
@@ -134,6 +136,20 @@ __device__ __forceinline__ void ls_solve_f64(int n, const double* d, const doubl
     alpha[1] = (float)((c01 * q[0] + c11 * q[1] + c12 * q[2]) * inv);
     alpha[2] = (float)((c02 * q[0] + c12 * q[1] + c22 * q[2]) * inv);
   }
+}
+
+// lane j keeps the wave-uniform 64-bit value `mk` (the ballot of slot j).  `ln` is the lane number as
+// the caller's pass sees it (see pass_lane).
+__device__ __forceinline__ void keep_in_lane(unsigned long long& mine, unsigned long long mk, int j, int ln) {
+  if (ln == j) mine = mk;
+}
+// The lane number, opaque to the compiler: a pass over the slots compares it with every slot number,
+// and left to itself the compiler computes those comparison masks once for the whole kernel and keeps
+// (then spills) two scalar registers per slot.
+__device__ __forceinline__ int pass_lane() {
+  int ln = lane_id();
+  asm volatile("" : "+v"(ln));
+  return ln;
 }
 
 __device__ __forceinline__ float readlane_f(float v, int l) {
@@ -396,8 +412,7 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
   for (int i = 0; i < K; ++i) {
     unsigned long long mine = 0ull;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      if (lane == j) mine = mk[i][j];
+    for (int j = 0; j < NJ; ++j) keep_in_lane(mine, mk[i][j], j, lane);
     mym[i] = mine;
   }
 }
@@ -423,11 +438,24 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
   constexpr int NP = K * (K - 1) / 2;
   const int lane = lane_id();
   const double dn = (double)n;
-  if (do_greedy) {
+  const bool n_pow2 = (n & (n - 1)) == 0;
+  const double inv_n = 1.0 / dn;  // exact for a power of two, where s / n == s * inv_n bit for bit
+  // Every slot of this wave inside the vector (the common case of the throughput regime: rows whose
+  // length is a multiple of 64 * NJ * NW) takes a second instantiation of the per-entry loops without
+  // the range checks.
+  const bool full = nj == NJ && (base + NJ) * 64 <= n;
+  // One cycle has no effect at K = 1 (Eq. 5 returns sum |w| / n again -- the same terms in the same
+  // order -- and the only midpoint of the code table {-alpha, +alpha} is 0), so the greedy codes and
+  // coefficient are final there.
+  if (K == 1 && do_greedy) iters = 0;
+
+  auto greedy = [&](auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
     // ---- greedy initialisation, Eq. 4.  One pass per stage: it assigns the signs, updates the
     // residual and accumulates the l1 norm of the new residual for the next stage.
     float r[NJ];
     double s[1];
+    double lane_l1;  // this lane's share of sum |w|, which is also its share of b_1^T w
     {
       double s0 = 0.0, s1 = 0.0;
 #pragma unroll
@@ -435,35 +463,48 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
         r[j] = w[j];
         if (j & 1) s1 += (double)fabsf(w[j]); else s0 += (double)fabsf(w[j]);
       }
-      s[0] = s0 + s1;
+      lane_l1 = s0 + s1;
+      s[0] = lane_l1;
     }
     block_totals<NW, 1>(s, sh, phase);
 #pragma unroll
     for (int i = 0; i < K; ++i) {
-      const float al = (float)(s[0] / dn);
+      const float al = n_pow2 ? (float)(s[0] * inv_n) : (float)(s[0] / dn);
       alpha[i] = al;
       unsigned long long mine = 0ull;
       double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
+      const int ln = pass_lane();
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        if (j < nj) {
-          const bool valid = (base + j) * 64 + lane < n;
+        if (FULL || j < nj) {
+          const bool valid = FULL || (base + j) * 64 + lane < n;
           const bool bit = valid && (r[j] >= 0.0f);
-          const unsigned long long mk = __ballot(bit);
-          if (lane == j) mine = mk;
-          const double sw = bit ? (double)w[j] : -(double)w[j];
-          const float rn = valid ? r[j] - (bit ? al : -al) : 0.0f;
-          r[j] = rn;
-          if (j & 1) { q1 += sw; s1 += (double)fabsf(rn); } else { q0 += sw; s0 += (double)fabsf(rn); }
+          keep_in_lane(mine, __ballot(bit), j, ln);
+          if constexpr (K > 1) {
+            const float rn = valid ? r[j] - (bit ? al : -al) : 0.0f;
+            r[j] = rn;
+            if (i > 0) {  // (stage 0: b_1^T w is sum |w|, term by term)
+              const double sw = bit ? (double)w[j] : -(double)w[j];
+              if (j & 1) q1 += sw; else q0 += sw;
+            }
+            if (i + 1 < K) {
+              if (j & 1) s1 += (double)fabsf(rn); else s0 += (double)fabsf(rn);
+            }
+          }
         }
+        // (keeps the slots apart: left alone, the scheduler forms all ballots first and spills them)
+        if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
       }
       mym[i] = mine;
-      q[i] = q0 + q1;
+      q[i] = (i == 0) ? lane_l1 : q0 + q1;
       if (i + 1 < K) {
         s[0] = s0 + s1;
         block_totals<NW, 1>(s, sh, phase);
       }
     }
+  };
+  if (do_greedy) {
+    if (full) greedy(std::true_type{}); else greedy(std::false_type{});
   }
   AMQ_PHASE(marks, 2);
   for (int it = 0; it < iters; ++it) {
@@ -482,9 +523,14 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
       }
       block_totals<NW, K + NP>(red, sh, phase);
       AMQ_PHASE(marks, 4 + 4 * it);
-      int G[K][K];
-      double qq[K];
-      {
+      if constexpr (K <= 3) {
+        double qq[K];
+#pragma unroll
+        for (int i = 0; i < K; ++i) qq[i] = red[i];
+        ls_solve_f64<K>(n, red + K, qq, alpha);
+      } else {
+        int G[K][K];
+        double qq[K];
         int t = K;
 #pragma unroll
         for (int i = 0; i < K; ++i) {
@@ -497,8 +543,8 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
             G[j][i] = G[i][j];
           }
         }
+        ls_solve<K>(G, qq, alpha);
       }
-      ls_solve<K>(G, qq, alpha);
       AMQ_PHASE(marks, 5 + 4 * it);
       if (!do_bst) break;
     }
@@ -533,34 +579,43 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
     // ---- codes with the coefficients fixed (Alg. 1); the position in the sorted table is the
     // number of midpoints <= w, which is where the k-comparison tree walk ends.
     const bool more = do_ls && (it + 1 < iters);  // B^T w is needed by another cycle
-    unsigned long long mine[K];
-    double qa[K], qb[K];
+    auto assign = [&](auto full_c, auto more_c) {
+      constexpr bool FULL = decltype(full_c)::value;
+      constexpr bool MORE = decltype(more_c)::value;
+      unsigned long long mine[K];
+      double qa[K], qb[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) { mine[i] = 0ull; qa[i] = 0.0; qb[i] = 0.0; }
+      for (int i = 0; i < K; ++i) { mine[i] = 0ull; qa[i] = 0.0; qb[i] = 0.0; }
+      const int ln = pass_lane();
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      if (j < nj) {
-        const bool valid = (base + j) * 64 + lane < n;
-        int pos = 0;
+      for (int j = 0; j < NJ; ++j) {
+        if (FULL || j < nj) {
+          const bool valid = FULL || (base + j) * 64 + lane < n;
+          int pos = 0;
 #pragma unroll
-        for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
-        const double wd = (double)w[j];
+          for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
+          const double wd = (double)w[j];
 #pragma unroll
-        for (int i = 0; i < K; ++i) {
-          const bool bit = valid && ((bm[i] >> pos) & 1u);
-          const unsigned long long mk = __ballot(bit);
-          if (lane == j) mine[i] = mk;
-          if (more) {
-            if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
+          for (int i = 0; i < K; ++i) {
+            const bool bit = valid && ((bm[i] >> pos) & 1u);
+            keep_in_lane(mine[i], __ballot(bit), j, ln);
+            if constexpr (MORE) {
+              if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
+            }
           }
         }
+        if ((j & 3) == 3) __builtin_amdgcn_sched_barrier(0);
       }
-    }
 #pragma unroll
-    for (int i = 0; i < K; ++i) { mym[i] = mine[i]; q[i] = qa[i] + qb[i]; }
+      for (int i = 0; i < K; ++i) { mym[i] = mine[i]; q[i] = qa[i] + qb[i]; }
+    };
+    if (full) {
+      if (more) assign(std::true_type{}, std::true_type{}); else assign(std::true_type{}, std::false_type{});
+    } else {
+      if (more) assign(std::false_type{}, std::true_type{}); else assign(std::false_type{}, std::false_type{});
+    }
     AMQ_PHASE(marks, 7 + 4 * it);
   }
-
 }
 
 }  // namespace amq

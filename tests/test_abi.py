@@ -76,6 +76,14 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 16000, 16000, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_lstm_step_packed_grouped(3, p, p, p, p, 8, 8, 2, None, p, p, p, p, null, 2, p, p, None) == INVALID
+    assert L.amq_lstm_step_packed_grouped(0, p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 2, p, p, None) == INVALID
+    assert L.amq_lstm_step_packed_grouped(70000, p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_lstm_step_packed_grouped(3, p, p, p, p, 9000, 8, 2, None, p, p, p, p, p, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_stream_read_probe(p, 24, p, None) == INVALID          # not a multiple of 16
+    assert L.amq_stream_read_probe(p, 0, p, None) == INVALID
+    assert L.amq_stream_read_probe(null, 32, p, None) == INVALID
+    assert L.amq_lstm_step_static(p, p, p, p, 8, 8, 2, None, p, p, null, 1, 2, 2, p, p, None) == INVALID
     # comparison quantizer and error measure
     assert L.amq_quantize_refined_greedy(null, 4, 4, 4, 2, p, p, None) == INVALID
     assert L.amq_quantize_refined_greedy(p, 4, 8, 4, 2, p, p, None) == INVALID

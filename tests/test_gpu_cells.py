@@ -115,6 +115,49 @@ def test_lstm_step_packed(amq, I, H, B, k_w, k_a):
     assert_vec_close(host(h_g), h_ref, "h")
 
 
+@pytest.mark.parametrize("G,I,H,k_w,k_a", [(5, 300, 200, 2, 2), (3, 1024, 1024, 3, 3), (70, 64, 33, 1, 4), (2, 2000, 129, 2, 3)])
+def test_lstm_step_packed_grouped(amq, G, I, H, k_w, k_a):
+    # G independent batch-1 cells in one launch (how the memory-bound step is streamed from HBM): every
+    # group against its own oracle cell, operands quantized by the oracle
+    g = np.random.default_rng(G * 31 + I + H)
+    bias = (g.standard_normal(4 * H) * 0.1).astype(np.float32)
+    packs = {k: [] for k in ("Wxp", "ax", "Whp", "ah", "Xp", "bx", "Hp", "bh", "c")}
+    refs = []
+    say("grouped packed lstm G=%d I=%d H=%d W%d/A%d" % (G, I, H, k_w, k_a))
+    for _ in range(G):
+        Wx = (g.standard_normal((4 * H, I)) * 0.05).astype(np.float32)
+        Wh = (g.standard_normal((4 * H, H)) * 0.05).astype(np.float32)
+        x = g.standard_normal((1, I)).astype(np.float32)
+        h = np.tanh(g.standard_normal((1, H))).astype(np.float32)
+        c = g.standard_normal((1, H)).astype(np.float32)
+        Wxp, ax = quantized(Wx, k_w)
+        Whp, ah = quantized(Wh, k_w)
+        Xp, bx = oracle.quantize_rows(x, k_a, 2)
+        Hp, bh = oracle.quantize_rows(h, k_a, 2)
+        for k, v in zip(packs, (Wxp, ax, Whp, ah, Xp[:, 0], bx[0], Hp[:, 0], bh[0], c[0])):
+            packs[k].append(v)
+        refs.append(oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, x, h, c, k_a, 2))
+    d = {k: to_dev(np.stack(v)) for k, v in packs.items()}
+    h_g, c_g = amq.lstm_step_packed_grouped(d["Wxp"], d["ax"], d["Whp"], d["ah"], I, H, to_dev(bias), d["Xp"], d["bx"],
+                                            d["Hp"], d["bh"], d["c"])
+    for gi in range(G):
+        assert_vec_close(host(h_g)[gi][None, :], refs[gi][0], "h of group %d" % gi)
+        assert_vec_close(host(c_g)[gi][None, :], refs[gi][1], "c of group %d" % gi)
+
+
+def test_stream_read_probe_reads_every_byte(amq):
+    # the bandwidth yardstick folds everything it reads into per-workgroup checksums
+    import torch
+    g = np.random.default_rng(5)
+    for n16 in (1, 255, 4096 * 256 * 4 + 77, 3_000_001):
+        a = g.integers(0, 2 ** 32, size=(n16, 4), dtype=np.uint64).astype(np.uint32)
+        sink = amq.stream_read_probe(to_dev(a))
+        got = np.bitwise_xor.reduce(host(sink).view(np.uint64))
+        x = np.bitwise_xor.reduce(a, axis=0).astype(np.uint64)
+        want = ((x[0] ^ x[2]) << np.uint64(32)) | (x[1] ^ x[3])
+        assert got == want, (n16, hex(int(got)), hex(int(want)))
+
+
 def code_differences(a_prev, b_prev, k_a, T):
     """Rows of two versions of the same state that the on-line quantizer treats differently: final
     codes differ, or final coefficients differ by more than 1e-5 of the largest (an entry that crossed
