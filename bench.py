@@ -7,10 +7,15 @@ A step is one pass of the whole hot path -- on-line quantization of x_t and h_{t
 binary products with both weight blocks, the coefficient epilogue and the cell -- over one
 batch of synthetic input that already sits in HBM.  The primary line reports the batch-64
 LSTM (hidden 1024, W3/A3) in steps/s; `also` carries the batch-1 LSTM (hidden 300, W2/A2),
-the streamed batch-1 binary GEMV in GB/s (the HBM-bound kernel), the cache-resident GEMV
-latency, the GRU + projection step and the offline weight quantizer.  `roofline` describes the
-dominant kernel of the primary workload, `roofline_gemv` the HBM-bound GEMV.  `cpu_baseline`
-is the CPU oracle timed on a bounded sample of the primary workload.
+the streamed batch-1 LSTM step and binary GEMV in GB/s (the HBM-bound kernels), the cache-resident
+GEMV latency, the GRU + projection step and the offline weight quantizer.  `roofline` describes the
+kernel of the primary workload that takes the most time, `roofline_lstm_b1` and `roofline_gemv` the
+HBM-bound kernels (each fraction against the nominal 8 TB/s and against a read-only streaming probe
+measured in the same run).  `cpu_baseline` is the CPU oracle timed on a bounded sample of the primary
+workload.
+
+The primary line never times fewer than 100 sequence calls after 10 warm-up calls, whatever --steps
+and --warmup say; `steps` and `warmup` in the line are what was really run.
 
 One GPU only: nothing here shards, and --gpus above 1 is refused.
 """
@@ -33,9 +38,15 @@ FP4_MFMA_PEAK_TFLOPS = 10100.0               # dense fp4 matrix cores
 # profiles/gemv_streamed_4096x1024.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (scale factors from a plain
 # 512 MiB device copy) = (2 x 270913.6 + 8192.6) KiB
 GEMV_TRAFFIC_BYTES = (2 * 270913.6 + 8192.6) * 1024
-# the same for the fused kernel of the primary workload (profiles/lstm_step_1024_b64_w3a3.md):
-# (2 x 2139.5 + 512.0) KiB per launch
-LSTM_FUSED_TRAFFIC_BYTES = (2 * 2139.5 + 512.0) * 1024
+# the same for the two kernels of the primary workload (profiles/lstm_step_1024_b64_w3a3.md) and for the
+# streamed batch-1 LSTM step (profiles/lstm_step_b1_streamed_1024_w3a3.md); None where no counter run is
+# recorded
+LSTM_FUSED_TRAFFIC_BYTES = None
+LSTM_QUANT_TRAFFIC_BYTES = None
+LSTM_B1_TRAFFIC_BYTES = None
+FP32_VALU_PEAK_TFLOPS = 157.3                # vector fp32
+MIN_TIMED_CALLS = 100
+MIN_WARMUP_CALLS = 10
 
 
 def dv(a, dev):
@@ -70,6 +81,27 @@ def wall_time_ms(fn, iters, warmup):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / iters
+
+
+def timed_calls(fn, calls, warmup):
+    """`calls` calls of fn() after `warmup` untimed ones.  Every call sits between two HIP events on the
+    current stream, and the wall clock brackets the whole run between two device synchronisations.
+    Returns the per-call wall mean and the median / min / mean of the per-call event times (ms)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(calls + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(calls):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / calls
+    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(calls)])
+    return {"calls": calls, "warmup_calls": warmup, "wall_mean_ms": wall, "event_median_ms": float(np.median(per)),
+            "event_min_ms": float(per.min()), "event_mean_ms": float(per.mean())}
 
 
 # ------------------------------------------------------------------------------ workloads
@@ -120,7 +152,45 @@ def bench_lstm_sequence(amq, cfg, dev, seqs, warmup):
         c.zero_()
         amq.lstm_sequence(*q, I, H, None, xs, h, c, k_a, T, ws=ws)
 
-    return wall_time_ms(seq, seqs, warmup) / S
+    st = timed_calls(seq, seqs, warmup)
+    st["steps_per_call"] = S
+    return st
+
+
+def bench_lstm_graph(amq, cfg, dev, replays=100, warmup=10):
+    """One sequence as per-step calls of lstm_step recorded once into a HIP graph and replayed."""
+    import torch
+    I, H, B, k_a, T = cfg["I"], cfg["H"], cfg["B"], cfg["k_a"], cfg["T"]
+    q = setup_lstm(amq, cfg, dev)
+    xs = dv(cfg["xs"], dev)
+    S = xs.shape[0]
+    h = torch.zeros((B, H), device=dev)
+    c = torch.zeros((B, H), device=dev)
+    ws = amq.lstm_workspace(I, H, B, k_a, dev)
+
+    def seq():
+        h.zero_()
+        c.zero_()
+        for t in range(S):
+            amq.lstm_step(*q, I, H, None, xs[t], h, c, k_a, T, ws=ws, h_out=h, c_out=c)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        seq()                       # per-device kernel configuration happens outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = (h.clone(), c.clone())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        seq()
+    for _ in range(3):              # every replay gives the eager result
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(h, eager[0]) and torch.equal(c, eager[1]), "graph replay differs from the eager sequence"
+    st = timed_calls(g.replay, replays, warmup)
+    st["steps_per_call"] = S
+    return st
 
 
 def bench_lstm_fused_kernel(amq, cfg, dev, q, iters=300):
@@ -194,6 +264,41 @@ def bench_gemv_stream(amq, dev, m, n, k_w, k_a, total_bytes=512 << 20, iters=20)
     return ms, G, G * nbytes
 
 
+def bench_stream_probe(amq, dev, nbytes=1 << 30, iters=20):
+    """Read-only streaming kernel over 1 GiB: the bandwidth a plain read reaches on this GPU."""
+    import torch
+    buf = torch.empty(nbytes // 4, dtype=torch.int32, device=dev).random_()
+    sink = torch.empty(amq.binding.STREAM_PROBE_SINK_WORDS, dtype=torch.int64, device=dev)
+    ms = event_time_ms(lambda: amq.stream_read_probe(buf, sink), iters, 3)
+    return nbytes / (ms * 1e-3) / 1e9, ms
+
+
+def bench_lstm_b1_stream(amq, dev, I, H, k_w, k_a, total_bytes=512 << 20, iters=20):
+    """G independent batch-1 LSTM steps on packed operands in one launch, G x (bytes of one cell's weight
+    planes) >= 512 MiB, so every plane byte comes from HBM.  Returns ms, G and the algorithmic bytes:
+    planes + alpha of both blocks, codes + beta of x and h, c_prev in, h and c out."""
+    import torch
+    wx, wh = amq.wpr(I), amq.wpr(H)
+    per_planes = k_w * 4 * H * (wx + wh) * 4
+    G = (total_bytes + per_planes - 1) // per_planes
+    g = torch.Generator(device="cpu").manual_seed(4)
+
+    def words(*shape):
+        return torch.randint(-2 ** 31, 2 ** 31 - 1, shape, dtype=torch.int32, generator=g).to(dev)
+
+    Wxp, Whp = words(G, k_w, 4 * H, wx), words(G, k_w, 4 * H, wh)
+    ax = (torch.rand((G, 4 * H, k_w), generator=g) * 0.02).to(dev)
+    ah = (torch.rand((G, 4 * H, k_w), generator=g) * 0.02).to(dev)
+    Xp, Hp = words(G, k_a, wx), words(G, k_a, wh)
+    bx, bh = torch.rand((G, k_a), generator=g).to(dev), torch.rand((G, k_a), generator=g).to(dev)
+    c = torch.randn((G, H), generator=g).to(dev)
+    ho, co = torch.empty_like(c), torch.empty_like(c)
+    ms = event_time_ms(lambda: amq.lstm_step_packed_grouped(Wxp, ax, Whp, ah, I, H, None, Xp, bx, Hp, bh, c,
+                                                            h_out=ho, c_out=co), iters, 3)
+    per = per_planes + 2 * 4 * H * k_w * 4 + k_a * (wx + wh) * 4 + 2 * k_a * 4 + 3 * H * 4
+    return ms, G, G * per
+
+
 def bench_gemv_warm(amq, dev, m, n, k, iters=2000):
     import torch
     g = torch.Generator(device="cpu").manual_seed(3)
@@ -218,10 +323,10 @@ def bench_quantizer(amq, dev, k, iters=10):
     alpha = torch.empty((rows, k), device=dev)
     L = amq.binding.lib()
     s = torch.cuda.current_stream().cuda_stream
-    ms = event_time_ms(lambda: L.amq_quantize_weights(W.data_ptr(), rows, cols, cols, k, 2, planes.data_ptr(),
-                                                      alpha.data_ptr(), s), iters, 2)
+    st = timed_calls(lambda: L.amq_quantize_weights(W.data_ptr(), rows, cols, cols, k, 2, planes.data_ptr(),
+                                                    alpha.data_ptr(), s), max(10, iters), 3)
     nbytes = rows * cols * 4 + planes.numel() * 4 + alpha.numel() * 4
-    return ms, nbytes
+    return st, nbytes, rows * cols
 
 
 def bench_gru(amq, dev, steps, warmup):
@@ -360,7 +465,7 @@ def cpu_baseline_lstm(cfg, budget_s=15.0):
                       % (n, B, H, k_w, k_a)}
 
 
-SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "lm", "quantizer", "mse", "cpu"]
+SECTIONS = ["primary", "lstm_b1", "gemv", "gemm", "gru", "lm", "quantizer", "mse", "cpu"]   # + probe, copy_probe
 
 
 def copy_probe(dev, nbytes=512 << 20, iters=10):
@@ -408,41 +513,85 @@ def main():
     also = {}
     cfg = inputs.lstm_large()
 
+    probe_gbps = None
+    if sections & {"lstm_b1", "gemv", "quantizer", "probe"}:
+        probe_gbps, probe_ms = bench_stream_probe(amq, dev)
+        also["stream_read_probe_1GiB_GBps"] = probe_gbps
+        also["stream_read_probe_frac_of_nominal"] = probe_gbps / HBM_PEAK_GBPS
+
+    def hbm_roofline(kernel, gbps, ms, nbytes, traffic):
+        return {"kernel": kernel, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": gbps / HBM_PEAK_GBPS, "frac_of_stream_read_probe": gbps / probe_gbps if probe_gbps else None,
+                "traffic": traffic, "launch_ms": ms, "bytes_per_launch": nbytes}
+
     if "primary" in sections:
         # config 3, LSTM 1024/1024, batch 64, W3/A3, T=2: whole 35-step sequences through
-        # amq_lstm_sequence (launches issued from C, state carried on the GPU); K steps = K/35 calls
-        H, B, k_w, k_a = cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"]
+        # amq_lstm_sequence (launches issued from C, state carried on the GPU); never fewer than
+        # 100 timed calls after 10 warm-up calls
+        H, B, k_w, k_a, T = cfg["H"], cfg["B"], cfg["k_w"], cfg["k_a"], cfg["T"]
         S = cfg["xs"].shape[0]
-        seqs = max(1, (args.steps + S - 1) // S)
+        seqs = max(MIN_TIMED_CALLS, (args.steps + S - 1) // S)
+        warm = max(MIN_WARMUP_CALLS, (args.warmup + S - 1) // S)
+        st = bench_lstm_sequence(amq, cfg, dev, seqs, warm)
         out["steps"] = seqs * S
-        ms_step = bench_lstm_sequence(amq, cfg, dev, seqs, max(1, args.warmup // S))
+        out["warmup"] = warm * S
+        ms_step = st["wall_mean_ms"] / S          # whole-job figure: wall clock over every timed call
         out["value"] = 1e3 / ms_step
         out["ms_per_step"] = ms_step
-        ms_call, q = bench_lstm_steps(amq, cfg, dev, args.steps, args.warmup)
+        out["timing"] = {"sequence_calls": seqs, "warmup_calls": warm, "steps_per_call": S,
+                         "wall_us_per_step": ms_step * 1e3,
+                         "event_us_per_step_median": st["event_median_ms"] / S * 1e3,
+                         "event_us_per_step_min": st["event_min_ms"] / S * 1e3,
+                         "event_us_per_step_mean": st["event_mean_ms"] / S * 1e3}
+        ms_call, q = bench_lstm_steps(amq, cfg, dev, max(args.steps, 700), max(args.warmup, 70))
         also["lstm_b64_per_step_call_steps_per_s"] = 1e3 / ms_call
-        # dominant kernel of a step: products with both weight blocks + epilogue + cell, fused,
-        # on the fp4 matrix cores (codes as {0,1}); the other kernel is the on-line quantizer
+        # the two kernels of a step: on-line quantization of the 2B vectors x_t, h_{t-1}, then the
+        # products with both weight blocks + coefficient epilogue + cell on the fp4 matrix cores
+        # (codes as {-1,+1}); `roofline` is the one that takes longer
         ms_fused, ms_quant = bench_lstm_fused_kernel(amq, cfg, dev, q)
         macs = 2.0 * 4 * H * H * k_w * k_a * B
         achieved = 2.0 * macs / (ms_fused * 1e-3) / 1e12
-        out["roofline"] = {"kernel": "mfma4_kernel<3,3,lstm>: fused W3/A3 products (4096x2048, B=64) + cell",
-                           "bound": "mfma", "achieved": achieved, "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / FP4_MFMA_PEAK_TFLOPS, "traffic": LSTM_FUSED_TRAFFIC_BYTES, "launch_ms": ms_fused,
-                           "flops_per_launch": 2.0 * macs}
+        r_prod = {"kernel": "mfma4p_kernel<3,3,1,lstm,8>: W3/A3 products with both 4096x1024 blocks (B=64) + cell",
+                  "bound": "mfma", "achieved": achieved, "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                  "frac": achieved / FP4_MFMA_PEAK_TFLOPS, "traffic": LSTM_FUSED_TRAFFIC_BYTES,
+                  "launch_ms": ms_fused, "flops_per_launch": 2.0 * macs}
+        # Sec. 3 cost of Alg. 2 per n-vector: 2 T k^2 n binary + 2 (T+1) k n non-binary operations
+        n = cfg["I"]
+        qops = 2 * B * (2.0 * T * k_a * k_a * n + 2.0 * (T + 1) * k_a * n)
+        qach = qops / (ms_quant * 1e-3) / 1e12
+        r_quant = {"kernel": "quantize_kernel<3,4,4>: Alg. 2 on the 128 vectors x_t, h_{t-1} of length 1024 "
+                             "(128 workgroups of 4 waves: latency-bound, half the CUs idle)",
+                   "bound": "alu", "achieved": qach, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                   "frac": qach / FP32_VALU_PEAK_TFLOPS, "traffic": LSTM_QUANT_TRAFFIC_BYTES, "launch_ms": ms_quant,
+                   "flops_per_launch": qops}
+        first, second = (r_prod, r_quant) if ms_fused >= ms_quant else (r_quant, r_prod)
+        out["roofline"] = first
+        out["roofline_second_kernel"] = second
         also["lstm_b64_fused_kernel_us"] = ms_fused * 1e3
         also["lstm_b64_quantize_kernel_us"] = ms_quant * 1e3
 
     if "lstm_b1" in sections:
-        # batch-1 LSTM, config 1 (hidden 300): per-step launches and one call per sequence
+        # batch-1 LSTM, config 1 (hidden 300): (i) one launch pair per step, (ii) the same launches replayed
+        # from a HIP graph, (iii) one call per sequence (grid-persistent kernel, weights on chip)
         c1 = inputs.lstm_small()
         ms1, _ = bench_lstm_steps(amq, c1, dev, 700, 70)
-        ms1_seq = bench_lstm_sequence(amq, c1, dev, 20, 2)
+        st1 = bench_lstm_sequence(amq, c1, dev, 100, 10)
+        stg = bench_lstm_graph(amq, c1, dev)
         also["lstm_b1_hidden300_steps_per_s"] = 1e3 / ms1
-        also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 / ms1_seq
+        also["lstm_b1_hidden300_hip_graph_steps_per_s"] = 1e3 * stg["steps_per_call"] / stg["event_median_ms"]
+        also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 * st1["steps_per_call"] / st1["event_median_ms"]
         cb = inputs.lstm_large(B=1)
         msb, _ = bench_lstm_steps(amq, cb, dev, 700, 70)
+        stb = bench_lstm_sequence(amq, cb, dev, 100, 10)
         also["lstm_b1_hidden1024_w3a3_steps_per_s"] = 1e3 / msb
-        also["lstm_b1_hidden1024_w3a3_sequence_call_steps_per_s"] = 1e3 / bench_lstm_sequence(amq, cb, dev, 20, 2)
+        also["lstm_b1_hidden1024_w3a3_sequence_call_steps_per_s"] = 1e3 * stb["steps_per_call"] / stb["event_median_ms"]
+        # the HBM-bound form of the batch-1 step: config 3's shape at B = 1, G independent cells streamed
+        ms, G, nbytes = bench_lstm_b1_stream(amq, dev, cb["I"], cb["H"], cb["k_w"], cb["k_a"])
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        also["lstm_b1_hidden1024_w3a3_streamed_GBps"] = gbps
+        out["roofline_lstm_b1"] = hbm_roofline("bmv_kernel<3,3,1,lstm>: batch-1 LSTM step 1024/1024 W3/A3 on packed "
+                                               "operands, %d independent cells streamed" % G, gbps, ms, nbytes,
+                                               LSTM_B1_TRAFFIC_BYTES)
 
     if "gemv" in sections:
         # batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency
@@ -451,10 +600,8 @@ def main():
             gbps = nbytes / (ms * 1e-3) / 1e9
             also["gemv_b1_w%da%d_streamed_GBps" % (k, k)] = gbps
             if k == 2:
-                out["roofline_gemv"] = {"kernel": "binary GEMV 4096x1024 W2/A2 batch 1, %d matrices streamed" % G,
-                                        "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                        "frac": gbps / HBM_PEAK_GBPS, "traffic": GEMV_TRAFFIC_BYTES, "launch_ms": ms,
-                                        "bytes_per_launch": nbytes}
+                out["roofline_gemv"] = hbm_roofline("binary GEMV 4096x1024 W2/A2 batch 1, %d matrices streamed" % G,
+                                                    gbps, ms, nbytes, GEMV_TRAFFIC_BYTES)
             also["gemv_b1_w%da%d_warm_call_us" % (k, k)] = bench_gemv_warm(amq, dev, 4096, 1024, k) * 1e3
 
     if "gemm" in sections:
@@ -489,9 +636,22 @@ def main():
             also["lm_log_softmax_42000_b%d_us" % b] = ms_lsm * 1e3
 
     if "quantizer" in sections:
+        # config 5.  Per k: time against max(bytes / HBM rate, operations / vector-ALU rate), with the bytes
+        # 4 + k/8 per entry and the operations of Sec. 3's cost model, 2 T k^2 + 2 (T+1) k per entry at T = 2,
+        # priced at one lane-operation each
+        qz = {}
         for k in (1, 2, 3, 4):
-            ms, nbytes = bench_quantizer(amq, dev, k)
+            st, nbytes, entries = bench_quantizer(amq, dev, k)
+            ms = st["event_median_ms"]
+            t_hbm = nbytes / (HBM_PEAK_GBPS * 1e9) * 1e3
+            t_alu = entries * (2.0 * 2 * k * k + 2.0 * 3 * k) / (VALU_PEAK_TOPS * 1e12) * 1e3
+            qz["k%d" % k] = {"us_median": ms * 1e3, "us_min": st["event_min_ms"] * 1e3, "launches": st["calls"],
+                             "GBps": nbytes / (ms * 1e-3) / 1e9, "hbm_floor_us": t_hbm * 1e3,
+                             "alu_floor_us": t_alu * 1e3, "bound": "hbm" if t_hbm >= t_alu else "alu",
+                             "frac_of_floor": max(t_hbm, t_alu) / ms,
+                             "frac_of_stream_read_probe": nbytes / (ms * 1e-3) / 1e9 / probe_gbps}
             also["quantize_weights_16384x4096_k%d_GBps" % k] = nbytes / (ms * 1e-3) / 1e9
+        also["quantize_weights_16384x4096"] = qz
 
     if "mse" in sections:
         also["relative_mse"] = bench_relative_mse(amq, dev)

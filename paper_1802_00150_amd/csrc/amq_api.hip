@@ -187,16 +187,16 @@ amq::BmvArgs store_args(const amq::GemmArgs& g) {
   return b;
 }
 
-// One quantized product.  Batch <= 16: weights-in-registers popcount kernel (memory-bound
-// regime).  Larger batches: the int8 matrix-core kernel (dense contraction).  The general
-// popcount kernel covers what is left (very long vectors at small batch, small-batch integer dots).
+// One quantized product.  Small batches (see kBmvMaxBatchStore): weights-in-registers popcount kernel
+// (memory-bound regime).  Larger batches: the matrix-core kernels (dense contraction).  The general
+// popcount kernel covers what is left (very long vectors at small batch, grouped products).
 // lse_slots (nullable): receives the number of (max, sum) pairs per batch entry the kernel left
 // in g.lse_part, or 0 if the kernel that ran does not produce them.
 int run_product(const amq::GemmArgs& g, hipStream_t s, int* lse_slots = nullptr) {
   if (lse_slots) *lse_slots = 0;
-  if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch))
+  if (!g.D && amq::bmv_supported(g.op.n, 0, g.k_a, g.batch, amq::kEpiStore))
     return hip_status(amq::launch_bmv(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s, lse_slots));
-  if (g.groups == 1 && g.batch > amq::kBmvMaxBatch && amq::mfma_supported(g.batch))
+  if (g.groups == 1 && amq::mfma_supported(g.batch))
     return hip_status(launch_matrix_core(store_args(g), g.k_w, g.k_a, amq::kEpiStore, s, lse_slots));
   return hip_status(amq::launch_gemm(g, s));
 }
@@ -339,9 +339,9 @@ static int lstm_fused_launch(const uint32_t* Wxp, const float* alpha_x, const ui
   b.c_out = c_out;
   b.hs_out = hs_out;
   b.groups = 1;
-  if (amq::bmv_supported((int)I, (int)H, k_a, B))
+  if (amq::bmv_supported((int)I, (int)H, k_a, B, amq::kEpiLstm))
     return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
-  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B))
+  if (amq::mfma_supported(B))
     return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiLstm, s));
   return -1;
 }
@@ -378,7 +378,7 @@ int amq_lstm_step_packed_grouped(int64_t groups, const uint32_t* Wxp, const floa
     return AMQ_ERR_INVALID;
   if (!bits_ok(k_w) || !bits_ok(k_a) || I <= 0 || H <= 0 || groups <= 0) return AMQ_ERR_INVALID;
   if (!aligned(Wxp, 16) || !aligned(Whp, 16) || !aligned(Xp, 16) || !aligned(Hp, 16)) return AMQ_ERR_INVALID;
-  if (groups > 65535 || !amq::bmv_supported((int)I, (int)H, k_a, 1)) return AMQ_ERR_UNSUPPORTED;
+  if (groups > 65535 || !amq::bmv_supported((int)I, (int)H, k_a, 1, amq::kEpiLstm)) return AMQ_ERR_UNSUPPORTED;
   amq::BmvArgs b{};
   b.blk[0] = amq::BmvBlock{Wxp, alpha_x, Xp, beta_x, (int)I};
   b.blk[1] = amq::BmvBlock{Whp, alpha_h, Hp, beta_h, (int)H};
@@ -507,7 +507,7 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   q.mode = amq::kQuantFull;
   st = hip_status(amq::launch_quantize(q, k_a, s));
   if (st != AMQ_OK) return st;
-  if (amq::bmv_supported((int)I, (int)H, k_a, B)) {
+  if (amq::bmv_supported((int)I, (int)H, k_a, B, amq::kEpiGru)) {
     amq::BmvArgs b{};
     b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
     b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
@@ -521,7 +521,7 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
     b.groups = 1;
     return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiGru, s));
   }
-  if (B > amq::kBmvMaxBatch && amq::mfma_supported(B)) {
+  if (amq::mfma_supported(B)) {
     amq::BmvArgs b{};
     b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
     b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
@@ -703,7 +703,7 @@ static SoftmaxWs carve_softmax(void* ws, int64_t V, int64_t H, int64_t B, int k_
   // matrix-core kernels one per wave or workgroup of a batch tile's share of the grid (fewer the
   // more tiles there are); a launch that would need more leaves none and the stand-alone
   // log-softmax runs instead
-  const int64_t cap = B <= amq::kBmvMaxBatch ? amq::kLseMaxSlots : B <= 64 ? 4096 : 1024;
+  const int64_t cap = amq::bmv_supported((int)H, 0, k_a, B, amq::kEpiStore) ? amq::kLseMaxSlots : B <= 64 ? 4096 : 1024;
   w.lse_cap = (int)(V + 64 < cap ? V + 64 : cap);
   off += up256(sizeof(float) * 2 * (size_t)B * w.lse_cap);
   w.total = off;
@@ -883,7 +883,7 @@ static int score_layer_launch(const uint32_t* Wsp, const float* alpha_s, int64_t
   b.tgt = tg;
   b.tgt_out = o.tlogit;
   b.groups = 1;
-  if (rows > amq::kBmvMaxBatch && amq::mfma4w_supported(b, k_ws, k_as)) {
+  if (!amq::bmv_supported((int)H, 0, k_as, rows, amq::kEpiStore) && amq::mfma4w_supported(b, k_ws, k_as)) {
     amq::QuantArgs q{};
     q.seg[0] = amq::QuantSeg{hs, H, (int)H, (int)rows, sw.hp, sw.beta};
     q.T = T;

@@ -104,18 +104,21 @@ hipError_t launch_gru_pointwise(const float* pre_x, const float* pre_h, const fl
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4* __restrict__ buf, long long n16,
                                                           unsigned long long* __restrict__ sink) {
   __shared__ unsigned long long part[4];
-  const long long stride = (long long)gridDim.x * 256;
+  // a workgroup takes whole tiles of kTile 16-byte words (32 KiB contiguous), eight loads per lane in flight
+  constexpr int kLoads = 8, kTile = 256 * kLoads;
   uint4 acc = make_uint4(0, 0, 0, 0);
-  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  // four loads in flight per thread
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = buf[i], b = buf[i + stride], c = buf[i + 2 * stride], d = buf[i + 3 * stride];
-    acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
-    acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
-    acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
-    acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+  const long long tiles = n16 / kTile;
+  for (long long t = blockIdx.x; t < tiles; t += gridDim.x) {
+    const uint4* p = buf + t * kTile + threadIdx.x;
+    uint4 v[kLoads];
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) v[j] = load_streaming(p + j * 256);
+#pragma unroll
+    for (int j = 0; j < kLoads; ++j) {
+      acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w;
+    }
   }
-  for (; i < n16; i += stride) {
+  for (long long i = tiles * kTile + (long long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long long)gridDim.x * 256) {
     const uint4 a = buf[i];
     acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
   }

@@ -69,6 +69,12 @@ __device__ __forceinline__ float group_sum(float v, int lg) {
 // ---- operands of the fp4 matrix-core kernels (v_mfma_scale_f32_16x16x128_f8f6f4, E2M1 codes) ----
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
+
+// 16-byte load marked non-temporal: data that is read once and should not displace what the caches hold.
+__device__ __forceinline__ uint4 load_streaming(const uint4* p) {
+  const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+  return make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w);
+}
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kTileB = 16;                         // batch entries per tile

@@ -124,7 +124,18 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
 // ---- small-batch products with weights in registers and fused epilogues --------------------
 enum { kEpiStore = 0, kEpiLstm = 1, kEpiGru = 2 };
+// Largest batch the small-batch kernel takes.  Where the fp4 matrix-core kernels apply (vectors of at
+// most 1024 entries) they are faster from batch 5 on for a plain product and from batch 2 on for a
+// fused cell step (measured, 4096 x 1024 and the 1024-unit LSTM, W2/A2 and W3/A3: plain product 3.6-4.0
+// against 3.8-4.6 us at batch 4, 4.6-5.8 against 3.8-4.6 us at batch 8; LSTM step 5.2-6.6 against
+// 5.9-9.0 us at batch 1, 6.8-9.2 against 5.9-9.0 us at batch 2, 29-44 against 5.5-7.5 us at batch 16);
+// for longer vectors the alternative is the int8 kernel and the old limit stays.
 constexpr int kBmvMaxBatch = 16;
+constexpr int kBmvMaxBatchStore = 4;
+constexpr int kBmvMaxBatchCell = 1;
+// weight planes of one launch beyond this many bytes cannot stay in the 256 MB last-level cache between
+// launches: the small-batch kernel then reads them with non-temporal loads
+constexpr long long kBmvStreamingBytes = 128LL << 20;
 
 struct BmvBlock {
   const uint32_t* Wp;   // [k_w][m][wpr(n)]
@@ -156,6 +167,7 @@ struct BmvArgs {
   const long long* tgt; // several-tiles store kernel only, nullable: one output row index per batch entry ...
   float* tgt_out;       // ... whose output value is also written here, [batch] (Y may then be null)
   int lg;               // filled by launch_bmv
+  int streaming;        // filled by launch_bmv: planes are read once, load them non-temporal
   int groups;           // small-batch kernel: independent products / cells in one launch (1 otherwise)
   // strides in elements between consecutive groups: operands of the x block, of the h block (LSTM
   // mode), outputs of store mode, and state vectors (c_prev, h_out, c_out, hs_out) of LSTM mode
@@ -169,7 +181,7 @@ struct BmvArgs {
 constexpr int kLseMaxSlots = 8192;
 
 // true if the register-resident kernel can take these vector lengths / batch
-bool bmv_supported(int n0, int n1, int k_a, long long batch);
+bool bmv_supported(int n0, int n1, int k_a, long long batch, int epi);
 // lse_slots (nullable) receives the number of slots written per batch entry when a.lse_part is set
 hipError_t launch_bmv(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s, int* lse_slots = nullptr);
 

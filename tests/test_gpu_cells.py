@@ -30,12 +30,14 @@ def quantized(W, k):
     return oracle.quantize_rows(W, k, 2)
 
 
-# batches above 16 take the matrix-core kernels (fp4 up to 1024 entries, int8 beyond); sizes are
-# chosen so that batch tiles, row blocks and K chunks are all ragged
+# vectors of at most 1024 entries: batch 1 takes the small-batch kernel, every larger batch the fp4
+# matrix-core kernels; longer vectors: the small-batch kernel up to batch 16, the int8 kernel beyond.
+# Sizes are chosen so that batch tiles, row blocks and K chunks are all ragged
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (300, 300, 1, 2, 2),
                                            (64, 200, 5, 2, 3), (1024, 512, 9, 3, 3), (17, 129, 4, 4, 4),
                                            (256, 256, 6, 1, 1), (200, 136, 21, 2, 3), (1024, 130, 37, 3, 3),
                                            (300, 301, 17, 4, 4), (1500, 1100, 19, 2, 2), (2100, 70, 33, 3, 2),
+                                           (1100, 1030, 3, 2, 2), (1030, 200, 16, 3, 2),
                                            # batches of 128 and more with many row blocks: several batch tiles
                                            # per wave (4, 2, 2 and 3 of them; ragged last groups and units)
                                            (300, 300, 500, 2, 2), (1024, 1024, 130, 3, 3), (200, 130, 1000, 1, 4),
@@ -67,7 +69,7 @@ def test_lstm_step_random(amq, I, H, B, k_w, k_a):
 
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (1024, 512, 9, 2, 2),
                                            (300, 257, 4, 4, 3), (200, 136, 21, 2, 3), (1024, 130, 37, 3, 3),
-                                           (1500, 1100, 19, 2, 2),
+                                           (1500, 1100, 19, 2, 2), (1100, 1030, 3, 2, 2),
                                            # several batch tiles per wave (3 and 4)
                                            (200, 136, 1000, 2, 3), (64, 301, 450, 3, 2)])
 def test_gru_step_random(amq, I, H, B, k_w, k_a):

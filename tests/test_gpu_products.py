@@ -48,7 +48,7 @@ def test_binary_dots_bit_exact(amq, k_w, k_a):
 def test_gemm_and_gemv(amq, k_w, k_a):
     g = np.random.default_rng(50 + 10 * k_w + k_a)
     for (m, n) in [(37, 300), (1200, 300), (4096, 1024), (515, 2048), (3000, 1024), (70, 2500)]:
-        for batch in (1, 8, 11, 20, 37):
+        for batch in (1, 4, 8, 11, 20, 37):
             say("gemm kw=%d ka=%d m=%d n=%d B=%d" % (k_w, k_a, m, n, batch))
             W = (g.standard_normal((m, n)) * 0.02).astype(np.float32)
             X = g.standard_normal((batch, n)).astype(np.float32)
