@@ -160,7 +160,7 @@ int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32
  * [k_a][B][wpr(I)] with beta_x [B][k_a] (Sec. 4: with one-hot inputs x_t is a row of the
  * quantized embedding matrix, so it arrives already quantized), h_{t-1} as Hp / beta_h.
  * Products, coefficient epilogue and cell only; no workspace.  Returns AMQ_ERR_UNSUPPORTED for
- * B <= 16 with I or H above 8192 (that shape needs the workspace path of amq_lstm_step).
+ * I or H above AMQ_MAX_QUANT_N.
  */
 int amq_lstm_step_packed(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                          const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
@@ -201,15 +201,28 @@ int amq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* strea
  * launch that occupies the whole chip (pieces of 64 steps), the workgroups exchanging
  * h_t through the workspace.  That launch needs all its workgroups resident at once:
  * do not run it concurrently with other work that keeps compute units busy.  Its waits
- * are bounded; if one gives up, h and c are left as they were, hs is incomplete, and
- * the 32-bit word at byte amq_lstm_sequence_flag_offset(...) of the workspace is
- * non-zero (it is zero after a completed call; SIZE_MAX: this shape has no such word).
+ * are bounded.  If one gives up, the return value is still AMQ_OK (the launches were
+ * issued; the outcome is only known on the device): h and c hold the state after the
+ * last 64-step piece that completed (the initial state if none did), the rows of hs
+ * from the piece that gave up onwards hold NaN, and the 32-bit word
+ * at byte amq_lstm_sequence_flag_offset(...) of the workspace is non-zero.  A caller
+ * that needs to know reads that word after synchronising the stream (it is zero after a
+ * completed call; SIZE_MAX: this shape has no such word).
  */
 size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a);
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                       const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
                       const float* xs, int64_t steps, float* h, float* c, int64_t B, int k_a, int T,
                       float* hs, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Test hook for the give-up path above: the number of polls after which a wait of the
+ * one-launch recurrence gives up, for launches issued from now on (process-wide; 0
+ * restores the default of 2^19).  With 1 the first wait that is not satisfied at once
+ * gives up, every workgroup leaves, and the documented failure state results without
+ * any kernel hanging.
+ */
+void amq_debug_set_sequence_spin_limit(unsigned polls);
 
 /*
  * One quantized GRU step.  The paper evaluates GRUs (Tables 2-5) without
@@ -352,7 +365,8 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
  * arithmetic as `steps` calls of amq_lm_step.  For B = 1 (with E, H <= 1024 and 2- or 3-bit codes)
  * the recurrence runs in one launch per 64 steps (see amq_lstm_sequence, including its residency
  * requirement and its flag word: amq_lstm_sequence_flag_offset(E, H, 1, k_a) applies to this
- * workspace too) and the output layer then takes all h_t of those steps as one batch.  For larger
+ * workspace too; AMQ_OK does not cover a give-up, after which the log-probabilities from the piece
+ * that gave up onwards are NaN) and the output layer then takes all h_t of those steps as one batch.  For larger
  * B the recurrent halves of the steps run one after the other and the output layer takes the
  * hidden states of about 4096 / B steps at a time (the inputs are given, so only the recurrence
  * is serial); the workspace holds those hidden states.

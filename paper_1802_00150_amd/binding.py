@@ -21,7 +21,7 @@ EXPORTS = [
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed",
     "amq_lstm_step_packed_grouped", "amq_stream_read_probe", "amq_lstm_sequence",
-    "amq_lstm_sequence_flag_offset",
+    "amq_lstm_sequence_flag_offset", "amq_debug_set_sequence_spin_limit",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
@@ -63,6 +63,8 @@ def lib():
         L.amq_gru_workspace_bytes.argtypes, L.amq_gru_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
         L.amq_lstm_sequence_flag_offset.argtypes = [_i64, _i64, _i64, _int]
         L.amq_lstm_sequence_flag_offset.restype = _sz
+        L.amq_debug_set_sequence_spin_limit.argtypes = [C.c_uint]
+        L.amq_debug_set_sequence_spin_limit.restype = None
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
                                     _p, _sz, _p]
         L.amq_lstm_step_static.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
@@ -363,6 +365,11 @@ def gru_step_reset_before(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h
                                            _dev(h_prev, torch.float32), B, k_a, T, _dev(h_out, torch.float32),
                                            _opt(g_out), ws.data_ptr(), ws.numel(), _stream()))
     return h_out
+
+
+def debug_set_sequence_spin_limit(polls):
+    """Test hook: polls before a wait of the one-launch recurrence gives up (0 restores the default)."""
+    lib().amq_debug_set_sequence_spin_limit(int(polls))
 
 
 def lstm_sequence_abandoned(ws, I, H, B, k_a):

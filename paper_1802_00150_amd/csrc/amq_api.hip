@@ -459,6 +459,8 @@ size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a) {
   return carve(nullptr, I, H, B, k_a, 4, 1).sync_off;
 }
 
+void amq_debug_set_sequence_spin_limit(unsigned polls) { amq::set_seqg_spin_limit(polls); }
+
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
                       int64_t I, int64_t H, int k_w, const float* bias, const float* xs, int64_t steps,
                       float* h, float* c, int64_t B, int k_a, int T, float* hs, void* workspace,
@@ -475,9 +477,14 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
     for (int64_t t0 = 0; t0 < steps; t0 += amq::kSeqGMaxSteps) {
       const int n = (int)(steps - t0 < amq::kSeqGMaxSteps ? steps - t0 : amq::kSeqGMaxSteps);
       amq::SeqGArgs q{Wxp, alpha_x, Whp, alpha_h, (int)I, (int)H, bias, xs + t0 * I, n, h, c,
-                      hs ? hs + t0 * H : nullptr, T, 0, w.sync, w.hbuf, w.xq, w.xbeta};
+                      hs ? hs + t0 * H : nullptr, T, 0, w.sync, w.hbuf, w.xq, w.xbeta, t0 == 0, 0};
       st = hip_status(amq::launch_lstm_seqg(q, k_w, k_a, static_cast<hipStream_t>(stream)));
       if (st != AMQ_OK) return st;
+      // a launch that gave up (or found the flag of an earlier one) leaves its rows of hs as NaN
+      if (hs) {
+        st = hip_status(amq::launch_seqg_poison(w.sync, hs + t0 * H, (long long)n * H, static_cast<hipStream_t>(stream)));
+        if (st != AMQ_OK) return st;
+      }
     }
     return AMQ_OK;
   }
@@ -968,10 +975,15 @@ static int lm_sequence_impl(const uint32_t* Ep, const float* alpha_e, int64_t vo
       st = hip_status(amq::launch_quantize(q, k_a, s));
       if (st != AMQ_OK) return st;
       amq::SeqGArgs g{Wxp, alpha_x, Whp, alpha_h, (int)E, (int)H, bias, nullptr, n, h, c, lw.hs, T, 0, w.sync, w.hbuf,
-                      w.xq, w.xbeta};
+                      w.xq, w.xbeta, t0 == 0, 0};
       st = hip_status(amq::launch_lstm_seqg(g, k_w, k_a, s));
       if (st != AMQ_OK) return st;
       st = output_layer(t0, n);
+      if (st != AMQ_OK) return st;
+      // the output layer has just read hidden states that are incomplete if the recurrence gave up (now
+      // or in an earlier piece of this call): its results for these steps become NaN
+      st = hip_status(o.logprob ? amq::launch_seqg_poison(w.sync, o.logprob + t0 * V, (long long)n * V, s)
+                                : amq::launch_seqg_poison(w.sync, o.target_logprob + t0, n, s));
       if (st != AMQ_OK) return st;
     }
     return AMQ_OK;

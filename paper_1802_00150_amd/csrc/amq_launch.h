@@ -218,7 +218,7 @@ hipError_t launch_gather_columns(const float* logprob, long long B, long long V,
                                  hipStream_t s);
 
 // ---- whole batch-1 LSTM sequences in one launch spread over the chip (weights resident in
-// registers, one grid barrier per time step) ------------------------------------------------
+// registers; the workgroups exchange h_t as tagged entries, one grid barrier per launch) ------
 constexpr int kSeqGMaxGrid = 256;   // workgroups: one per compute unit, all resident at once
 constexpr int kSeqGMaxSteps = 64;   // time steps per launch (size of the table of input codes)
 struct SeqGArgs {
@@ -240,9 +240,18 @@ struct SeqGArgs {
   unsigned long long* hbuf;  // [2][H]: h_t as published by the grid, {value, step tag} pairs, double-buffered
   uint32_t* xq;         // [k_a][steps][wpr(I)]: codes of the inputs (operand layout)
   float* xbeta;         // [steps][k_a]: their coefficients
+  int first_piece;      // non-zero: also clear the give-up flag (once per API call; a later piece of the
+                        // same call must see a flag an earlier piece raised)
+  unsigned spin_limit;  // filled by launch_lstm_seqg: polls of a wait before it gives up
 };
 bool lstm_seqg_supported(long long I, long long H, long long B, int k_w, int k_a);
 hipError_t launch_lstm_seqg(SeqGArgs a, int k_w, int k_a, hipStream_t s);
+// Polls before a wait of the sequence kernel gives up (0 restores the default).  Tests of the failure
+// path set it to 1, which makes the first wait that is not satisfied at once give up.
+void set_seqg_spin_limit(unsigned polls);
+// After a launch of the sequence kernel and whatever consumed its hs: if the give-up flag is set,
+// overwrite out[0 .. count) with NaN (results computed from an incomplete recurrence must not look valid).
+hipError_t launch_seqg_poison(const unsigned* sync, float* out, long long count, hipStream_t s);
 
 // ---- bandwidth yardstick ------------------------------------------------------------------
 // Reads `bytes` (a multiple of 16) once with 16-byte loads over kStreamReadBlocks workgroups and leaves

@@ -12,13 +12,19 @@
 //   - the inputs x_t do not depend on the recurrence: workgroup g quantizes x_t for t = g, g + G,
 //     ... ahead of the loop into a small global table (one grid barrier closes that phase);
 //   - per step every workgroup reads h_{t-1} (a few KB), quantizes it itself (4 waves, the shared
-//     quantizer core; redundant across workgroups, but it saves a second grid barrier), forms
-//     the pre-activations of its units (xor + popcount, coefficients per lane, DPP sum over the
-//     lanes of a unit's gate), applies the cell, publishes its entries of h_t, and meets the
-//     others at a grid barrier (one atomic counter, release / acquire fences at device scope).
-// The grid barrier spins a bounded number of times; if it ever gives up (the grid was not
-// resident as a whole) it raises a flag in the workspace, every workgroup leaves, and the state
-// outputs are not written.
+//     quantizer core; redundant across workgroups, but it saves a second exchange), forms the
+//     pre-activations of its units (xor + popcount, coefficients per lane, DPP sum over the lanes of a
+//     unit's gate), applies the cell and publishes its entries of h_t as 8-byte {value, step tag}
+//     pairs, each written with one 64-bit device-scope store.  The readers poll the entries they need
+//     until all carry the tag of the step: the data is its own arrival signal, so the steps need no
+//     barrier and no ordering between separate locations.
+// Every wait spins a bounded number of times; if one gives up (the grid was not resident as a whole)
+// it raises a flag in the workspace, every workgroup leaves, the state outputs h and c are not
+// written and hs is incomplete.  The flag is cleared once per API call, not per launch: the later
+// launches of a longer sequence see it and leave at once, and launch_seqg_poison turns whatever was
+// derived from hs into NaN.
+#include <atomic>
+
 #include "amq_launch.h"
 #include "amq_quantize_core.h"
 
@@ -28,7 +34,8 @@ namespace {
 
 constexpr int kGWaves = 4;
 constexpr int kGNJ = 4;                      // vectors of at most 1024 entries: 16 slots over 4 waves
-constexpr unsigned kSpinLimit = 1u << 19;    // polls of the barrier counter before giving up
+constexpr unsigned kSpinLimit = 1u << 19;    // polls of a wait before giving up
+std::atomic<unsigned> g_spin_limit{kSpinLimit};
 
 // Device-scope accesses to the data the workgroups exchange (see grid_barrier).
 __device__ __forceinline__ void put_f(float* p, float v) {
@@ -52,11 +59,13 @@ __device__ __forceinline__ uint32_t get_u(const uint32_t* p) {
 // workgroup the pollers saturated the one memory channel that holds the words).  Workgroups
 // are never more than one epoch apart, so a byte equal to the epoch or one above it counts as
 // arrived.  Returns false if the barrier was abandoned.
-__device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch) {
-  // Everything the workgroups exchange is written and read with device-scope atomic accesses,
-  // which go through to the point of coherence on their own; a device-scope fence here would
-  // write back and invalidate the whole L2 at every step (measured: ~40 us per barrier).  It is
-  // enough that this thread's exchange stores have completed before the arrival byte is written.
+__device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch, unsigned limit) {
+  // Used once per launch (after the inputs have been quantized).  What the workgroups exchange is
+  // written and read with device-scope atomic accesses, which go through to the point of coherence
+  // on their own.  Ordering: every thread waits for its own exchange stores, the workgroup barrier
+  // collects them, and lane 0's arrival store is a release at device scope; the pollers end with an
+  // acquire fence at device scope.  (Per step this pair would cost a write-back and an invalidate of
+  // the L2 each time, ~40 us measured, which is why the steps exchange self-tagged entries instead.)
   __builtin_amdgcn_s_waitcnt(0);
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
@@ -66,7 +75,7 @@ __device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch) {
     const int G = gridDim.x;
     unsigned char* arrive = reinterpret_cast<unsigned char*>(sync + 1);
     if (lane == 0)
-      __hip_atomic_store(arrive + blockIdx.x, (unsigned char)epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(arrive + blockIdx.x, (unsigned char)epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     // this lane watches workgroups 4 * lane .. 4 * lane + 3
     unsigned watch = 0;  // byte mask of the workgroups that exist
 #pragma unroll
@@ -85,7 +94,7 @@ __device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch) {
       }
       if (__all(here)) break;
       ++spins;
-      if (spins > kSpinLimit) {
+      if (spins > limit) {
         if (lane == 0) __hip_atomic_store(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ok = 0;
         break;
@@ -96,6 +105,7 @@ __device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch) {
       }
       __builtin_amdgcn_s_sleep(1);
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   }
   ok = __syncthreads_and(ok);
   return ok != 0;
@@ -109,8 +119,9 @@ __device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned epoch) {
 // the expected tag, so the data itself is the synchronisation: no arrival flags and no separate
 // round trip between "everything is there" and "read it".  Returns false if the wait was given up.
 template <int KA, bool SHARED>
-__device__ __forceinline__ bool quantize_wg(const void* src_v, unsigned tag, unsigned* sync, int n, int T,
-                                            uint32_t* planes, float* coef, double (*sh)[16 * kMaxRed], int& phase) {
+__device__ __forceinline__ bool quantize_wg(const void* src_v, unsigned tag, unsigned* sync, unsigned limit, int n,
+                                            int T, uint32_t* planes, float* coef, double (*sh)[16 * kMaxRed],
+                                            int& phase) {
   const int lane = lane_id(), wv = wave_id();
   const int wpr = 4 * ((n + 127) >> 7);
   const int nslots = wpr >> 1;
@@ -135,7 +146,7 @@ __device__ __forceinline__ bool quantize_wg(const void* src_v, unsigned tag, uns
       }
       if (__all(ready)) break;
       ++spins;
-      if (spins > kSpinLimit) {
+      if (spins > limit) {
         __hip_atomic_store(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         ok = 0;
         break;
@@ -172,11 +183,20 @@ __device__ __forceinline__ bool quantize_wg(const void* src_v, unsigned tag, uns
   return true;
 }
 
-// Clears the barrier words and the tags of the published state before a launch.
-__global__ void seqg_reset_kernel(unsigned* sync, unsigned long long* hbuf, int H) {
+// Before a launch: clears the arrival bytes and the tags of the published state; the give-up flag only
+// for the first launch of an API call.
+__global__ void seqg_reset_kernel(unsigned* sync, unsigned long long* hbuf, int H, int clear_flag) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
-  for (int i = t; i < 1 + kSeqGMaxGrid / 4; i += nt) sync[i] = 0u;
+  if (t == 0 && clear_flag) sync[0] = 0u;
+  for (int i = 1 + t; i < 1 + kSeqGMaxGrid / 4; i += nt) sync[i] = 0u;
   for (int i = t; i < 2 * H; i += nt) hbuf[i] = 0ull;
+}
+
+__global__ void seqg_poison_kernel(const unsigned* sync, float* out, long long count) {
+  if (*sync == 0u) return;
+  const long long nt = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += nt)
+    out[i] = __builtin_nanf("");
 }
 
 template <int KW, int KA>
@@ -203,6 +223,13 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
   const int nlen = blk ? H : I;
   const bool cok = uok && c < cpr;
   int phase = 0;
+  // an earlier launch of the same call gave up: nothing this launch could compute would be valid
+  // (one thread reads the flag, so that the whole workgroup takes the same decision)
+  __shared__ unsigned gave_up;
+  if (threadIdx.x == 0) gave_up = get_u(a.sync);
+  __syncthreads();
+  if (gave_up != 0u) return;
+  const unsigned limit = a.spin_limit;
 
   // ---- once: this lane's plane chunks and coefficients, the cell lane's bias and state
   uint4 wq[KW];
@@ -232,14 +259,14 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
   // (with a.xs null the table has been filled by an earlier launch: the embedding lookup of a
   // language model, whose inputs arrive already quantized)
   for (int t = blockIdx.x; a.xs && t < a.steps; t += gridDim.x) {
-    quantize_wg<KA, false>(a.xs + (long long)t * I, 0, a.sync, I, a.T, xq, bx, sh, phase);
+    quantize_wg<KA, false>(a.xs + (long long)t * I, 0, a.sync, limit, I, a.T, xq, bx, sh, phase);
     __syncthreads();
     for (int i = tid; i < KA * wprI; i += 64 * kGWaves)
       put_u(a.xq + ((long long)(i / wprI) * a.steps + t) * wprI + i % wprI, xq[i]);
     if (tid < KA) put_f(a.xbeta + t * KA + tid, bx[tid]);
     __syncthreads();
   }
-  bool alive = a.xs ? grid_barrier(a.sync, 1) : true;
+  bool alive = a.xs ? grid_barrier(a.sync, 1, limit) : true;
 
   // codes of x_0 (KA * wpr(I) <= 128 words: one per thread); those of x_{t+1} are requested while
   // the grid is still working on step t
@@ -253,8 +280,8 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
     if (tid < KA * wprI) xq[tid] = xnext;
     if (tid < KA) bx[tid] = bxnext;
     // h_{t-1}: the caller's state at the first step, afterwards what the grid published (tag t)
-    if (t == 0) alive = quantize_wg<KA, false>(a.h, 0, a.sync, H, a.T, hq, bh, sh, phase);
-    else alive = quantize_wg<KA, true>(a.hbuf + ((t - 1) & 1) * H, (unsigned)t, a.sync, H, a.T, hq, bh, sh, phase);
+    if (t == 0) alive = quantize_wg<KA, false>(a.h, 0, a.sync, limit, H, a.T, hq, bh, sh, phase);
+    else alive = quantize_wg<KA, true>(a.hbuf + ((t - 1) & 1) * H, (unsigned)t, a.sync, limit, H, a.T, hq, bh, sh, phase);
     if (!alive) break;
     __syncthreads();
 
@@ -315,7 +342,7 @@ __global__ __launch_bounds__(64 * kGWaves) void lstm_seqg_kernel(SeqGArgs a) {
 
 template <int KW, int KA>
 hipError_t launch_kk(const SeqGArgs& a, int grid, hipStream_t s) {
-  hipLaunchKernelGGL(seqg_reset_kernel, dim3(8), dim3(256), 0, s, a.sync, a.hbuf, a.H);
+  hipLaunchKernelGGL(seqg_reset_kernel, dim3(8), dim3(256), 0, s, a.sync, a.hbuf, a.H, a.first_piece);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((lstm_seqg_kernel<KW, KA>), dim3(grid), dim3(64 * kGWaves), 0, s, a);
@@ -341,8 +368,19 @@ bool lstm_seqg_supported(long long I, long long H, long long B, int k_w, int k_a
   return (H + units_per_wg - 1) / units_per_wg <= kSeqGMaxGrid;
 }
 
+void set_seqg_spin_limit(unsigned polls) { g_spin_limit.store(polls ? polls : kSpinLimit); }
+
+hipError_t launch_seqg_poison(const unsigned* sync, float* out, long long count, hipStream_t s) {
+  if (!out || count <= 0) return hipSuccess;
+  const long long blocks = (count + 255) / 256;
+  hipLaunchKernelGGL(seqg_poison_kernel, dim3((unsigned)(blocks < 1024 ? blocks : 1024)), dim3(256), 0, s, sync, out,
+                     count);
+  return hipGetLastError();
+}
+
 hipError_t launch_lstm_seqg(SeqGArgs a, int k_w, int k_a, hipStream_t s) {
   a.lg = seqg_lg(a.I, a.H);
+  a.spin_limit = g_spin_limit.load();
   const int units_per_wg = kGWaves * (8 >> a.lg);
   const int grid = (a.H + units_per_wg - 1) / units_per_wg;
   if (grid > kSeqGMaxGrid || a.steps > kSeqGMaxSteps) return hipErrorInvalidValue;

@@ -75,7 +75,7 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_lstm_sequence(p, p, p, p, 8, 8, 2, None, p, 0, p, p, 1, 2, 2, None, ws, need, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
-    assert L.amq_lstm_step_packed(p, p, p, p, 16000, 16000, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
+    assert L.amq_lstm_step_packed(p, p, p, p, 16385, 16, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
     assert L.amq_lstm_step_packed_grouped(3, p, p, p, p, 8, 8, 2, None, p, p, p, p, null, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed_grouped(0, p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed_grouped(70000, p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 2, p, p, None) == UNSUPPORTED

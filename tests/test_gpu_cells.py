@@ -37,7 +37,7 @@ def quantized(W, k):
                                            (64, 200, 5, 2, 3), (1024, 512, 9, 3, 3), (17, 129, 4, 4, 4),
                                            (256, 256, 6, 1, 1), (200, 136, 21, 2, 3), (1024, 130, 37, 3, 3),
                                            (300, 301, 17, 4, 4), (1500, 1100, 19, 2, 2), (2100, 70, 33, 3, 2),
-                                           (1100, 1030, 3, 2, 2), (1030, 200, 16, 3, 2),
+                                           (1100, 1030, 3, 2, 2), (1030, 200, 16, 3, 2), (9000, 40, 3, 2, 2),
                                            # batches of 128 and more with many row blocks: several batch tiles
                                            # per wave (4, 2, 2 and 3 of them; ragged last groups and units)
                                            (300, 300, 500, 2, 2), (1024, 1024, 130, 3, 3), (200, 130, 1000, 1, 4),
@@ -269,6 +269,53 @@ def test_lstm_sequence_batch1_single_launch(amq, I, H, k_w, k_a, steps):
         assert_vec_close(hs_g[t], hs_ref[t], "h_%d" % t)
     assert_vec_close(host(dh), h, "h final")
     assert_vec_close(host(dc), c, "c final")
+
+
+def test_lstm_sequence_give_up_leaves_the_documented_state(amq):
+    # The waits of the one-launch recurrence are bounded.  The test hook makes every wait give up at its
+    # second poll, so the failure path runs with every kernel still ending normally: 150 steps are three
+    # launches; the first one that gives up raises the flag, the later ones leave at entry, the rows of hs
+    # from that piece on are NaN, and h / c hold the state after the last completed piece.
+    import torch
+    I, H, k_w, k_a, steps, piece = 300, 300, 2, 2, 150, 64
+    g = np.random.default_rng(4242)
+    Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((4 * H, H)) * 0.08).astype(np.float32)
+    xs = g.standard_normal((steps, 1, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((1, H))).astype(np.float32)
+    c0 = g.standard_normal((1, H)).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    states = [(h0, c0)]
+    h, c = h0.copy(), c0.copy()
+    for t in range(steps):
+        h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, None, xs[t], h, c, k_a, 2)
+        states.append((h.copy(), c.copy()))
+    d = [to_dev(t) for t in (Wxp, ax, Whp, ah)]
+    dh, dc = to_dev(h0), to_dev(c0)
+    hs = torch.zeros((steps, 1, H), dtype=torch.float32, device=dh.device)
+    ws = amq.lstm_workspace(I, H, 1, k_a, dh.device)
+    say("sequence with waits that give up at once")
+    amq.binding.debug_set_sequence_spin_limit(1)
+    try:
+        amq.lstm_sequence(*d, I, H, None, to_dev(xs), dh, dc, k_a, 2, ws=ws, hs=hs)
+        torch.cuda.synchronize()
+    finally:
+        amq.binding.debug_set_sequence_spin_limit(0)
+    assert amq.lstm_sequence_abandoned(ws, I, H, 1, k_a)
+    bad = np.isnan(host(hs)).all(axis=(1, 2))
+    first = int(np.argmax(bad))
+    say("gave up in the piece that starts at step %d" % first)
+    assert bad.any() and first % piece == 0 and bad[first:].all() and not np.isnan(host(hs)[:first]).any()
+    assert_vec_close(host(dh), states[first][0], "h after the last completed piece")
+    assert_vec_close(host(dc), states[first][1], "c after the last completed piece")
+    # the next call clears the flag and completes
+    dh, dc = to_dev(h0), to_dev(c0)
+    amq.lstm_sequence(*d, I, H, None, to_dev(xs), dh, dc, k_a, 2, ws=ws, hs=hs)
+    assert not amq.lstm_sequence_abandoned(ws, I, H, 1, k_a)
+    assert_vec_close(host(dh), states[steps][0], "h final")
+    assert_vec_close(host(dc), states[steps][1], "c final")
+    assert_vec_close(host(hs)[steps - 1], states[steps][0], "last row of hs")
 
 
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(40, 24, 3, 2, 2), (130, 33, 2, 3, 3), (1024, 512, 9, 2, 2),

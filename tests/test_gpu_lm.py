@@ -201,6 +201,46 @@ def test_lm_sequence(amq, E, H, V, B, k, k_ws, k_as, steps):
     assert_vec_close(host(dc), c, "c final")
 
 
+def test_lm_sequence_give_up_turns_log_probabilities_into_nan(amq):
+    # Same failure path as in the plain LSTM sequence (waits that give up at their second poll, through the
+    # test hook): the output layer must not present log-probabilities computed from an incomplete recurrence.
+    import torch
+    E, H, V, B, k, k_ws, k_as, steps, piece = 128, 256, 1000, 1, 3, 3, 3, 70, 64
+    cfg = inputs.language_model(trial=777, steps=steps, B=B, H=H, E=E, vocab=V, k=k)
+    q = lm_setup(cfg, k_ws)
+    dq = {n: to_dev(q[n]) for n in ("Ep", "ae", "Wxp", "ax", "Whp", "ah", "Wsp", "as", "bias", "bs")}
+    ids = torch.from_numpy(np.ascontiguousarray(cfg["ids"])).to("cuda:0")
+    dh = torch.zeros((B, H), device="cuda:0")
+    dc = torch.zeros((B, H), device="cuda:0")
+    out = torch.zeros((steps, B, V), device="cuda:0")
+    ws = torch.empty(int(amq.binding.lib().amq_lm_sequence_workspace_bytes(E, H, V, B, k, k_as)), dtype=torch.uint8,
+                     device="cuda:0")
+    say("lm sequence with waits that give up at once")
+    amq.binding.debug_set_sequence_spin_limit(1)
+    try:
+        amq.lm_sequence(dq["Ep"], dq["ae"], E, dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], H, dq["bias"], dq["Wsp"],
+                        dq["as"], dq["bs"], ids, dh, dc, k, k_as, 2, ws=ws, logprob=out)
+        torch.cuda.synchronize()
+    finally:
+        amq.binding.debug_set_sequence_spin_limit(0)
+    assert amq.lstm_sequence_abandoned(ws, E, H, 1, k)
+    bad = np.isnan(host(out)).all(axis=(1, 2))
+    first = int(np.argmax(bad))
+    assert bad.any() and first % piece == 0 and bad[first:].all() and not np.isnan(host(out)[:first]).any()
+    # and the same call without the hook completes, with the flag cleared
+    dh.zero_()
+    dc.zero_()
+    amq.lm_sequence(dq["Ep"], dq["ae"], E, dq["Wxp"], dq["ax"], dq["Whp"], dq["ah"], H, dq["bias"], dq["Wsp"],
+                    dq["as"], dq["bs"], ids, dh, dc, k, k_as, 2, ws=ws, logprob=out)
+    assert not amq.lstm_sequence_abandoned(ws, E, H, 1, k)
+    assert not np.isnan(host(out)).any()
+    h = np.zeros((B, H), np.float32)
+    c = np.zeros((B, H), np.float32)
+    for t in range(steps):
+        h, c, lp = lm_oracle_step(q, cfg["ids"][t], h, c, k_as)
+    assert_vec_close(host(out)[steps - 1], lp, "logprob of the last step")
+
+
 @pytest.mark.parametrize("E,H,V,B,k,k_ws,k_as,steps", [
     (300, 300, 10000, 1, 2, 2, 3, 5),         # batch 1, few rows: 64 rows at a time through the ordinary layer
     (128, 256, 1000, 1, 3, 3, 3, 70),         # two pieces of the batch-1 recurrence
