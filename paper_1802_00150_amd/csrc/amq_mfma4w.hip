@@ -11,6 +11,8 @@
 // everything on the weight side (loads, expansion, popcounts, row coefficients) is paid once per
 // NBT tiles and only the per-output epilogue grows with the tile count.  A workgroup of 8 waves
 // stages NBT * 16 batch entries (all planes) in LDS once and its waves walk over row blocks.
+#include <type_traits>
+
 #include "amq_device.h"
 #include "amq_launch.h"
 
@@ -519,20 +521,29 @@ __global__ __launch_bounds__(64 * NWV) void mfma4wc_kernel(BmvArgs a, int rb_per
 // wave issues from start to end, so this form cuts the per-wave path down:
 //   * a wave takes ONE operand block (the x block and the h block of a row block go to two paired
 //     waves; the h-side sums cross through LDS) and NBT batch tiles per set of weight words;
-//   * no staging: the packed activation words of a batch column and k-block are 32 contiguous bytes
-//     in the exchange layout -- exactly what a lane of the B operand needs for the eight k-steps -- so
-//     they are loaded straight into registers like the weight words, all requests issued before the
-//     first wait, no LDS tile and no barrier before the contraction;
+//   * no shared staging and no barrier before the contraction: a wave fetches the packed words of its
+//     own 16 weight rows and 16 batch columns itself, all requests issued before the first wait.  The
+//     requests are contiguous (8 adjacent lanes take one 128-byte row): in the operand layout adjacent
+//     lanes are adjacent rows, 128 bytes apart, and a compute unit needs three times as long to serve
+//     such loads (measured for this kernel's 12 KiB per wave: operands complete after 3.3 K / 6.2 K
+//     cycles for the first / second wave of a SIMD, against 1.7 K / 2.7 K cycles this way).  The wave
+//     turns the rows into the operand layout through a private piece of LDS (rows padded to 144 bytes,
+//     no barrier: LDS serves one wave's accesses in order): lane (row, k-block b) ends with the 16-byte
+//     pieces b and b + 4 of its row -- which K positions a k-block holds is free as long as both
+//     operands agree;
 //   * both operands are expanded to {-1, +1} codes (expand4_signed) under the matrix instructions of
 //     the previous k-step, so the accumulators hold the inner products of the codes themselves: no
 //     popcounts.  Positions past the end of a vector are 0 bits in both operands, i.e. (-1)(-1) = +1
 //     each, a constant that the epilogue takes off.
 // Workgroups of NWV waves (NWV / 2 row blocks x 2 operand blocks).  Same arithmetic and summation
 // order as the other cell kernels: results are bit-identical to theirs.
+constexpr int kTurnStride = 9;  // 16-byte units per row in the LDS piece that turns rows into operands (128 B + 16 B pad)
+
 template <int KW, int KA, int NBT, int EPI, int NWV>
 __global__ __launch_bounds__(64 * NWV) void mfma4p_kernel(BmvArgs a, int rowblocks) {
   static_assert(EPI == kEpiLstm || EPI == kEpiGru, "cell modes only");
   __shared__ float4 xch[(NWV / 2) * NBT * 64];  // [pair][tile][lane]: the h-side sums on their way to the x wave
+  extern __shared__ __attribute__((aligned(16))) uint4 turn[];  // [wave][operand tile][16 rows][kTurnStride]
   constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
 
   // (phase timers of the profiling build: 0 start, 1 requests issued, 10 operands arrived, 5 contraction,
@@ -560,40 +571,68 @@ __global__ __launch_bounds__(64 * NWV) void mfma4p_kernel(BmvArgs a, int rowbloc
   const float* beta = kb ? a.blk[1].beta : a.blk[0].beta;
   const int nlen = kb ? a.blk[1].n : a.blk[0].n;
   const int wq = (nlen + 127) >> 7;  // 16-byte groups per row
-  // weight words, A-operand view: lane = (tile row l16 = 4 * unit + gate, k-block l4), 32 bytes per plane
+  // weight words: request v of plane i covers gates 2v and 2v + 1 of the row block's 4 units, 512
+  // contiguous bytes each (lane -> gate 2v + lane / 32, unit (lane / 8) % 4, 16-byte piece lane % 8);
+  // activation words: request v of plane j covers batch columns 8v .. 8v + 7 of the tile, 1 KiB contiguous.
+  // Rows, gates and columns past the end are clamped to the last valid one (their results are never
+  // stored); pieces past the end of a short row must read as zero bits.  Addresses are a uniform base
+  // plus a 32-bit byte offset per lane.
   uint4 araw[KW][2];
+  uint4 braw[NBT][KA][2];
+  const int ld_piece = lane & 7;
   {
-    const int unit_a = rb * 4 + (l16 >> 2), gate_a = l16 & 3;
-    const bool wok = live && unit_a < H && gate_a < NG;
-    const int base = (wok ? gate_a * H + unit_a : 0) * wq;
-    const int plane = m * wq;
-#pragma unroll
-    for (int i = 0; i < KW; ++i)
+    unsigned aoff[2], boff[NBT][2];
+    {
+      int unit = rb * 4 + ((lane >> 3) & 3);
+      unit = unit < H ? unit : H - 1;
 #pragma unroll
       for (int v = 0; v < 2; ++v) {
-        const int g = 2 * l4 + v;
-        const uint4 t4 = Wp4[base + i * plane + (g < wq ? g : 0)];
-        araw[i][v] = (wok && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
+        int gate = 2 * v + (lane >> 5);
+        gate = gate < NG ? gate : NG - 1;
+        aoff[v] = (unsigned)((gate * H + unit) * wq + ld_piece) * 16u;
       }
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) {
+          int col = bg0 + bt * kTileB + 8 * v + (lane >> 3);
+          col = col < batch ? col : batch - 1;
+          boff[bt][v] = (unsigned)(col * wq + ld_piece) * 16u;
+        }
+    }
+    const char* Wb = reinterpret_cast<const char*>(Wp4);
+    const char* Xb = reinterpret_cast<const char*>(Xp4);
+    const size_t wplane = (size_t)m * wq * 16, xplane = (size_t)batch * wq * 16;
+    auto request = [&](auto full_rows) {
+      const bool in_row = decltype(full_rows)::value || ld_piece < wq;
+#pragma unroll
+      for (int v = 0; v < 2; ++v)
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          if (in_row) araw[i][v] = *reinterpret_cast<const uint4*>(Wb + i * wplane + aoff[v]);
+          else araw[i][v] = make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+#pragma unroll
+          for (int j = 0; j < KA; ++j) {
+            if (in_row) braw[bt][j][v] = *reinterpret_cast<const uint4*>(Xb + j * xplane + boff[bt][v]);
+            else braw[bt][j][v] = make_uint4(0, 0, 0, 0);
+          }
+    };
+    if (wq == 8) request(std::true_type{});  // rows of 1024 entries: no lane is past the end
+    else request(std::false_type{});
   }
-  // activation words, B-operand view: lane = (batch column l16 of every tile, k-block l4)
   int bcol[NBT];
   bool bok[NBT];
-  uint4 braw[NBT][KA][2];
   float beta_req[NBT];
 #pragma unroll
   for (int bt = 0; bt < NBT; ++bt) {
     bcol[bt] = bg0 + bt * kTileB + l16;
     bok[bt] = bcol[bt] < batch;
     const int bc = bok[bt] ? bcol[bt] : batch - 1;
-#pragma unroll
-    for (int j = 0; j < KA; ++j)
-#pragma unroll
-      for (int v = 0; v < 2; ++v) {
-        const int g = 2 * l4 + v;
-        const uint4 t4 = Xp4[(j * batch + bc) * wq + (g < wq ? g : 0)];
-        braw[bt][j][v] = (bok[bt] && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
-      }
     // column coefficients: lane (l16, l4) asks for plane min(l4, KA - 1) of its column
     beta_req[bt] = beta[bc * KA + (l4 < KA ? l4 : KA - 1)];
   }
@@ -617,6 +656,37 @@ __global__ __launch_bounds__(64 * NWV) void mfma4p_kernel(BmvArgs a, int rowbloc
     }
   }
   AMQ_PHASE_B(AMQ_PHASE_OF(a), 1);
+
+  // ---- rows -> operand layout through this wave's piece of LDS: tile row l16 = 4 * unit + gate for the
+  // weights, the batch column for the activations; lane (l16, l4) takes pieces l4 and l4 + 4 of its row
+  {
+    uint4* mine = turn + wv * ((KW + NBT * KA) * kTileB * kTurnStride);
+    {
+      const int row = 4 * ((lane >> 3) & 3) + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < KW; ++i)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) mine[(i * kTileB + row + 2 * v) * kTurnStride + ld_piece] = araw[i][v];
+    }
+    uint4* mineb = mine + KW * kTileB * kTurnStride;
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int j = 0; j < KA; ++j)
+#pragma unroll
+        for (int v = 0; v < 2; ++v)
+          mineb[((bt * KA + j) * kTileB + 8 * v + (lane >> 3)) * kTurnStride + ld_piece] = braw[bt][j][v];
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int v = 0; v < 2; ++v) araw[i][v] = mine[(i * kTileB + l16) * kTurnStride + l4 + 4 * v];
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+      for (int j = 0; j < KA; ++j)
+#pragma unroll
+        for (int v = 0; v < 2; ++v) braw[bt][j][v] = mineb[((bt * KA + j) * kTileB + l16) * kTurnStride + l4 + 4 * v];
+  }
 
   // ---- contraction: k-step t multiplies the t-th words of this lane's k-block; the operands of step
   // t + 1 are expanded under the matrix instructions of step t
@@ -916,7 +986,14 @@ hipError_t launch_pair_one(const BmvArgs& a, hipStream_t s) {
     dim3 grid((unsigned)((rowblocks + NWV / 2 - 1) / (NWV / 2)), (unsigned)groups);
     BmvArgs b = a;
     AMQ_PHASE_ATTACH(b);
-    hipLaunchKernelGGL((mfma4p_kernel<KW, KA, NBT, EPI, NWV>), grid, dim3(64 * NWV), 0, s, b, rowblocks);
+    constexpr size_t lds = sizeof(uint4) * NWV * (KW + NBT * KA) * kTileB * kTurnStride;
+    static std::atomic<unsigned long long> configured{0};
+    {
+      hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(&mfma4p_kernel<KW, KA, NBT, EPI, NWV>), (int)lds,
+                                        configured);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((mfma4p_kernel<KW, KA, NBT, EPI, NWV>), grid, dim3(64 * NWV), lds, s, b, rowblocks);
     return hipGetLastError();
   }
 }
