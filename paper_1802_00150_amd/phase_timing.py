@@ -23,10 +23,10 @@ QUANT_MARKS = [(0, "start"), (1, "vector in registers"), (2, "greedy initialisat
                (6, "cycle 1: sorted code table"), (7, "cycle 1: code assignment (Alg. 1)"),
                (8, "cycle 2: reduction"), (9, "cycle 2: solve"), (10, "cycle 2: code table"),
                (11, "cycle 2: code assignment"), (31, "codes and coefficients stored")]
-STEP_MARKS = [(0, "start"), (1, "requests issued (activation words, first row block)"),
-              (9, "activation words arrived, own part of the tile staged"), (2, "barrier: tile staged"),
-              (3, "column coefficients and popcounts read"), (4, "row coefficients spread"),
-              (10, "weight words arrived (their popcounts taken)"), (5, "contraction done (matrix cores)"),
+STEP_MARKS = [(0, "start"), (1, "operand requests issued"),
+              (9, "own share of the activation operands expanded and written"), (2, "barrier: activation operands complete"),
+              (3, "weight words arrived and written to the private piece of LDS"), (4, "weight words in operand layout"),
+              (10, "first operands ready"), (5, "contraction done (matrix cores)"),
               (6, "coefficient epilogue done"), (7, "x/h exchange (barrier)"), (8, "cell applied, stores issued")]
 
 
