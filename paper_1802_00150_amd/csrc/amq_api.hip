@@ -322,11 +322,10 @@ size_t amq_gru_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
 
 // Products + epilogue + cell in one launch, given quantized operands.  Returns -1 if no fused
 // kernel takes this shape (the caller then uses the unfused path, which needs a workspace).
-static int lstm_fused_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
-                             const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
-                             const uint32_t* Xp, const float* beta_x, const uint32_t* Hp, const float* beta_h,
-                             const float* c_prev, int64_t B, int k_a, float* h_out, float* c_out,
-                             float* hs_out, hipStream_t s) {
+static amq::BmvArgs lstm_args(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                              int64_t I, int64_t H, const float* bias, const uint32_t* Xp, const float* beta_x,
+                              const uint32_t* Hp, const float* beta_h, const float* c_prev, int64_t B, float* h_out,
+                              float* c_out, float* hs_out) {
   amq::BmvArgs b{};
   b.blk[0] = amq::BmvBlock{Wxp, alpha_x, Xp, beta_x, (int)I};
   b.blk[1] = amq::BmvBlock{Whp, alpha_h, Hp, beta_h, (int)H};
@@ -339,6 +338,16 @@ static int lstm_fused_launch(const uint32_t* Wxp, const float* alpha_x, const ui
   b.c_out = c_out;
   b.hs_out = hs_out;
   b.groups = 1;
+  return b;
+}
+
+static int lstm_fused_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                             const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                             const uint32_t* Xp, const float* beta_x, const uint32_t* Hp, const float* beta_h,
+                             const float* c_prev, int64_t B, int k_a, float* h_out, float* c_out,
+                             float* hs_out, hipStream_t s) {
+  const amq::BmvArgs b = lstm_args(Wxp, alpha_x, Whp, alpha_h, I, H, bias, Xp, beta_x, Hp, beta_h, c_prev, B, h_out,
+                                   c_out, hs_out);
   if (amq::bmv_supported((int)I, (int)H, k_a, B, amq::kEpiLstm))
     return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiLstm, s));
   if (amq::mfma_supported(B))

@@ -13,16 +13,17 @@ constexpr int kWave = 64;
 // the quantizer uses rows 0..7 (AMQ_PHASE), the product kernels rows 8..15 (AMQ_PHASE_B), so that the
 // two kernels of one step can be timed in the same run.  In the ordinary build the marks expand to nothing.
 #ifdef AMQ_PHASE_TIMING
-#define AMQ_PHASE_AT(buf, row0, id)                                                             \
+#define AMQ_PHASE_WHEN(cond, buf, row0, id)                                                     \
   do {                                                                                          \
-    if ((buf) && blockIdx.x == 0 && blockIdx.y == 0 && (threadIdx.x & 63) == 0)                 \
+    if ((buf) && (cond) && (threadIdx.x & 63) == 0)                                             \
       (buf)[((row0) + (threadIdx.x >> 6)) * 32 + (id)] = __builtin_readcyclecounter();          \
   } while (0)
 #else
-#define AMQ_PHASE_AT(buf, row0, id) \
-  do {                              \
+#define AMQ_PHASE_WHEN(cond, buf, row0, id) \
+  do {                                      \
   } while (0)
 #endif
+#define AMQ_PHASE_AT(buf, row0, id) AMQ_PHASE_WHEN(blockIdx.x == 0 && blockIdx.y == 0, buf, row0, id)
 #define AMQ_PHASE(buf, id) AMQ_PHASE_AT(buf, 0, id)
 #define AMQ_PHASE_B(buf, id) AMQ_PHASE_AT(buf, 8, id)
 

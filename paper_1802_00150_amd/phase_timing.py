@@ -30,10 +30,13 @@ STEP_MARKS = [(0, "start"), (1, "operand requests issued"),
               (6, "coefficient epilogue done"), (7, "x/h exchange (barrier)"), (8, "cell applied, stores issued")]
 
 
-def _report(name, names, samples, row0):
-    samples = np.asarray(samples, np.int64)[:, row0:row0 + 8]   # [launch, wave, mark]
+def _report(name, names, samples, row0, origin_row=None):
+    """origin_row: row whose mark 0 is the time origin (default: wave 0 of the reported kernel; for a step
+    that runs as one launch the quantizer's wave 0, which puts both roles on one time line)."""
+    allrows = np.asarray(samples, np.int64)
+    samples = allrows[:, row0:row0 + 8]   # [launch, wave, mark]
     print(name)
-    start = samples[:, 0, names[0][0]]
+    start = samples[:, 0, names[0][0]] if origin_row is None else allrows[:, origin_row, 0]
     nwaves = [w for w in range(samples.shape[1]) if (samples[:, w, names[0][0]] != 0).all()]
     print("  %-58s %s" % ("cycles after wave 0 started, per wave:", " ".join("%6d" % w for w in nwaves)))
     for i, label in names:
@@ -88,6 +91,7 @@ def main():
     _report("on-line quantizer, %d vectors of %d, %d-bit, T=2" % (2 * B, H, k), QUANT_MARKS, samples, 0)
     _report("products + LSTM cell, 4H x 2H = %d x %d, batch %d, W%d/A%d" % (4 * H, 2 * H, B, k, k), STEP_MARKS,
             samples, 8)
+    _report("the same on the quantizer's time line (meaningful when the step is one launch)", STEP_MARKS, samples, 8, 0)
 
 
 if __name__ == "__main__":
