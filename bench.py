@@ -36,14 +36,13 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T integer lane-ops/s: 256 C
 FP4_MFMA_PEAK_TFLOPS = 10100.0               # dense fp4 matrix cores
 # HBM bytes per launch of the streamed W2/A2 GEMV from the rocprofv3 counter runs summarised in
 # profiles/gemv_streamed_4096x1024.md: 2.0 x FETCH_SIZE + 1.0 x WRITE_SIZE (scale factors from a plain
-# 512 MiB device copy) = (2 x 270913.6 + 8192.6) KiB
-GEMV_TRAFFIC_BYTES = (2 * 270913.6 + 8192.6) * 1024
+# 512 MiB device copy and a 1 GiB read) = (2 x 270918.5 + 8192.2) KiB
+GEMV_TRAFFIC_BYTES = (2 * 270918.5 + 8192.2) * 1024
 # the same for the two kernels of the primary workload (profiles/lstm_step_1024_b64_w3a3.md) and for the
-# streamed batch-1 LSTM step (profiles/lstm_step_b1_streamed_1024_w3a3.md); None where no counter run is
-# recorded
-LSTM_FUSED_TRAFFIC_BYTES = None
-LSTM_QUANT_TRAFFIC_BYTES = None
-LSTM_B1_TRAFFIC_BYTES = None
+# streamed batch-1 LSTM step (profiles/lstm_step_b1_streamed_1024_w3a3.md)
+LSTM_FUSED_TRAFFIC_BYTES = (2 * 2109.4 + 512.0) * 1024
+LSTM_QUANT_TRAFFIC_BYTES = (2 * 333.1 + 52.8) * 1024
+LSTM_B1_TRAFFIC_BYTES = (2 * 271843.8 + 1368.0) * 1024
 FP32_VALU_PEAK_TFLOPS = 157.3                # vector fp32
 MIN_TIMED_CALLS = 100
 MIN_WARMUP_CALLS = 10
@@ -483,6 +482,8 @@ def main():
     ap.add_argument("--steps", type=int, default=700)
     ap.add_argument("--warmup", type=int, default=70)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--counters", action="store_true",
+                    help="run under a counter-collecting profiler: few launches of everything (timings are then meaningless)")
     ap.add_argument("--sections", default=",".join(SECTIONS),
                     help="comma list out of %s, plus copy_probe (for counter calibration)" % SECTIONS)
     args = ap.parse_args()
@@ -532,6 +533,8 @@ def main():
         S = cfg["xs"].shape[0]
         seqs = max(MIN_TIMED_CALLS, (args.steps + S - 1) // S)
         warm = max(MIN_WARMUP_CALLS, (args.warmup + S - 1) // S)
+        if args.counters:
+            seqs, warm = 3, 2
         st = bench_lstm_sequence(amq, cfg, dev, seqs, warm)
         out["steps"] = seqs * S
         out["warmup"] = warm * S
@@ -543,12 +546,13 @@ def main():
                          "event_us_per_step_median": st["event_median_ms"] / S * 1e3,
                          "event_us_per_step_min": st["event_min_ms"] / S * 1e3,
                          "event_us_per_step_mean": st["event_mean_ms"] / S * 1e3}
-        ms_call, q = bench_lstm_steps(amq, cfg, dev, max(args.steps, 700), max(args.warmup, 70))
+        ms_call, q = bench_lstm_steps(amq, cfg, dev, 35 if args.counters else max(args.steps, 700),
+                                      35 if args.counters else max(args.warmup, 70))
         also["lstm_b64_per_step_call_steps_per_s"] = 1e3 / ms_call
         # the two kernels of a step: on-line quantization of the 2B vectors x_t, h_{t-1}, then the
         # products with both weight blocks + coefficient epilogue + cell on the fp4 matrix cores
         # (codes as {-1,+1}); `roofline` is the one that takes longer
-        ms_fused, ms_quant = bench_lstm_fused_kernel(amq, cfg, dev, q)
+        ms_fused, ms_quant = bench_lstm_fused_kernel(amq, cfg, dev, q, iters=20 if args.counters else 300)
         macs = 2.0 * 4 * H * H * k_w * k_a * B
         achieved = 2.0 * macs / (ms_fused * 1e-3) / 1e12
         r_prod = {"kernel": "mfma4p_kernel<3,3,1,lstm,8>: W3/A3 products with both 4096x1024 blocks (B=64) + cell",
@@ -573,18 +577,20 @@ def main():
     if "lstm_b1" in sections:
         # batch-1 LSTM, config 1 (hidden 300): (i) one launch pair per step, (ii) the same launches replayed
         # from a HIP graph, (iii) one call per sequence (grid-persistent kernel, weights on chip)
-        c1 = inputs.lstm_small()
-        ms1, _ = bench_lstm_steps(amq, c1, dev, 700, 70)
-        st1 = bench_lstm_sequence(amq, c1, dev, 100, 10)
-        stg = bench_lstm_graph(amq, c1, dev)
-        also["lstm_b1_hidden300_steps_per_s"] = 1e3 / ms1
-        also["lstm_b1_hidden300_hip_graph_steps_per_s"] = 1e3 * stg["steps_per_call"] / stg["event_median_ms"]
-        also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 * st1["steps_per_call"] / st1["event_median_ms"]
         cb = inputs.lstm_large(B=1)
-        msb, _ = bench_lstm_steps(amq, cb, dev, 700, 70)
-        stb = bench_lstm_sequence(amq, cb, dev, 100, 10)
-        also["lstm_b1_hidden1024_w3a3_steps_per_s"] = 1e3 / msb
-        also["lstm_b1_hidden1024_w3a3_sequence_call_steps_per_s"] = 1e3 * stb["steps_per_call"] / stb["event_median_ms"]
+        if not args.counters:
+            c1 = inputs.lstm_small()
+            ms1, _ = bench_lstm_steps(amq, c1, dev, 700, 70)
+            st1 = bench_lstm_sequence(amq, c1, dev, 100, 10)
+            stg = bench_lstm_graph(amq, c1, dev)
+            also["lstm_b1_hidden300_steps_per_s"] = 1e3 / ms1
+            also["lstm_b1_hidden300_hip_graph_steps_per_s"] = 1e3 * stg["steps_per_call"] / stg["event_median_ms"]
+            also["lstm_b1_hidden300_sequence_call_steps_per_s"] = 1e3 * st1["steps_per_call"] / st1["event_median_ms"]
+            msb, _ = bench_lstm_steps(amq, cb, dev, 700, 70)
+            stb = bench_lstm_sequence(amq, cb, dev, 100, 10)
+            also["lstm_b1_hidden1024_w3a3_steps_per_s"] = 1e3 / msb
+            also["lstm_b1_hidden1024_w3a3_sequence_call_steps_per_s"] = (1e3 * stb["steps_per_call"] /
+                                                                         stb["event_median_ms"])
         # the HBM-bound form of the batch-1 step: config 3's shape at B = 1, G independent cells streamed
         ms, G, nbytes = bench_lstm_b1_stream(amq, dev, cb["I"], cb["H"], cb["k_w"], cb["k_a"])
         gbps = nbytes / (ms * 1e-3) / 1e9
