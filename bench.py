@@ -520,10 +520,12 @@ def main():
         also["stream_read_probe_1GiB_GBps"] = probe_gbps
         also["stream_read_probe_frac_of_nominal"] = probe_gbps / HBM_PEAK_GBPS
 
-    def hbm_roofline(kernel, gbps, ms, nbytes, traffic):
+    def hbm_roofline(kernel, gbps, ms, nbytes, traffic, source):
+        # `traffic` is the counter figure recorded in the named summary (a separate rocprofv3 run of this
+        # file), not something measured in this run
         return {"kernel": kernel, "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": gbps / HBM_PEAK_GBPS, "frac_of_stream_read_probe": gbps / probe_gbps if probe_gbps else None,
-                "traffic": traffic, "launch_ms": ms, "bytes_per_launch": nbytes}
+                "traffic": traffic, "traffic_source": source, "launch_ms": ms, "bytes_per_launch": nbytes}
 
     if "primary" in sections:
         # config 3, LSTM 1024/1024, batch 64, W3/A3, T=2: whole 35-step sequences through
@@ -558,7 +560,8 @@ def main():
         r_prod = {"kernel": "mfma4p_kernel<3,3,1,lstm,8>: W3/A3 products with both 4096x1024 blocks (B=64) + cell",
                   "bound": "mfma", "achieved": achieved, "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                   "frac": achieved / FP4_MFMA_PEAK_TFLOPS, "traffic": LSTM_FUSED_TRAFFIC_BYTES,
-                  "launch_ms": ms_fused, "flops_per_launch": 2.0 * macs}
+                  "traffic_source": "profiles/lstm_step_1024_b64_w3a3.md", "launch_ms": ms_fused,
+                  "flops_per_launch": 2.0 * macs}
         # Sec. 3 cost of Alg. 2 per n-vector: 2 T k^2 n binary + 2 (T+1) k n non-binary operations
         n = cfg["I"]
         qops = 2 * B * (2.0 * T * k_a * k_a * n + 2.0 * (T + 1) * k_a * n)
@@ -566,7 +569,8 @@ def main():
         r_quant = {"kernel": "quantize_kernel<3,4,4>: Alg. 2 on the 128 vectors x_t, h_{t-1} of length 1024 "
                              "(128 workgroups of 4 waves: latency-bound, half the CUs idle)",
                    "bound": "alu", "achieved": qach, "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
-                   "frac": qach / FP32_VALU_PEAK_TFLOPS, "traffic": LSTM_QUANT_TRAFFIC_BYTES, "launch_ms": ms_quant,
+                   "frac": qach / FP32_VALU_PEAK_TFLOPS, "traffic": LSTM_QUANT_TRAFFIC_BYTES,
+                   "traffic_source": "profiles/lstm_step_1024_b64_w3a3.md", "launch_ms": ms_quant,
                    "flops_per_launch": qops}
         first, second = (r_prod, r_quant) if ms_fused >= ms_quant else (r_quant, r_prod)
         out["roofline"] = first
@@ -597,7 +601,7 @@ def main():
         also["lstm_b1_hidden1024_w3a3_streamed_GBps"] = gbps
         out["roofline_lstm_b1"] = hbm_roofline("bmv_kernel<3,3,1,lstm>: batch-1 LSTM step 1024/1024 W3/A3 on packed "
                                                "operands, %d independent cells streamed" % G, gbps, ms, nbytes,
-                                               LSTM_B1_TRAFFIC_BYTES)
+                                               LSTM_B1_TRAFFIC_BYTES, "profiles/lstm_step_b1_streamed_1024_w3a3.md")
 
     if "gemv" in sections:
         # batch-1 GEMV, config 2: streamed from HBM (grouped) and cache-resident latency
@@ -607,7 +611,8 @@ def main():
             also["gemv_b1_w%da%d_streamed_GBps" % (k, k)] = gbps
             if k == 2:
                 out["roofline_gemv"] = hbm_roofline("binary GEMV 4096x1024 W2/A2 batch 1, %d matrices streamed" % G,
-                                                    gbps, ms, nbytes, GEMV_TRAFFIC_BYTES)
+                                                    gbps, ms, nbytes, GEMV_TRAFFIC_BYTES,
+                                                    "profiles/gemv_streamed_4096x1024.md")
             also["gemv_b1_w%da%d_warm_call_us" % (k, k)] = bench_gemv_warm(amq, dev, 4096, 1024, k) * 1e3
 
     if "gemm" in sections:
