@@ -144,7 +144,7 @@ def bench_lstm_sequence(amq, cfg, dev, seqs, warmup):
     S = xs.shape[0]
     h = torch.zeros((B, H), device=dev)
     c = torch.zeros((B, H), device=dev)
-    ws = amq.lstm_workspace(I, H, B, k_a, dev)
+    ws = amq.lstm_sequence_workspace(I, H, B, k_a, dev)
 
     def seq():
         h.zero_()

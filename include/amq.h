@@ -210,6 +210,14 @@ int amq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* strea
  * completed call; SIZE_MAX: this shape has no such word).
  */
 size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a);
+/*
+ * Workspace with which amq_lstm_sequence takes W_x x_t off the recurrent chain for B > 1 (Eq. 6: the
+ * inputs do not depend on the recurrence): amq_lstm_workspace_bytes plus room for the codes of two
+ * consecutive inputs and the x-side sums of one step.  With a smaller workspace (at least
+ * amq_lstm_workspace_bytes) the call runs the steps one after the other; the results are the same bit
+ * for bit.
+ */
+size_t amq_lstm_sequence_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a);
 int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                       const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
                       const float* xs, int64_t steps, float* h, float* c, int64_t B, int k_a, int T,

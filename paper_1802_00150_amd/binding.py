@@ -21,7 +21,7 @@ EXPORTS = [
     "amq_binary_dots", "amq_binary_gemv", "amq_binary_gemm", "amq_binary_gemv_grouped",
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed",
     "amq_lstm_step_packed_grouped", "amq_stream_read_probe", "amq_lstm_sequence",
-    "amq_lstm_sequence_flag_offset", "amq_debug_set_sequence_spin_limit",
+    "amq_lstm_sequence_flag_offset", "amq_lstm_sequence_workspace_bytes", "amq_debug_set_sequence_spin_limit",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
@@ -63,6 +63,8 @@ def lib():
         L.amq_gru_workspace_bytes.argtypes, L.amq_gru_workspace_bytes.restype = [_i64, _i64, _i64, _int], _sz
         L.amq_lstm_sequence_flag_offset.argtypes = [_i64, _i64, _i64, _int]
         L.amq_lstm_sequence_flag_offset.restype = _sz
+        L.amq_lstm_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.amq_lstm_sequence_workspace_bytes.restype = _sz
         L.amq_debug_set_sequence_spin_limit.argtypes = [C.c_uint]
         L.amq_debug_set_sequence_spin_limit.restype = None
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,
@@ -246,6 +248,12 @@ def lstm_workspace(I, H, B, k_a, device):
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
+def lstm_sequence_workspace(I, H, B, k_a, device):
+    """Workspace with which lstm_sequence takes the input products off the recurrent chain (B > 1)."""
+    nbytes = int(lib().amq_lstm_sequence_workspace_bytes(I, H, B, k_a))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
 def gru_workspace(I, H, B, k_a, device):
     nbytes = int(lib().amq_gru_workspace_bytes(I, H, B, k_a))
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -338,7 +346,7 @@ def lstm_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias, xs, h, c, k_a, T, ws=N
     k_w = Wxp.shape[0]
     steps, B, _ = xs.shape
     if ws is None:
-        ws = lstm_workspace(I, H, B, k_a, xs.device)
+        ws = lstm_sequence_workspace(I, H, B, k_a, xs.device)
     _check(lib().amq_lstm_sequence(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32),
                                    _dev(Whp, torch.int32), _dev(alpha_h, torch.float32), I, H, k_w,
                                    _opt(bias), _dev(xs, torch.float32), steps, _dev(h, torch.float32),

@@ -17,7 +17,7 @@ LIB = os.path.join(HERE, "libamq.so")
 # point amq_debug_set_phase_buffer); loaded instead of libamq.so when AMQ_LIBRARY names it
 LIB_PHASES = os.path.join(HERE, "libamq_phases.so")
 
-SOURCES = ["amq_api.hip", "amq_quantize.hip", "amq_gemm.hip", "amq_bmv.hip", "amq_mfma.hip", "amq_mfma4.hip", "amq_mfma4w.hip", "amq_lstm_seqg.hip", "amq_cells.hip", "amq_lm.hip", "amq_baselines.hip"]
+SOURCES = ["amq_api.hip", "amq_quantize.hip", "amq_gemm.hip", "amq_bmv.hip", "amq_mfma.hip", "amq_mfma4.hip", "amq_mfma4w.hip", "amq_step.hip", "amq_lstm_seqg.hip", "amq_cells.hip", "amq_lm.hip", "amq_baselines.hip"]
 # packed-fp32 instructions are disabled on purpose; -ffp-contract=off keeps single binary32
 # operations single (the code-assignment comparison must round like the reference arithmetic).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

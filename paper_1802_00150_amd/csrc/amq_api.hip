@@ -103,6 +103,35 @@ StepWs carve(void* ws, int64_t I, int64_t H, int64_t B, int k_a, int gates, int 
   return w;
 }
 
+// Workspace of a batched sequence with given inputs: the step's regions, then what the split step keeps
+// between launches -- codes and coefficients of two consecutive inputs, the x-side sums of one step.
+struct SeqWs {
+  StepWs step;
+  uint32_t* xq[2];
+  float* xbeta[2];
+  float* xsum;
+  size_t total;
+};
+
+SeqWs carve_seq(void* ws, int64_t I, int64_t H, int64_t B, int k_a) {
+  SeqWs w;
+  w.step = carve(ws, I, H, B, k_a, 4, 1);
+  size_t off = w.step.total;
+  char* base = static_cast<char*>(ws);
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += up256(bytes);
+    return p;
+  };
+  for (int i = 0; i < 2; ++i) {
+    w.xq[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(I)));
+    w.xbeta[i] = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * k_a));
+  }
+  w.xsum = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * H * 4));
+  w.total = off;
+  return w;
+}
+
 int check_step(const void* Wxp, const void* ax, const void* Whp, const void* ah, int64_t I, int64_t H,
                int k_w, const void* x, const void* h_prev, int64_t B, int k_a, int T, const void* h_out,
                const void* ws, size_t ws_bytes, size_t need) {
@@ -463,6 +492,11 @@ int amq_lstm_step_static(const uint32_t* Wxp, const float* alpha_x, const uint32
                           c_out, nullptr, w, static_cast<hipStream_t>(stream));
 }
 
+size_t amq_lstm_sequence_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve_seq(nullptr, I, H, B, k_a).total;
+}
+
 size_t amq_lstm_sequence_flag_offset(int64_t I, int64_t H, int64_t B, int k_a) {
   if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return SIZE_MAX;
   return carve(nullptr, I, H, B, k_a, 4, 1).sync_off;
@@ -498,9 +532,55 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
     return AMQ_OK;
   }
   StepWs w = carve(workspace, I, H, B, k_a, 4, 1);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  {
+    // The inputs are all given, so W_x x_t is taken off the recurrent chain where the shape allows and the
+    // workspace has room (amq_lstm_sequence_workspace_bytes): per step a front launch (quantize h_{t-1} and,
+    // in its shadow, quantize x_{t+1} and form the x-side sums of step t from the codes of x_t) and a back
+    // launch (h-side sums + stored x-side sums + cell).  The first step has no codes of x_0 yet: its front
+    // launch quantizes h, x_0 and x_1 and its back launch is the whole-step kernel.  Same results as the
+    // per-step path, bit for bit.
+    const SeqWs sw = carve_seq(workspace, I, H, B, k_a);
+    const amq::BmvArgs probe = lstm_args(Wxp, alpha_x, Whp, alpha_h, I, H, bias, sw.xq[0], sw.xbeta[0], w.hp, w.beta_h,
+                                         c, B, h, c, nullptr);
+    if (workspace_bytes >= sw.total && amq::step_split_supported(probe, k_w, k_a, amq::kEpiLstm)) {
+      auto step_args = [&](int64_t t) {
+        amq::BmvArgs b = probe;
+        b.blk[0].Xp = sw.xq[t % 2];
+        b.blk[0].beta = sw.xbeta[t % 2];
+        b.Y = sw.xsum;
+        b.hs_out = hs ? hs + t * B * H : nullptr;
+        return b;
+      };
+      auto x_seg = [&](int64_t u) {
+        return amq::QuantSeg{xs + u * B * I, I, (int)I, (int)B, sw.xq[u % 2], sw.xbeta[u % 2]};
+      };
+      for (int64_t t = 0; t < steps; ++t) {
+        amq::QuantArgs q{}, q2{};
+        q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
+        q.T = q2.T = T;
+        q.mode = q2.mode = amq::kQuantFull;
+        const amq::BmvArgs b = step_args(t);
+        if (t == 0) {
+          q.seg[1] = x_seg(0);
+          if (steps > 1) q2.seg[0] = x_seg(1);
+          st = hip_status(amq::launch_step_front(q, steps > 1 ? &q2 : nullptr, nullptr, k_w, k_a, amq::kEpiLstm, s));
+          if (st != AMQ_OK) return st;
+          st = hip_status(amq::launch_mfma4_pair(b, k_w, k_a, amq::kEpiLstm, s));
+        } else {
+          if (t + 1 < steps) q.seg[1] = x_seg(t + 1);
+          st = hip_status(amq::launch_step_front(q, nullptr, &b, k_w, k_a, amq::kEpiLstm, s));
+          if (st != AMQ_OK) return st;
+          st = hip_status(amq::launch_step_back(b, k_w, k_a, amq::kEpiLstm, s));
+        }
+        if (st != AMQ_OK) return st;
+      }
+      return AMQ_OK;
+    }
+  }
   for (int64_t t = 0; t < steps; ++t) {
     st = lstm_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias, xs + t * B * I, h, c, B, k_a, T, h, c,
-                          hs ? hs + t * B * H : nullptr, w, static_cast<hipStream_t>(stream));
+                          hs ? hs + t * B * H : nullptr, w, s);
     if (st != AMQ_OK) return st;
   }
   return AMQ_OK;

@@ -253,6 +253,17 @@ void set_seqg_spin_limit(unsigned polls);
 // overwrite out[0 .. count) with NaN (results computed from an incomplete recurrence must not look valid).
 hipError_t launch_seqg_poison(const unsigned* sync, float* out, long long count, hipStream_t s);
 
+// ---- the recurrent step of a sequence with given inputs, cut along the operand blocks ----------
+// Front launch: quantizes the vectors of q (seg[0] = h_{t-1}, seg[1] = a later x, count 0 for none) and of
+// q2 (nullable; more inputs, at the first step), and forms the x-side product x (nullable; operand block 0
+// of *x: codes from an earlier front launch; x->Y receives the sums as [batch][H][4]).  Back launch:
+// h-side products of a (operand block 1), plus the x-side sums in a.Y, then the cell.  Same shapes as the
+// paired one-tile kernel, k_w and k_a at most 3.
+bool step_split_supported(const BmvArgs& b, int k_w, int k_a, int epi);
+hipError_t launch_step_front(const QuantArgs& q, const QuantArgs* q2, const BmvArgs* x, int k_w, int k_a, int epi,
+                             hipStream_t s);
+hipError_t launch_step_back(BmvArgs a, int k_w, int k_a, int epi, hipStream_t s);
+
 // ---- bandwidth yardstick ------------------------------------------------------------------
 // Reads `bytes` (a multiple of 16) once with 16-byte loads over kStreamReadBlocks workgroups and leaves
 // an xor checksum per workgroup in sink [kStreamReadBlocks].

@@ -25,6 +25,12 @@
 //     operands agree.
 // Workgroups of NWV waves (NWV / 2 row blocks x 2 operand blocks).  Same arithmetic and summation
 // order as the other cell kernels: results are bit-identical to theirs.
+//
+// The step can also be cut in two along the operand blocks (Eq. 6: W_x x_t does not depend on the
+// recurrence): kPairXOnly forms the x-side sums of NWV row blocks and stores them, kPairHOnly forms the
+// h-side sums, adds the stored x-side sums in the order the whole step adds them, and applies the cell.
+// The stored sums are exactly the values that otherwise travel from the x wave's registers, so the
+// results stay bit-identical.
 #pragma once
 #include "amq_device.h"
 #include "amq_launch.h"
@@ -33,19 +39,29 @@ namespace amq {
 
 constexpr int kTurnStride = 9;  // 16-byte units per row in the LDS piece that turns rows into operands (128 B + 16 B pad)
 
+// Which part of the step a workgroup forms.  The x-side sums of the split form live in a.Y as
+// [batch][hidden unit][4 gates] binary32 (16 bytes per (entry, unit): one store / load per lane).
+enum { kPairBoth = 0, kPairXOnly = 1, kPairHOnly = 2 };
+
 // Dynamic LDS of the body: activation operand images [block][tile][plane][k-step][64 lanes] x 16 B, then
 // one padded 16-row tile per wave.
-template <int KW, int KA, int NBT, int NWV>
+template <int KW, int KA, int NBT, int NWV, int MODE = kPairBoth>
 constexpr size_t pair_body_lds() {
-  return sizeof(uint4) * (2 * NBT * KA * kSteps * 64 + NWV * kTileB * kTurnStride);
+  return sizeof(uint4) * ((MODE == kPairBoth ? 2 : 1) * NBT * KA * kSteps * 64 + NWV * kTileB * kTurnStride);
+}
+// Row blocks (of 4 hidden units) per workgroup.
+template <int NWV, int MODE>
+constexpr int pair_body_rowblocks() {
+  return MODE == kPairBoth ? NWV / 2 : NWV;
 }
 
 // bx, by: row-block group and batch group of this workgroup.  turn: pair_body_lds() bytes of LDS, 16-byte
-// aligned.  xch: (NWV / 2) * NBT * 64 float4 of LDS.
-template <int KW, int KA, int NBT, int EPI, int NWV>
+// aligned.  xch (kPairBoth only): (NWV / 2) * NBT * 64 float4 of LDS.
+template <int KW, int KA, int NBT, int EPI, int NWV, int MODE = kPairBoth>
 __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int bx, int by, uint4* turn, float4* xch) {
   static_assert(EPI == kEpiLstm || EPI == kEpiGru, "cell modes only");
   constexpr int NG = (EPI == kEpiGru) ? 3 : 4;
+  constexpr int NBLK = MODE == kPairBoth ? 2 : 1;  // operand blocks whose activations the workgroup stages
 
   // (phase timers of the profiling build: 0 start, 1 first requests issued, 9 activation operands written,
   // 2 barrier, 4 weight words in operand layout, 10 first operands expanded, 5 contraction, 6 epilogue,
@@ -54,11 +70,14 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, l4 = lane >> 4;
-  const int pr = wv >> 1, kb = wv & 1;  // row block of the workgroup, operand block (0: x and the cell, 1: h)
+  // row block of the workgroup, operand block (0: x, 1: h; in the whole step the x wave applies the cell)
+  const int pr = MODE == kPairBoth ? wv >> 1 : wv;
+  const int kb = MODE == kPairBoth ? (wv & 1) : MODE == kPairHOnly ? 1 : 0;
+  constexpr bool kCellHere = MODE != kPairXOnly;  // this workgroup applies the cell (its kb == 0 waves in kPairBoth)
   const int bg0 = by * NBT * kTileB;
   const int batch = a.batch;
   const int m = (int)a.m, H = (int)a.H;
-  const int rb = bx * (NWV / 2) + pr;
+  const int rb = bx * pair_body_rowblocks<NWV, MODE>() + pr;
   const bool live = rb < rowblocks;  // (a wave without a row block still meets the barriers)
 
   const float* alpha = kb ? a.blk[1].alpha : a.blk[0].alpha;
@@ -76,7 +95,7 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
   // (block, tile, plane, half: batch columns 8v .. 8v + 7 of the tile, lane -> column lane / 8, piece
   // lane % 8); wave w issues requests w, w + NWV, ...  A wave whose share is one request short repeats
   // the last one: same bytes to the same place.
-  constexpr int kShareReq = 2 * NBT * KA * 2;
+  constexpr int kShareReq = NBLK * NBT * KA * 2;
   constexpr int kSharePer = (kShareReq + NWV - 1) / NWV;
   uint4 bshare[kSharePer];
   uint32_t bshare_keep[kSharePer];  // all ones, or zero for a lane past the end of a short row
@@ -85,7 +104,8 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
     for (int q = 0; q < kSharePer; ++q) {
       int idx = wv + q * NWV;  // (uniform)
       idx = idx < kShareReq ? idx : kShareReq - 1;
-      const int v = idx & 1, j = (idx >> 1) % KA, bt = (idx >> 1) / KA % NBT, k2 = idx / (2 * KA * NBT);
+      const int v = idx & 1, j = (idx >> 1) % KA, bt = (idx >> 1) / KA % NBT;
+      const int k2 = MODE == kPairBoth ? idx / (2 * KA * NBT) : kb;
       const int n2 = k2 ? a.blk[1].n : a.blk[0].n;
       const int wq2 = (n2 + 127) >> 7;
       const char* Xb = reinterpret_cast<const char*>(k2 ? a.blk[1].Xp : a.blk[0].Xp);
@@ -128,9 +148,14 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
   }
   const int unit_c = rb * 4 + l4;
   const bool uok = live && unit_c < H;
+  const bool cell_wave = kCellHere && (MODE == kPairHOnly || kb == 0);
   float alpha_req = 0.0f, bias_req = 0.0f, prev[NBT];
+  float4 xside[NBT];  // kPairHOnly: the stored x-side sums of this lane's (entry, unit)
 #pragma unroll
-  for (int bt = 0; bt < NBT; ++bt) prev[bt] = 0.0f;
+  for (int bt = 0; bt < NBT; ++bt) {
+    prev[bt] = 0.0f;
+    xside[bt] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   auto request_column_coefficients = [&]() {
 #pragma unroll
     for (int bt = 0; bt < NBT; ++bt) {
@@ -144,7 +169,7 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
     // the wave that applies the cell the biases and the previous state
     const int r = l16 / KW, i = l16 % KW;
     alpha_req = alpha[((uok && r < NG) ? r * H + unit_c : 0) * KW + i];
-    if (kb == 0) {
+    if (cell_wave) {
       const float* src = (l16 & 4) ? ((EPI == kEpiGru) ? a.bias1 : nullptr) : a.bias0;
       const int rr = l16 & 3;
       bias_req = (src && l16 < 8) ? src[(uok && rr < NG) ? rr * H + unit_c : 0] : 0.0f;
@@ -152,6 +177,7 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
       for (int bt = 0; bt < NBT; ++bt) {
         const int t = (bok[bt] ? bcol[bt] : batch - 1) * H + (uok ? unit_c : 0);
         prev[bt] = (EPI == kEpiLstm) ? a.c_prev[t] : a.h_prev[t];
+        if constexpr (MODE == kPairHOnly) xside[bt] = reinterpret_cast<const float4*>(a.Y)[t];
       }
     }
   };
@@ -203,7 +229,7 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
   turn_weights();
   AMQ_PHASE_WHEN(bx == 0 && by == 0, AMQ_PHASE_OF(a), 8, 4);
   // this lane's operand of (tile, plane, k-step)
-  const uint4* const myimage = image + kb * (NBT * KA * kSteps * 64) + 16 * l4;
+  const uint4* const myimage = image + (MODE == kPairBoth ? kb : 0) * (NBT * KA * kSteps * 64) + 16 * l4;
   auto b_operand = [&](int bt, int j, int t) {
     return myimage[((bt * KA + j) * kSteps + t) * 64 + (l16 ^ ((l4 << 1) | ((t >> 2) << 3)))];
   };
@@ -299,14 +325,24 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
       ysum[bt][r] = y;
     }
   AMQ_PHASE_WHEN(bx == 0 && by == 0, AMQ_PHASE_OF(a), 8, 6);
-  if (kb == 1) {
+  if constexpr (MODE == kPairXOnly) {
+    // the x-side sums of (entry, unit), all gates, as one 16-byte store
 #pragma unroll
     for (int bt = 0; bt < NBT; ++bt)
-      xch[(pr * NBT + bt) * 64 + lane] = make_float4(ysum[bt][0], ysum[bt][1], ysum[bt][2], ysum[bt][3]);
+      if (bok[bt] && uok)
+        reinterpret_cast<float4*>(a.Y)[bcol[bt] * H + unit_c] = make_float4(ysum[bt][0], ysum[bt][1], ysum[bt][2], ysum[bt][3]);
+    return;
   }
-  lds_barrier();
-  AMQ_PHASE_WHEN(bx == 0 && by == 0, AMQ_PHASE_OF(a), 8, 7);
-  if (kb != 0) return;
+  if constexpr (MODE == kPairBoth) {
+    if (kb == 1) {
+#pragma unroll
+      for (int bt = 0; bt < NBT; ++bt)
+        xch[(pr * NBT + bt) * 64 + lane] = make_float4(ysum[bt][0], ysum[bt][1], ysum[bt][2], ysum[bt][3]);
+    }
+    lds_barrier();
+    AMQ_PHASE_WHEN(bx == 0 && by == 0, AMQ_PHASE_OF(a), 8, 7);
+    if (kb != 0) return;
+  }
   float bias0[4], bias1[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -316,14 +352,25 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
   // (no early exit for padded batch columns or units: every lane stays active, the stores are predicated)
 #pragma unroll
   for (int bt = 0; bt < NBT; ++bt) {
-    const float4 o = xch[(pr * NBT + bt) * 64 + lane];
-    const float yh[4] = {o.x, o.y, o.z, o.w};
+    // x-side and h-side sums of this lane's (entry, unit): in the whole step this wave formed the x side and
+    // the h side comes through LDS; in the split step the x side was stored by the earlier launch
+    float yx[4], yh[4];
+    if constexpr (MODE == kPairBoth) {
+      const float4 o = xch[(pr * NBT + bt) * 64 + lane];
+      yh[0] = o.x; yh[1] = o.y; yh[2] = o.z; yh[3] = o.w;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) yx[r] = ysum[bt][r];
+    } else {
+      yx[0] = xside[bt].x; yx[1] = xside[bt].y; yx[2] = xside[bt].z; yx[3] = xside[bt].w;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) yh[r] = ysum[bt][r];
+    }
     const int t = bcol[bt] * H + unit_c;
     if constexpr (EPI == kEpiLstm) {
-      const float gi = sigmoidf_dev(ysum[bt][0] + yh[0] + bias0[0]);
-      const float gf = sigmoidf_dev(ysum[bt][1] + yh[1] + bias0[1]);
-      const float go = sigmoidf_dev(ysum[bt][2] + yh[2] + bias0[2]);
-      const float gg = tanhf_dev(ysum[bt][3] + yh[3] + bias0[3]);
+      const float gi = sigmoidf_dev(yx[0] + yh[0] + bias0[0]);
+      const float gf = sigmoidf_dev(yx[1] + yh[1] + bias0[1]);
+      const float go = sigmoidf_dev(yx[2] + yh[2] + bias0[2]);
+      const float gg = tanhf_dev(yx[3] + yh[3] + bias0[3]);
       const float c = fmaf(gf, prev[bt], gi * gg);
       const float h = go * tanhf_dev(c);
       if (bok[bt] && uok) {
@@ -332,9 +379,9 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
         if (a.hs_out) a.hs_out[t] = h;
       }
     } else {
-      const float rg = sigmoidf_dev(ysum[bt][0] + yh[0] + bias0[0] + bias1[0]);
-      const float z = sigmoidf_dev(ysum[bt][1] + yh[1] + bias0[1] + bias1[1]);
-      const float nn = tanhf_dev(fmaf(rg, yh[2] + bias1[2], ysum[bt][2] + bias0[2]));
+      const float rg = sigmoidf_dev(yx[0] + yh[0] + bias0[0] + bias1[0]);
+      const float z = sigmoidf_dev(yx[1] + yh[1] + bias0[1] + bias1[1]);
+      const float nn = tanhf_dev(fmaf(rg, yh[2] + bias1[2], yx[2] + bias0[2]));
       if (bok[bt] && uok) a.h_out[t] = fmaf(z, prev[bt] - nn, nn);
     }
   }

@@ -91,7 +91,31 @@ def main():
     _report("on-line quantizer, %d vectors of %d, %d-bit, T=2" % (2 * B, H, k), QUANT_MARKS, samples, 0)
     _report("products + LSTM cell, 4H x 2H = %d x %d, batch %d, W%d/A%d" % (4 * H, 2 * H, B, k, k), STEP_MARKS,
             samples, 8)
-    _report("the same on the quantizer's time line (meaningful when the step is one launch)", STEP_MARKS, samples, 8, 0)
+    # the split step of a sequence with given inputs: the marks left are those of the last step's launches
+    # (front launch: only the vectors of h to quantize; back launch: h-side sums + cell)
+    xs = torch.randn(3, B, H, generator=g).to(dev)
+    wss = binding.lstm_sequence_workspace(H, H, B, k, dev)
+    hh, cc = h.clone(), c.clone()
+
+    def sequence():
+        L.amq_lstm_sequence(Wxp.data_ptr(), ax.data_ptr(), Whp.data_ptr(), ah.data_ptr(), H, H, k, None, xs.data_ptr(), 3,
+                            hh.data_ptr(), cc.data_ptr(), B, k, 2, None, wss.data_ptr(), wss.numel(), s)
+
+    samples = []
+    for it in range(40):
+        L.amq_debug_set_phase_buffer(None)
+        for _ in range(2):
+            sequence()
+        buf.zero_()
+        torch.cuda.synchronize()
+        L.amq_debug_set_phase_buffer(buf.data_ptr())
+        sequence()
+        torch.cuda.synchronize()
+        if it >= 5:
+            samples.append(buf.cpu().numpy().copy())
+    L.amq_debug_set_phase_buffer(None)
+    _report("split step, front launch of the last step: quantizer of h (%d vectors)" % B, QUANT_MARKS, samples, 0)
+    _report("split step, back launch: h-side sums + stored x-side sums + cell", STEP_MARKS, samples, 8)
 
 
 if __name__ == "__main__":

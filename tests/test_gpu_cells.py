@@ -388,6 +388,50 @@ def test_lstm_sequence_batched(amq, I, H, B, k_w, k_a, steps):
     assert_vec_close(host(dc), c, "c final")
 
 
+@pytest.mark.parametrize("I,H,B,k_w,k_a,steps", [(300, 200, 17, 3, 3, 5), (1024, 1024, 64, 3, 3, 6), (100, 64, 20, 2, 2, 1),
+                                                 (130, 1000, 33, 2, 3, 2), (1024, 516, 50, 2, 2, 7)])
+def test_lstm_sequence_split_step_is_bit_identical(amq, I, H, B, k_w, k_a, steps):
+    # With the larger workspace a batched sequence takes W_x x_t off the recurrent chain (front launch:
+    # quantize h_{t-1}, quantize x_{t+2}, x-side sums of step t + 1; back launch: h-side sums + cell).  The
+    # stored x-side sums are the very values the whole-step kernel adds, in the same order, so every h_t and
+    # the final state must equal those of the per-step path (small workspace) and of repeated lstm_step calls
+    # exactly.  Ragged tiles, units and short rows included; 1 and 2 steps cover the ends of the pipeline.
+    import torch
+    g = np.random.default_rng(I * 11 + H + B + steps)
+    Wx = (g.standard_normal((4 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((4 * H, H)) * 0.08).astype(np.float32)
+    bias = (g.standard_normal(4 * H) * 0.1).astype(np.float32)
+    xs = g.standard_normal((steps, B, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    c0 = g.standard_normal((B, H)).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    d = [to_dev(t) for t in (Wxp, ax, Whp, ah)]
+    dxs, dbias = to_dev(xs), to_dev(bias)
+    say("split step I=%d H=%d B=%d kw=%d ka=%d steps=%d" % (I, H, B, k_w, k_a, steps))
+    out = []
+    for ws in (amq.lstm_sequence_workspace(I, H, B, k_a, dxs.device), amq.lstm_workspace(I, H, B, k_a, dxs.device)):
+        dh, dc = to_dev(h0), to_dev(c0)
+        hs = torch.full((steps, B, H), float("nan"), dtype=torch.float32, device=dh.device)
+        amq.lstm_sequence(*d, I, H, dbias, dxs, dh, dc, k_a, 2, ws=ws, hs=hs)
+        out.append((host(hs), host(dh), host(dc)))
+    dh, dc = to_dev(h0), to_dev(c0)
+    per_step = []
+    for t in range(steps):
+        amq.lstm_step(*d, I, H, dbias, dxs[t], dh, dc, k_a, 2, h_out=dh, c_out=dc)
+        per_step.append(host(dh))
+    for t in range(steps):
+        assert np.array_equal(out[0][0][t], out[1][0][t]), "h_%d differs between the two sequence paths" % t
+        assert np.array_equal(out[0][0][t], per_step[t]), "h_%d differs from the per-step call" % t
+    assert np.array_equal(out[0][1], out[1][1]) and np.array_equal(out[0][2], out[1][2])
+    assert np.array_equal(out[0][2], host(dc))
+    # and against the oracle for the last step
+    h, c = h0.copy(), c0.copy()
+    for t in range(steps):
+        h, c = oracle.lstm_step(Wxp, ax, Whp, ah, I, H, bias, xs[t], h, c, k_a, 2)
+    assert_vec_close(out[0][1], h, "h final")
+
+
 def test_config3_lstm_1024_batch64(amq):
     # all 35 steps: every step teacher-forced (asserted) and the free-running trajectory (first step
     # outside tolerance reported; none is expected)
