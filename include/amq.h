@@ -233,6 +233,20 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
 void amq_debug_set_sequence_spin_limit(unsigned polls);
 
 /*
+ * Measurement hook: one of the two launches of a steady-state step of the batched amq_lstm_sequence
+ * path, on its own, so that each can be timed and profiled under its own name.  half = 0: the front
+ * launch (quantizes h and x_next, forms the x-side sums from the input codes the workspace holds);
+ * half = 1: the back launch (h-side sums + the stored x-side sums + cell; h and c updated in place).
+ * workspace: one that an amq_lstm_sequence call of the same shape has used (at least
+ * amq_lstm_sequence_workspace_bytes), so that the codes and sums it reads are valid numbers.  The results
+ * are not a step of any sequence.  AMQ_ERR_UNSUPPORTED where the sequence call would not take this path.
+ */
+int amq_debug_lstm_split_half(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                              const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias,
+                              const float* x_next, float* h, float* c, int64_t B, int k_a, int T,
+                              void* workspace, size_t workspace_bytes, int half, void* stream);
+
+/*
  * One quantized GRU step.  The paper evaluates GRUs (Tables 2-5) without
  * printing the cell; this is the textbook cell in the form where the reset
  * gate multiplies the hidden-side product of the candidate, so that one

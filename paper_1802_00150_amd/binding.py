@@ -22,6 +22,7 @@ EXPORTS = [
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed",
     "amq_lstm_step_packed_grouped", "amq_stream_read_probe", "amq_lstm_sequence",
     "amq_lstm_sequence_flag_offset", "amq_lstm_sequence_workspace_bytes", "amq_debug_set_sequence_spin_limit",
+    "amq_debug_lstm_split_half",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
     "amq_lm_workspace_bytes", "amq_lm_step", "amq_lm_sequence_workspace_bytes", "amq_lm_sequence",
@@ -65,6 +66,8 @@ def lib():
         L.amq_lstm_sequence_flag_offset.restype = _sz
         L.amq_lstm_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.amq_lstm_sequence_workspace_bytes.restype = _sz
+        L.amq_debug_lstm_split_half.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _sz,
+                                                _int, _p]
         L.amq_debug_set_sequence_spin_limit.argtypes = [C.c_uint]
         L.amq_debug_set_sequence_spin_limit.restype = None
         L.amq_lstm_step.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _p,

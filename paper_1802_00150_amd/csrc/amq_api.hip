@@ -586,6 +586,29 @@ int amq_lstm_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t*
   return AMQ_OK;
 }
 
+int amq_debug_lstm_split_half(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                              int64_t I, int64_t H, int k_w, const float* bias, const float* x_next, float* h, float* c,
+                              int64_t B, int k_a, int T, void* workspace, size_t workspace_bytes, int half,
+                              void* stream) {
+  if (!c || !x_next || (half != 0 && half != 1)) return AMQ_ERR_INVALID;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve_seq(nullptr, I, H, B, k_a).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x_next, h, B, k_a, T, h, workspace, workspace_bytes, need);
+  if (st != AMQ_OK) return st;
+  const SeqWs sw = carve_seq(workspace, I, H, B, k_a);
+  amq::BmvArgs b = lstm_args(Wxp, alpha_x, Whp, alpha_h, I, H, bias, sw.xq[0], sw.xbeta[0], sw.step.hp, sw.step.beta_h, c,
+                             B, h, c, nullptr);
+  b.Y = sw.xsum;
+  if (!amq::step_split_supported(b, k_w, k_a, amq::kEpiLstm)) return AMQ_ERR_UNSUPPORTED;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (half == 1) return hip_status(amq::launch_step_back(b, k_w, k_a, amq::kEpiLstm, s));
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, sw.step.hp, sw.step.beta_h};
+  q.seg[1] = amq::QuantSeg{x_next, I, (int)I, (int)B, sw.xq[1], sw.xbeta[1]};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  return hip_status(amq::launch_step_front(q, nullptr, &b, k_w, k_a, amq::kEpiLstm, s));
+}
+
 int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
                  int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h, const float* x,
                  const float* h_prev, int64_t B, int k_a, int T, float* h_out, void* workspace,
