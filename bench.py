@@ -43,8 +43,8 @@ GEMV_TRAFFIC_BYTES = (2 * 270918.5 + 8192.2) * 1024
 LSTM_FUSED_TRAFFIC_BYTES = (2 * 2109.4 + 512.0) * 1024
 LSTM_QUANT_TRAFFIC_BYTES = (2 * 333.1 + 52.8) * 1024
 LSTM_B1_TRAFFIC_BYTES = (2 * 271843.8 + 1368.0) * 1024
-LSTM_FRONT_TRAFFIC_BYTES = None   # filled from the counter runs of the sequence path's two launches
-LSTM_BACK_TRAFFIC_BYTES = None
+LSTM_FRONT_TRAFFIC_BYTES = (2 * 1286.9 + 1077.0) * 1024   # step_front_kernel, steady-state form
+LSTM_BACK_TRAFFIC_BYTES = (2 * 1721.4 + 512.0) * 1024     # step_back_kernel
 FP32_VALU_PEAK_TFLOPS = 157.3                # vector fp32
 MIN_TIMED_CALLS = 100
 MIN_WARMUP_CALLS = 10
