@@ -138,18 +138,27 @@ __device__ __forceinline__ void ls_solve_f64(int n, const double* d, const doubl
   }
 }
 
-// lane j keeps the wave-uniform 64-bit value `mk` (the ballot of slot j).  `ln` is the lane number as
-// the caller's pass sees it (see pass_lane).
-__device__ __forceinline__ void keep_in_lane(unsigned long long& mine, unsigned long long mk, int j, int ln) {
-  if (ln == j) mine = mk;
-}
-// The lane number, opaque to the compiler: a pass over the slots compares it with every slot number,
-// and left to itself the compiler computes those comparison masks once for the whole kernel and keeps
-// (then spills) two scalar registers per slot.
-__device__ __forceinline__ int pass_lane() {
-  int ln = lane_id();
-  asm volatile("" : "+v"(ln));
-  return ln;
+// v_writelane_b32: lane `lane` (a constant) of `old` takes the wave-uniform `value`.  (The compiler's
+// intrinsic, reached by its name: this compiler has no builtin for it.)
+extern "C" __device__ int amq_writelane_i32(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
+// This lane's bit of a wave-uniform 64-bit mask, as a condition (the mask becomes the lane mask of whatever
+// selects on it; no vector instruction).
+extern "C" __device__ bool amq_inverse_ballot_i64(unsigned long long mask) __asm("llvm.amdgcn.inverse.ballot.i64");
+__device__ __forceinline__ bool lane_bit(unsigned long long mask) { return amq_inverse_ballot_i64(mask); }
+
+// Up to this many planes the code assignment of the throughput path works on comparison masks (scalar
+// unit); beyond, the 2^K - 1 masks and the logic on them cost more than counting the comparisons per lane
+// (measured at K = 3 on 16384 x 4096: 320 us with mask logic, 264 us with counted comparisons).
+constexpr int kMaskLogicMaxK = 2;
+
+// Lane j keeps the wave-uniform 64-bit value `mk` (the ballot of slot j): one lane write per half, which
+// takes the value straight from the scalar registers the comparison wrote.
+__device__ __forceinline__ void keep_in_lane(unsigned long long& mine, unsigned long long mk, int j) {
+  int lo = (int)(unsigned)(mine & 0xffffffffull), hi = (int)(unsigned)(mine >> 32);
+  lo = amq_writelane_i32((int)(unsigned)(mk & 0xffffffffull), j, lo);
+  hi = amq_writelane_i32((int)(unsigned)(mk >> 32), j, hi);
+  mine = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
 }
 
 __device__ __forceinline__ float readlane_f(float v, int l) {
@@ -412,7 +421,7 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
   for (int i = 0; i < K; ++i) {
     unsigned long long mine = 0ull;
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) keep_in_lane(mine, mk[i][j], j, lane);
+    for (int j = 0; j < NJ; ++j) keep_in_lane(mine, mk[i][j], j);
     mym[i] = mine;
   }
 }
@@ -473,13 +482,12 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
       alpha[i] = al;
       unsigned long long mine = 0ull;
       double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
-      const int ln = pass_lane();
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         if (FULL || j < nj) {
           const bool valid = FULL || (base + j) * 64 + lane < n;
           const bool bit = valid && (r[j] >= 0.0f);
-          keep_in_lane(mine, __ballot(bit), j, ln);
+          keep_in_lane(mine, __ballot(bit), j);
           if constexpr (K > 1) {
             const float rn = valid ? r[j] - (bit ? al : -al) : 0.0f;
             r[j] = rn;
@@ -579,6 +587,14 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
     // ---- codes with the coefficients fixed (Alg. 1); the position in the sorted table is the
     // number of midpoints <= w, which is where the k-comparison tree walk ends.
     const bool more = do_ls && (it + 1 < iters);  // B^T w is needed by another cycle
+    // wave-uniform masks (all ones or zero): the table's bit at position 0; whether it changes after position t
+    unsigned long long first[K], flips[K][M - 1];
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+      first[i] = 0ull - (unsigned long long)(bm[i] & 1u);
+#pragma unroll
+      for (int t = 0; t < M - 1; ++t) flips[i][t] = 0ull - (unsigned long long)(((bm[i] >> t) ^ (bm[i] >> (t + 1))) & 1u);
+    }
     auto assign = [&](auto full_c, auto more_c) {
       constexpr bool FULL = decltype(full_c)::value;
       constexpr bool MORE = decltype(more_c)::value;
@@ -586,20 +602,39 @@ __device__ __forceinline__ void quantize_core(const float (&w)[NJ], int n, int b
       double qa[K], qb[K];
 #pragma unroll
       for (int i = 0; i < K; ++i) { mine[i] = 0ull; qa[i] = 0.0; qb[i] = 0.0; }
-      const int ln = pass_lane();
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         if (FULL || j < nj) {
           const bool valid = FULL || (base + j) * 64 + lane < n;
-          int pos = 0;
-#pragma unroll
-          for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
           const double wd = (double)w[j];
+          unsigned long long plane[K];  // wave-uniform: plane i of the 64 codes of this slot
+          if constexpr (K <= kMaskLogicMaxK) {
+            // The comparisons with the ascending midpoints form a thermometer code, so plane i of an
+            // entry's code is the table's bit at position 0, flipped once for every midpoint <= w at which
+            // the table's bit changes: logic on whole comparison masks, on the scalar unit.
+            unsigned long long ge[M - 1];
+#pragma unroll
+            for (int t = 0; t < M - 1; ++t) ge[t] = __ballot(w[j] >= thr[t]);
+            const unsigned long long in_range = FULL ? ~0ull : __ballot(valid);
+#pragma unroll
+            for (int i = 0; i < K; ++i) {
+              unsigned long long b = first[i];
+#pragma unroll
+              for (int t = 0; t < M - 1; ++t) b ^= ge[t] & flips[i][t];
+              plane[i] = FULL ? b : (b & in_range);
+            }
+          } else {
+            int pos = 0;
+#pragma unroll
+            for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
+#pragma unroll
+            for (int i = 0; i < K; ++i) plane[i] = __ballot(valid && ((bm[i] >> pos) & 1u));
+          }
 #pragma unroll
           for (int i = 0; i < K; ++i) {
-            const bool bit = valid && ((bm[i] >> pos) & 1u);
-            keep_in_lane(mine[i], __ballot(bit), j, ln);
+            keep_in_lane(mine[i], plane[i], j);
             if constexpr (MORE) {
+              const bool bit = lane_bit(plane[i]);
               if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
             }
           }
