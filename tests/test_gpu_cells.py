@@ -432,6 +432,36 @@ def test_lstm_sequence_split_step_is_bit_identical(amq, I, H, B, k_w, k_a, steps
     assert_vec_close(out[0][1], h, "h final")
 
 
+def test_split_half_hook_runs_each_launch_alone(amq):
+    # the measurement hook: either launch of the batched sequence path's step on its own.  Its results are no
+    # step of a sequence; it must run on a workspace a sequence call has used, leave finite numbers, and say
+    # so where the sequence call would not take the split path (batch 1) or the half does not exist.
+    import torch
+    I, H, B, k_w, k_a = 256, 128, 24, 2, 2
+    g = np.random.default_rng(77)
+    Wxp, ax = quantized((g.standard_normal((4 * H, I)) * 0.08).astype(np.float32), k_w)
+    Whp, ah = quantized((g.standard_normal((4 * H, H)) * 0.08).astype(np.float32), k_w)
+    d = [to_dev(t) for t in (Wxp, ax, Whp, ah)]
+    xs = to_dev(g.standard_normal((3, B, I)).astype(np.float32))
+    dh, dc = to_dev(np.zeros((B, H), np.float32)), to_dev(np.zeros((B, H), np.float32))
+    ws = amq.lstm_sequence_workspace(I, H, B, k_a, xs.device)
+    amq.lstm_sequence(*d, I, H, None, xs, dh, dc, k_a, 2, ws=ws)
+    L = amq.binding.lib()
+    s = torch.cuda.current_stream().cuda_stream
+
+    def half(which, batch=B):
+        return L.amq_debug_lstm_split_half(d[0].data_ptr(), d[1].data_ptr(), d[2].data_ptr(), d[3].data_ptr(), I, H,
+                                           k_w, None, xs[2].data_ptr(), dh.data_ptr(), dc.data_ptr(), batch, k_a, 2,
+                                           ws.data_ptr(), ws.numel(), which, s)
+
+    say("split-half hook I=%d H=%d B=%d" % (I, H, B))
+    assert half(0) == 0 and half(1) == 0
+    torch.cuda.synchronize()
+    assert np.isfinite(host(dh)).all() and np.isfinite(host(dc)).all()
+    assert half(2) == 1       # AMQ_ERR_INVALID
+    assert half(0, batch=1) == 2   # AMQ_ERR_UNSUPPORTED
+
+
 def test_config3_lstm_1024_batch64(amq):
     # all 35 steps: every step teacher-forced (asserted) and the free-running trajectory (first step
     # outside tolerance reported; none is expected)
