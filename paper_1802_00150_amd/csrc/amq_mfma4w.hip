@@ -2,15 +2,17 @@
 // Y = (sum_i alpha_i B_i)(sum_j beta_j x_j) for many rows and 32 or more columns (mfma4w_kernel),
 // and the recurrent steps for batches of 128 and more (mfma4wc_kernel, further down).
 //
-// Same arithmetic and operand formats as the kernel in amq_mfma4.hip ({0, 1} codes as E2M1 nibbles,
-// v_mfma_scale_f32_16x16x128_f8f6f4, +-1 dot products recovered from popcounts), different work
-// split.  There a wave owns one 16 x 16 output tile per pass, and per pass it spends about 350
-// vector instructions (1400 cycles) on addressing, expanding the weight words, popcounts and the
-// coefficient epilogue against k_w k_a 8 matrix instructions (900 cycles at W2/A3): the vector
-// unit, not the matrix core, bounds it.  Here a wave owns 16 rows x NBT batch tiles, so that
-// everything on the weight side (loads, expansion, popcounts, row coefficients) is paid once per
-// NBT tiles and only the per-output epilogue grows with the tile count.  A workgroup of 8 waves
-// stages NBT * 16 batch entries (all planes) in LDS once and its waves walk over row blocks.
+// Same matrix instruction as the kernel in amq_mfma4.hip (codes as E2M1 nibbles,
+// v_mfma_scale_f32_16x16x128_f8f6f4), different work split.  There a wave owns one 16 x 16 output tile
+// per pass, and per pass it spends about 350 vector instructions (1400 cycles) on addressing, expanding
+// the weight words, popcounts and the coefficient epilogue against k_w k_a 8 matrix instructions (900
+// cycles at W2/A3): the vector unit, not the matrix core, bounds it.  Here a wave owns 16 rows x NBT batch
+// tiles, so that everything on the weight side (loads, expansion, row coefficients) is paid once per NBT
+// tiles and only the per-output epilogue grows with the tile count.  A workgroup of 8 waves stages NBT * 16
+// batch entries (all planes) in LDS once and its waves walk over row blocks.  mfma4w_kernel works on
+// {-1, +1} codes (the staged activations hold 0.0 beyond the end of a vector), so its accumulators are the
+// dot products of the codes and no popcount enters; mfma4wc_kernel still uses {0, 1} codes with popcount
+// corrections.
 #include <type_traits>
 
 #include "amq_device.h"
@@ -27,9 +29,12 @@ constexpr int kWaves = 8;
 // tile bt); the LDS reads (and, when the step changes, the weight expansion) of unit u + 1 are
 // issued under the matrix instructions of unit u.  `tile` points at this lane's 16 bytes of step 0
 // of the block's first tile and plane ([tile][plane][kPlaneBytes] layout).
-template <int KW, int KA, int NBT>
+template <int KW, int KA, int NBT, bool SIGNED = false>
 __device__ __forceinline__ void contract_tiles(const uint4 (&araw)[KW][2], const unsigned char* tile,
                                                v4f (&acc)[NBT][KW][KA]) {
+  // weight words as {0, 1} codes, or as {-1, +1} codes (then the staged tiles are signed too and hold 0.0
+  // beyond the end of a vector, and the accumulators are the dot products of the codes themselves)
+  auto expand = [](uint32_t w) { return SIGNED ? expand4_signed(w) : expand4(w); };
 #pragma unroll
   for (int bt = 0; bt < NBT; ++bt)
 #pragma unroll
@@ -40,7 +45,7 @@ __device__ __forceinline__ void contract_tiles(const uint4 (&araw)[KW][2], const
 #pragma unroll
   for (int j = 0; j < KA; ++j) bop[j] = *reinterpret_cast<const uint4*>(tile + j * kPlaneBytes);
 #pragma unroll
-  for (int i = 0; i < KW; ++i) aop[i] = expand4(word_of(araw[i], 0));
+  for (int i = 0; i < KW; ++i) aop[i] = expand(word_of(araw[i], 0));
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int u = 0; u < kSteps * NBT; ++u) {
@@ -52,7 +57,7 @@ __device__ __forceinline__ void contract_tiles(const uint4 (&araw)[KW][2], const
         bnx[j] = *reinterpret_cast<const uint4*>(tile + (bn * KA + j) * kPlaneBytes + tn * kTileB * 64);
       if (bn == 0) {
 #pragma unroll
-        for (int i = 0; i < KW; ++i) anx[i] = expand4(word_of(araw[i], tn));
+        for (int i = 0; i < KW; ++i) anx[i] = expand(word_of(araw[i], tn));
       }
     }
 #pragma unroll
@@ -107,9 +112,12 @@ __device__ __forceinline__ void load_activation_words(const uint32_t* Xp, int ba
     xw[it] = valid ? v : make_uint4(0, 0, 0, 0);
   }
 }
-template <int KA, int NBT, int NTHREADS>
+// SIGNED: {-1, +1} codes with 0.0 at the positions from nlen on (no popcounts are needed then: pops may be
+// null).
+template <int KA, int NBT, int NTHREADS, bool SIGNED = false>
 __device__ __forceinline__ void stage_activation_words(
-    const uint4 (&xw)[(NBT * KA * kTileB * 8 + NTHREADS - 1) / NTHREADS], unsigned char* btile, int* pops) {
+    const uint4 (&xw)[(NBT * KA * kTileB * 8 + NTHREADS - 1) / NTHREADS], unsigned char* btile, int* pops,
+    int nlen = 0) {
   constexpr int kGroupB = NBT * kTileB;
   constexpr int kItems = NBT * KA * kTileB * 8;
   constexpr int kIter = (kItems + NTHREADS - 1) / NTHREADS;
@@ -120,16 +128,31 @@ __device__ __forceinline__ void stage_activation_words(
     const int bt = nn >> 4, n16 = nn & 15;
     const uint4 w4 = xw[it];
     // popcount of the row: its 8 groups sit in 8 consecutive lanes (every lane takes part)
-    const int pc = sum8(__popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w));
+    int pc = 0;
+    if constexpr (!SIGNED) pc = sum8(__popc(w4.x) + __popc(w4.y) + __popc(w4.z) + __popc(w4.w));
     if (e < kItems) {
-      if (q == 0) pops[(bt * KA + j) * kTileB + n16] = pc;
+      if constexpr (!SIGNED) {
+        if (q == 0) pops[(bt * KA + j) * kTileB + n16] = pc;
+      }
       // words 4q .. 4q+3 of the row: k-block q >> 1, steps 4 * (q & 1) + 0..3
       uint4* dst = reinterpret_cast<uint4*>(btile + (bt * KA + j) * kPlaneBytes + ((4 * (q & 1)) * kTileB + n16) * 64 +
                                             (q >> 1) * 16);
-      dst[0 * kTileB * 4] = expand4(w4.x);
-      dst[1 * kTileB * 4] = expand4(w4.y);
-      dst[2 * kTileB * 4] = expand4(w4.z);
-      dst[3 * kTileB * 4] = expand4(w4.w);
+      if constexpr (SIGNED) {
+        // word 4q + c of the row holds positions 32 (4q + c) .. + 31
+        auto inside = [&](int c) {
+          const int left = nlen - 32 * (4 * q + c);
+          return left >= 32 ? 0xffffffffu : left <= 0 ? 0u : ((1u << left) - 1u);
+        };
+        dst[0 * kTileB * 4] = expand4_signed_valid(w4.x, inside(0));
+        dst[1 * kTileB * 4] = expand4_signed_valid(w4.y, inside(1));
+        dst[2 * kTileB * 4] = expand4_signed_valid(w4.z, inside(2));
+        dst[3 * kTileB * 4] = expand4_signed_valid(w4.w, inside(3));
+      } else {
+        dst[0 * kTileB * 4] = expand4(w4.x);
+        dst[1 * kTileB * 4] = expand4(w4.y);
+        dst[2 * kTileB * 4] = expand4(w4.z);
+        dst[3 * kTileB * 4] = expand4(w4.w);
+      }
     }
   }
 }
@@ -140,7 +163,6 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
   constexpr int kGroupB = NBT * kTileB;               // batch entries per workgroup
   constexpr int kIter = (NBT * KA * kTileB * 8 + 64 * kWaves - 1) / (64 * kWaves);
   unsigned char* btile = smem;                                           // [tile][plane][kPlaneBytes]
-  int* pops = reinterpret_cast<int*>(smem + NBT * KA * kPlaneBytes);     // [tile][plane][kTileB]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -161,29 +183,21 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
   {
     uint4 xw[kIter];
     load_activation_words<KA, NBT, 64 * kWaves>(a.blk[0].Xp, batch, bg0, wq, xw);
-    stage_activation_words<KA, NBT, 64 * kWaves>(xw, btile, pops);
+    stage_activation_words<KA, NBT, 64 * kWaves, true>(xw, btile, nullptr, nlen);
     __syncthreads();
   }
 
-  // per batch column of this lane (one per tile): sum_j beta_j and sum_j beta_j (n - 2 popc(x_j)),
-  // and the separate beta_j for the contraction part
+  // coefficients of this lane's batch column, one column per tile
   int bcol[NBT];
   bool bok[NBT];
-  float btv[NBT][KA], sb[NBT], sbcx[NBT];
+  float btv[NBT][KA];
 #pragma unroll
   for (int bt = 0; bt < NBT; ++bt) {
     bcol[bt] = bg0 + bt * kTileB + l16;
     bok[bt] = bcol[bt] < batch;
     const int bc = bok[bt] ? bcol[bt] : batch - 1;
-    sb[bt] = 0.0f;
-    sbcx[bt] = 0.0f;
 #pragma unroll
-    for (int j = 0; j < KA; ++j) {
-      btv[bt][j] = a.blk[0].beta[bc * KA + j];
-      const float cx = (float)(nlen - 2 * pops[(bt * KA + j) * kTileB + l16]);
-      sb[bt] += btv[bt][j];
-      sbcx[bt] = fmaf(btv[bt][j], cx, sbcx[bt]);
-    }
+    for (int j = 0; j < KA; ++j) btv[bt][j] = a.blk[0].beta[bc * KA + j];
   }
 
   // optional: the output row whose value is wanted on its own, per batch column
@@ -200,24 +214,44 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
   float* const lse_part = a.lse_part;
   const unsigned char* tile = btile + l16 * 64 + l4 * 16;
 
+  // Requests of a row block: its packed weight words in the A-operand view (lane = (tile row l16, k-block
+  // l4)) and its row coefficients and bias, one value per lane.  Every request is unconditional on a
+  // clamped row (results of rows outside the matrix are masked or never stored), and those of the next row
+  // block of this wave go out before the contraction of the current one.
+  const int plane = m * wq;
+  auto request_rowblock = [&](int rb, uint4 (&raw)[KW][2], float& coef, float& bs) {
+    const int rbc = rb < rowblocks ? rb : rowblocks - 1;
+    const int wrow = rbc * 16 + l16;
+    const int base = (wrow < m ? wrow : m - 1) * wq;
+#pragma unroll
+    for (int i = 0; i < KW; ++i)
+#pragma unroll
+      for (int v = 0; v < 2; ++v) {
+        const int g = 2 * l4 + v;
+        raw[i][v] = Wp4[base + i * plane + (g < wq ? g : 0)];
+      }
+    // lane l < 16 KW: coefficient l % KW of row rb * 16 + l / KW; lane l < 16: bias of row rb * 16 + l
+    const int ci = rbc * 16 * KW + (lane < 16 * KW ? lane : 0);
+    coef = alpha[ci < m * KW ? ci : m * KW - 1];
+    const int bi = rbc * 16 + l16;
+    bs = a.bias0 ? a.bias0[bi < m ? bi : m - 1] : 0.0f;
+  };
+  uint4 anext[KW][2];
+  float coef_next, bias_next;
+  request_rowblock(rb_first + wv, anext, coef_next, bias_next);
+
   for (int rb = rb_first + wv; rb < rb_end; rb += kWaves) {
     // ---- weight side of the row block, shared by all tiles
-    // A-operand view: lane = (tile row l16, k-block l4)
     const int wrow_a = rb * 16 + l16;
     const bool wok = wrow_a < m;
     uint4 araw[KW][2];
-    {
-      const int base = (wok ? wrow_a : 0) * wq;
-      const int plane = m * wq;
 #pragma unroll
-      for (int i = 0; i < KW; ++i)
+    for (int i = 0; i < KW; ++i)
 #pragma unroll
-        for (int v = 0; v < 2; ++v) {
-          const int g = 2 * l4 + v;
-          const uint4 t4 = Wp4[base + i * plane + (g < wq ? g : 0)];
-          araw[i][v] = (wok && g < wq) ? t4 : make_uint4(0, 0, 0, 0);
-        }
-    }
+      for (int v = 0; v < 2; ++v)
+        araw[i][v] = (wok && 2 * l4 + v < wq) ? anext[i][v] : make_uint4(0, 0, 0, 0);
+    const float coef_req = coef_next, bias_req = bias_next;
+    request_rowblock(rb + kWaves, anext, coef_next, bias_next);
     // C view: rows 4 * l4 + r
     int crow0 = rb * 16 + 4 * l4;
     bool cok[4];
@@ -225,43 +259,16 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       cok[r] = crow0 + r < m;
-      const int cr = cok[r] ? crow0 + r : 0;
 #pragma unroll
-      for (int i = 0; i < KW; ++i) alr[r][i] = alpha[cr * KW + i];
-      bias[r] = a.bias0 ? a.bias0[cr] : 0.0f;
+      for (int i = 0; i < KW; ++i) alr[r][i] = __shfl(coef_req, (4 * l4 + r) * KW + i, kWave);
+      bias[r] = __shfl(bias_req, 4 * l4 + r, kWave);
     }
-    // 2 popc of every weight row plane: this lane's 8 words, the four k-blocks of the row (lanes
-    // 16 apart), then fetched for the rows of the C view; folded with the row coefficients into
-    // pa = sum_i alpha_i 2 popc(w_i) and sa = sum_i alpha_i
-    float pa[4], sa[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      pa[r] = 0.0f;
-      sa[r] = 0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < KW; ++i) {
-      int pc = 0;
-#pragma unroll
-      for (int v = 0; v < 2; ++v)
-        pc += __popc(araw[i][v].x) + __popc(araw[i][v].y) + __popc(araw[i][v].z) + __popc(araw[i][v].w);
-      pc += __shfl_xor(pc, 16, kWave);
-      pc += __shfl_xor(pc, 32, kWave);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float pw2 = (float)(2 * __shfl(pc, 4 * l4 + r, kWave));
-        pa[r] = fmaf(alr[r][i], pw2, pa[r]);
-        sa[r] += alr[r][i];
-      }
-    }
-
     // ---- contraction with all tiles
     v4f acc[NBT][KW][KA];
-    contract_tiles<KW, KA, NBT>(araw, tile, acc);
+    contract_tiles<KW, KA, NBT, true>(araw, tile, acc);
 
-    // ---- epilogue per tile, lane = (batch column l16, row quad l4):
-    //   d_ij = 4 acc_ij - 2 popc(w_i) + (n - 2 popc(x_j)),  y = sum_i alpha_i sum_j beta_j d_ij
-    //     = 4 sum_i alpha_i (sum_j beta_j acc_ij) - pa sb + sa sbcx
+    // ---- epilogue per tile, lane = (batch column l16, row quad l4): the accumulators are the dot products
+    // d_ij of the codes (integers, exact in binary32);  y = sum_i alpha_i sum_j beta_j d_ij
 #pragma unroll
     for (int bt = 0; bt < NBT; ++bt) {
       float yv[4];
@@ -275,7 +282,7 @@ __global__ __launch_bounds__(64 * kWaves) void mfma4w_kernel(BmvArgs a, int rb_p
           for (int j = 0; j < KA; ++j) inner = fmaf(btv[bt][j], acc[bt][i][j][r], inner);
           y = fmaf(alr[r][i], inner, y);
         }
-        yv[r] = fmaf(4.0f, y, fmaf(sa[r], sbcx[bt], -pa[r] * sb[bt])) + bias[r];
+        yv[r] = y + bias[r];
       }
       if (a.tgt_out && bok[bt]) {  // (no accumulation in this use)
         const long long d = tg[bt] - crow0;
