@@ -277,14 +277,24 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
   for (int i = 0; i < K; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) mk[i][j] = 0ull;
-  bool valid[NJ];
+  // Which lanes of a slot lie inside the vector, as wave-uniform masks.  A comparison is written so that its
+  // ballot is the comparison's own scalar result, and "inside the vector" is an AND on the scalar unit;
+  // where a lane needs a mask as a condition it takes its bit straight from the mask (lane_bit).  A wave
+  // whose slots all lie inside (the usual case: 1024 entries on four waves) runs a form without the masks.
+  unsigned long long inside[NJ];
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) valid[j] = j < nj && (base + j) * 64 + lane < n;
+  for (int j = 0; j < NJ; ++j) inside[j] = (j < nj) ? __ballot((base + j) * 64 + lane < n) : 0ull;
+  const bool all_inside = nj == NJ && (base + NJ) * 64 <= n;
+  double wd[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) wd[j] = (double)w[j];
 
-  if (do_greedy) {
+  auto greedy = [&](auto full_c) {
+    constexpr bool FULL = decltype(full_c)::value;
     // ---- greedy initialisation, Eq. 4 (one pass per stage, as in quantize_core)
     float r[NJ];
     double s[1];
+    double lane_l1;  // this lane's share of sum |w|, which is also its share of b_1^T w (same terms, same order)
     {
       double s0 = 0.0, s1 = 0.0;
 #pragma unroll
@@ -292,7 +302,8 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
         r[j] = w[j];
         if (j & 1) s1 += (double)fabsf(w[j]); else s0 += (double)fabsf(w[j]);
       }
-      s[0] = s0 + s1;
+      lane_l1 = s0 + s1;
+      s[0] = lane_l1;
     }
     block_totals<NW, 1>(s, sh, phase);
 #pragma unroll
@@ -302,19 +313,32 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
       double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const bool bit = valid[j] && (r[j] >= 0.0f);
-        mk[i][j] = __ballot(bit);
-        const double sw = bit ? (double)w[j] : -(double)w[j];
-        const float rn = valid[j] ? r[j] - (bit ? al : -al) : 0.0f;
-        r[j] = rn;
-        if (j & 1) { q1 += sw; s1 += (double)fabsf(rn); } else { q0 += sw; s0 += (double)fabsf(rn); }
+        const unsigned long long ge = __ballot(r[j] >= 0.0f);
+        const unsigned long long m = FULL ? ge : (ge & inside[j]);
+        mk[i][j] = m;
+        const bool bit = lane_bit(m);
+        if constexpr (K > 1) {
+          float rn = r[j] - (bit ? al : -al);
+          if constexpr (!FULL) rn = lane_bit(inside[j]) ? rn : 0.0f;
+          r[j] = rn;
+          if (i > 0) {
+            const double sw = bit ? wd[j] : -wd[j];
+            if (j & 1) q1 += sw; else q0 += sw;
+          }
+          if (i + 1 < K) {
+            if (j & 1) s1 += (double)fabsf(rn); else s0 += (double)fabsf(rn);
+          }
+        }
       }
-      q[i] = q0 + q1;
+      q[i] = (i == 0) ? lane_l1 : q0 + q1;
       if (i + 1 < K) {
         s[0] = s0 + s1;
         block_totals<NW, 1>(s, sh, phase);
       }
     }
+  };
+  if (do_greedy) {
+    if (all_inside) greedy(std::true_type{}); else greedy(std::false_type{});
   } else if (do_ls) {
     // codes given by the caller as per-lane masks (lane j holds slot j)
 #pragma unroll
@@ -384,36 +408,53 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
     if (lane >= M) rank = lane;
     const float sv = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(v)));
     const int sp = __builtin_amdgcn_ds_permute(rank << 2, p);
+    // midpoint of a code and its upper neighbour: every lane forms its own (the neighbour's value comes
+    // through a row shift), the first M - 1 are then read out as wave-uniform values
+    const float up = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sv), 0x101 /* row_shl:1 */, 0xf, 0xf, true));
+    const float mid = 0.5f * (sv + up);
     float thr[M - 1];
 #pragma unroll
-    for (int j = 0; j < M - 1; ++j) thr[j] = 0.5f * (readlane_f(sv, j) + readlane_f(sv, j + 1));
-    unsigned bm[K];
+    for (int j = 0; j < M - 1; ++j) thr[j] = readlane_f(mid, j);
+    unsigned bm[K];  // bit `pos` of bm[i]: plane i is +1 for the code at sorted position pos
 #pragma unroll
-    for (int i = 0; i < K; ++i) bm[i] = (unsigned)__ballot(lane < M && ((sp >> (K - 1 - i)) & 1));
+    for (int i = 0; i < K; ++i) bm[i] = (unsigned)__ballot((sp & (1 << (K - 1 - i))) != 0) & (unsigned)((1ull << M) - 1ull);
     AMQ_PHASE(marks, 6 + 4 * it);
 
     // ---- codes with the coefficients fixed (Alg. 1)
     const bool more = do_ls && (it + 1 < iters);
-    double qa[K], qb[K];
+    auto assign = [&](auto full_c, auto more_c) {
+      constexpr bool FULL = decltype(full_c)::value;
+      constexpr bool MORE = decltype(more_c)::value;  // B^T w is needed by another cycle
+      double qa[K], qb[K];
 #pragma unroll
-    for (int i = 0; i < K; ++i) { qa[i] = 0.0; qb[i] = 0.0; }
+      for (int i = 0; i < K; ++i) { qa[i] = 0.0; qb[i] = 0.0; }
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      int pos = 0;
+      for (int j = 0; j < NJ; ++j) {
+        int pos = 0;  // position in the sorted table = number of midpoints <= w
 #pragma unroll
-      for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
-      const double wd = (double)w[j];
+        for (int t = 0; t < M - 1; ++t) pos += (w[j] >= thr[t]) ? 1 : 0;
+        const unsigned sel = 1u << pos;
 #pragma unroll
-      for (int i = 0; i < K; ++i) {
-        const bool bit = valid[j] && ((bm[i] >> pos) & 1u);
-        mk[i][j] = __ballot(bit);
-        if (more) {
-          if (j & 1) qb[i] += bit ? wd : -wd; else qa[i] += bit ? wd : -wd;
+        for (int i = 0; i < K; ++i) {
+          const unsigned long long hit = __ballot((sel & bm[i]) != 0u);
+          const unsigned long long m = FULL ? hit : (hit & inside[j]);
+          mk[i][j] = m;
+          if constexpr (MORE) {
+            const bool bit = lane_bit(m);
+            if (j & 1) qb[i] += bit ? wd[j] : -wd[j]; else qa[i] += bit ? wd[j] : -wd[j];
+          }
         }
       }
-    }
+      if constexpr (MORE) {
 #pragma unroll
-    for (int i = 0; i < K; ++i) q[i] = qa[i] + qb[i];
+        for (int i = 0; i < K; ++i) q[i] = qa[i] + qb[i];
+      }
+    };
+    if (all_inside) {
+      if (more) assign(std::true_type{}, std::true_type{}); else assign(std::true_type{}, std::false_type{});
+    } else {
+      if (more) assign(std::false_type{}, std::true_type{}); else assign(std::false_type{}, std::false_type{});
+    }
     AMQ_PHASE(marks, 7 + 4 * it);
   }
   // lane j takes the ballots of slot j (the layout the callers store)
