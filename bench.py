@@ -41,9 +41,9 @@ GEMV_TRAFFIC_BYTES = (2 * 270918.5 + 8192.2) * 1024
 # the same for the two kernels of the primary workload (profiles/lstm_step_1024_b64_w3a3.md) and for the
 # streamed batch-1 LSTM step (profiles/lstm_step_b1_streamed_1024_w3a3.md)
 LSTM_FUSED_TRAFFIC_BYTES = (2 * 2109.4 + 512.0) * 1024
-LSTM_QUANT_TRAFFIC_BYTES = (2 * 333.1 + 52.8) * 1024
+LSTM_QUANT_TRAFFIC_BYTES = (2 * 358.0 + 53.0) * 1024
 LSTM_B1_TRAFFIC_BYTES = (2 * 271843.8 + 1368.0) * 1024
-LSTM_FRONT_TRAFFIC_BYTES = (2 * 1286.9 + 1077.0) * 1024   # step_front_kernel, steady-state form
+LSTM_FRONT_TRAFFIC_BYTES = (2 * 1309.9 + 1077.0) * 1024   # step_front_kernel, steady-state form
 LSTM_BACK_TRAFFIC_BYTES = (2 * 1721.4 + 512.0) * 1024     # step_back_kernel
 FP32_VALU_PEAK_TFLOPS = 157.3                # vector fp32
 MIN_TIMED_CALLS = 100

@@ -310,6 +310,8 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
     for (int i = 0; i < K; ++i) {
       const float al = n_pow2 ? (float)(s[0] * inv_n) : (float)(s[0] / dn);
       alpha[i] = al;
+      // (sums of +-w start from their first term: 0.0 + x is an instruction the compiler may not drop,
+      // x being -0.0 for all it knows)
       double q0 = 0.0, q1 = 0.0, s0 = 0.0, s1 = 0.0;
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
@@ -323,14 +325,14 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
           r[j] = rn;
           if (i > 0) {
             const double sw = bit ? wd[j] : -wd[j];
-            if (j & 1) q1 += sw; else q0 += sw;
+            if (j & 1) q1 = (j == 1) ? sw : q1 + sw; else q0 = (j == 0) ? sw : q0 + sw;
           }
           if (i + 1 < K) {
             if (j & 1) s1 += (double)fabsf(rn); else s0 += (double)fabsf(rn);
           }
         }
       }
-      q[i] = (i == 0) ? lane_l1 : q0 + q1;
+      q[i] = (i == 0) ? lane_l1 : (NJ > 1 ? q0 + q1 : q0);
       if (i + 1 < K) {
         s[0] = s0 + s1;
         block_totals<NW, 1>(s, sh, phase);
@@ -440,14 +442,14 @@ __device__ __forceinline__ void quantize_core_uniform(const float (&w)[NJ], int 
           const unsigned long long m = FULL ? hit : (hit & inside[j]);
           mk[i][j] = m;
           if constexpr (MORE) {
-            const bool bit = lane_bit(m);
-            if (j & 1) qb[i] += bit ? wd[j] : -wd[j]; else qa[i] += bit ? wd[j] : -wd[j];
+            const double sw = lane_bit(m) ? wd[j] : -wd[j];
+            if (j & 1) qb[i] = (j == 1) ? sw : qb[i] + sw; else qa[i] = (j == 0) ? sw : qa[i] + sw;
           }
         }
       }
       if constexpr (MORE) {
 #pragma unroll
-        for (int i = 0; i < K; ++i) q[i] = qa[i] + qb[i];
+        for (int i = 0; i < K; ++i) q[i] = NJ > 1 ? qa[i] + qb[i] : qa[i];
       }
     };
     if (all_inside) {
