@@ -73,6 +73,15 @@ def test_validation_rejects_before_touching_the_device(L):
     assert L.amq_lstm_step(p, p, p, p, 8, 8, 2, None, p, p, null, 1, 2, 2, p, p, ws, need, None) == INVALID
     assert L.amq_gru_step(p, p, p, p, 8, 8, 2, None, None, p, p, 1, 2, 2, p, null, 0, None) == INVALID
     assert L.amq_lstm_sequence(p, p, p, p, 8, 8, 2, None, p, 0, p, p, 1, 2, 2, None, ws, need, None) == INVALID
+    need_seq = L.amq_lstm_sequence_workspace_bytes(8, 8, 4, 2)
+    assert need_seq > L.amq_lstm_workspace_bytes(8, 8, 4, 2) and need_seq % 256 == 0
+    assert L.amq_lstm_sequence_workspace_bytes(8, 8, 0, 2) == 0
+    half = lambda **kw: L.amq_debug_lstm_split_half(p, p, p, p, 8, 8, 2, None, kw.get("x_next", p), p, kw.get("c", p), 4, 2,
+                                                    2, ws, kw.get("bytes", need_seq), kw.get("half", 0), None)
+    assert half(half=2) == INVALID
+    assert half(x_next=null) == INVALID
+    assert half(c=null) == INVALID
+    assert half(bytes=need_seq - 1) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 16385, 16, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED
