@@ -391,7 +391,9 @@ int amq_lm_step(const uint32_t* Ep, const float* alpha_e, int64_t vocab, int64_t
  * that gave up onwards are NaN) and the output layer then takes all h_t of those steps as one batch.  For larger
  * B the recurrent halves of the steps run one after the other and the output layer takes the
  * hidden states of about 4096 / B steps at a time (the inputs are given, so only the recurrence
- * is serial); the workspace holds those hidden states.
+ * is serial: where the shape allows, the input rows are looked up one step ahead and W_x x_t is
+ * formed beside the quantization of h_{t-1}, as in amq_lstm_sequence); the workspace holds those
+ * hidden states, the looked-up codes of two steps and the x-side sums of one.
  *   workspace: at least amq_lm_sequence_workspace_bytes(E, H, V, B, k_a, k_as) bytes, 256-byte aligned.
  */
 size_t amq_lm_sequence_workspace_bytes(int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as);

@@ -950,6 +950,10 @@ struct LmSeqWs {
   float* hs;
   size_t soft_off;
   int soft_batch;
+  // split recurrent step (batch > 1): the looked-up input codes of two consecutive steps, the x-side sums
+  uint32_t* xq[2];
+  float* xbeta[2];
+  float* xsum;
   size_t total;
 };
 static LmSeqWs carve_lm_seq(void* ws, int64_t E, int64_t H, int64_t V, int64_t B, int k_a, int k_as) {
@@ -962,6 +966,16 @@ static LmSeqWs carve_lm_seq(void* ws, int64_t E, int64_t H, int64_t V, int64_t B
   off += up256(sizeof(float) * (size_t)w.soft_batch * H);
   w.soft_off = off;
   off += carve_softmax(nullptr, V, H, w.soft_batch, k_as).total;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += up256(bytes);
+    return p;
+  };
+  for (int i = 0; i < 2; ++i) {
+    w.xq[i] = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)k_a * B * amq_wpr(E)));
+    w.xbeta[i] = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * k_a));
+  }
+  w.xsum = reinterpret_cast<float*>(take(sizeof(float) * (size_t)B * H * 4));
   w.total = off;
   return w;
 }
@@ -1104,12 +1118,48 @@ static int lm_sequence_impl(const uint32_t* Ep, const float* alpha_e, int64_t vo
   // piece, the recurrent halves of its steps one after the other, every h_t kept, then one pass
   // of the output layer over all (step, batch entry) rows of the piece, which reads W_s once per
   // piece instead of once per step and runs its product at a shape the matrix cores fill.
+  // The recurrent halves themselves: where the split step of amq_lstm_sequence applies, W_x x_t leaves the
+  // chain here too -- the codes of x_t are rows of the quantized embedding, looked up one step ahead by
+  // workgroups of the front launch (front launch of step t: quantize h_{t-1}, look up x_{t+1}, form the
+  // x-side sums of step t; back launch: h-side sums + stored x-side sums + cell; the first step looks up
+  // x_0 and x_1 and runs the whole-step kernel).  Same results as the per-step launches, bit for bit.
+  const amq::BmvArgs probe = lstm_args(Wxp, alpha_x, Whp, alpha_h, E, H, bias, lw.xq[0], lw.xbeta[0], w.hp, w.beta_h, c,
+                                       B, h, c, nullptr);
+  const bool split = amq::step_split_supported(probe, k_w, k_a, amq::kEpiLstm);
+  auto lookup = [&](int64_t u) {  // the inputs of step u into the code buffer of its parity
+    return amq::GatherSeg{Ep, alpha_e, vocab, reinterpret_cast<const long long*>(ids + u * B), (int)E, (int)B,
+                          lw.xq[u % 2], lw.xbeta[u % 2]};
+  };
+  auto split_step = [&](int64_t u, float* hs_out) -> int {
+    amq::BmvArgs b = probe;
+    b.blk[0].Xp = lw.xq[u % 2];
+    b.blk[0].beta = lw.xbeta[u % 2];
+    b.Y = lw.xsum;
+    b.hs_out = hs_out;
+    amq::QuantArgs q{}, q2{};
+    q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
+    q.T = q2.T = T;
+    q.mode = q2.mode = amq::kQuantFull;
+    int r;
+    if (u == 0) {
+      q.gather = lookup(0);
+      if (steps > 1) q2.gather = lookup(1);
+      r = hip_status(amq::launch_step_front(q, steps > 1 ? &q2 : nullptr, nullptr, k_w, k_a, amq::kEpiLstm, s));
+      if (r != AMQ_OK) return r;
+      return hip_status(amq::launch_mfma4_pair(b, k_w, k_a, amq::kEpiLstm, s));
+    }
+    if (u + 1 < steps) q.gather = lookup(u + 1);
+    r = hip_status(amq::launch_step_front(q, nullptr, &b, k_w, k_a, amq::kEpiLstm, s));
+    if (r != AMQ_OK) return r;
+    return hip_status(amq::launch_step_back(b, k_w, k_a, amq::kEpiLstm, s));
+  };
   const int64_t piece = lm_piece_steps(B);
   for (int64_t t0 = 0; t0 < steps; t0 += piece) {
     const int64_t n = steps - t0 < piece ? steps - t0 : piece;
     for (int64_t t = 0; t < n; ++t) {
-      st = lm_recurrent_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias, ids + (t0 + t) * B, h,
-                               c, B, k_a, T, lw.hs + t * B * H, w, s);
+      st = split ? split_step(t0 + t, lw.hs + t * B * H)
+                 : lm_recurrent_launch(Ep, alpha_e, vocab, E, Wxp, alpha_x, Whp, alpha_h, H, k_w, bias,
+                                       ids + (t0 + t) * B, h, c, B, k_a, T, lw.hs + t * B * H, w, s);
       if (st != AMQ_OK) return st;
     }
     st = output_layer(t0 * B, n * B);

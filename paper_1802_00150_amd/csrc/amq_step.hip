@@ -27,8 +27,9 @@ constexpr int kSplitNJ = 4;     // slots per lane of the quantizer role: vectors
 // LDS, so that the quantizer of h_{t-1} shares its SIMDs with no x-side wave: 11.9 against 11.8 us per step.)
 
 struct FrontArgs {
-  QuantArgs q;      // seg[0] = h_{t-1}, seg[1] = x_{t+1} (count 0 at the end of the sequence); at the first step x_0
-  QuantArgs q2;     // first step only: seg[0] = x_1
+  QuantArgs q;      // seg[0] = h_{t-1}; x_{t+1} as seg[1], or as rows to look up in a quantized table (none at the
+                    // end of the sequence); at the first step x_0
+  QuantArgs q2;     // first step only: x_1
   BmvArgs x;        // x-side product to form (blk[0] only; Y = where the sums go)
   int nx;           // 0 or 1
   int nq, nq2;      // quantizer workgroups = vectors of q and of q2
@@ -134,17 +135,17 @@ bool step_split_supported(const BmvArgs& b, int k_w, int k_a, int epi) {
 
 hipError_t launch_step_front(const QuantArgs& q, const QuantArgs* q2, const BmvArgs* x, int k_w, int k_a, int epi,
                              hipStream_t s) {
-  if (q.mode != kQuantFull || q.gather.count != 0) return hipErrorInvalidValue;
-  if (q2 && (q2->mode != kQuantFull || q2->gather.count != 0)) return hipErrorInvalidValue;
+  if (q.mode != kQuantFull) return hipErrorInvalidValue;
+  if (q2 && q2->mode != kQuantFull) return hipErrorInvalidValue;
   if (q.seg[0].n > 1024 || (q.seg[1].count > 0 && q.seg[1].n > 1024)) return hipErrorInvalidValue;
   if (q2 && (q2->seg[0].n > 1024 || (q2->seg[1].count > 0 && q2->seg[1].n > 1024))) return hipErrorInvalidValue;
   FrontArgs f{};
   f.q = q;
   AMQ_PHASE_ATTACH(f.q);
-  f.nq = q.seg[0].count + q.seg[1].count;
+  f.nq = q.seg[0].count + q.seg[1].count + q.gather.count;  // (one workgroup per vector and per row to look up)
   if (q2) {
     f.q2 = *q2;
-    f.nq2 = q2->seg[0].count + q2->seg[1].count;
+    f.nq2 = q2->seg[0].count + q2->seg[1].count + q2->gather.count;
   }
   int per_x = 0;
   if (x) {

@@ -199,6 +199,15 @@ def test_lm_sequence(amq, E, H, V, B, k, k_ws, k_as, steps):
         assert_vec_close(got[t], ref[t], "logprob step %d" % t)
     assert_vec_close(host(dh), h, "h final")
     assert_vec_close(host(dc), c, "c final")
+    if B > 1:
+        # the sequence call regroups the recurrent work (inputs looked up a step ahead, W_x x_t off the chain,
+        # h-side sums + cell in a second launch) without changing a bit of it: the state it leaves is the
+        # state that step-by-step calls leave
+        sh, sc = torch.zeros((B, H), device="cuda:0"), torch.zeros((B, H), device="cuda:0")
+        for t in range(steps):
+            lm_gpu_step(amq, q, dq, cfg["ids"][t], sh, sc, k, k_as)
+        assert np.array_equal(host(dh), host(sh)), "h differs from step-by-step calls"
+        assert np.array_equal(host(dc), host(sc)), "c differs from step-by-step calls"
 
 
 def test_lm_sequence_give_up_turns_log_probabilities_into_nan(amq):
