@@ -379,7 +379,10 @@ def bench_gru(amq, dev, steps, warmup):
     # The same work when the inputs of a sequence are given: 16 recurrent steps keep their h_t, then
     # one quantize launch and one projection take all 16 x 256 rows.
     n = 16
-    hs = torch.zeros((n + 1, B, H), device=dev)
+    hs = torch.zeros((n, B, H), device=dev)
+    xs16 = torch.cat([xs, xs], 0).contiguous()
+    h16 = torch.zeros((B, H), device=dev)
+    ws_seq = amq.gru_sequence_workspace(I, H, B, k_a, dev)
     pH = torch.empty((k_p, n * B, amq.wpr(H)), dtype=torch.int32, device=dev)
     bH = torch.empty((n * B, k_p), device=dev)
     Y = torch.empty((n * B, cfg["V"]), device=dev)
@@ -387,9 +390,8 @@ def bench_gru(amq, dev, steps, warmup):
     s = torch.cuda.current_stream().cuda_stream
 
     def seq():
-        for t in range(n):
-            amq.gru_step(*q, I, H, None, None, xs[t % 8], hs[t], k_a, T, ws=ws, h_out=hs[t + 1])
-        st = L.amq_quantize_activations(hs[1:].data_ptr(), n * B, H, k_p, T, pH.data_ptr(), bH.data_ptr(), s)
+        amq.gru_sequence(*q, I, H, None, None, xs16, h16, k_a, T, ws=ws_seq, hs=hs)
+        st = L.amq_quantize_activations(hs.data_ptr(), n * B, H, k_p, T, pH.data_ptr(), bH.data_ptr(), s)
         assert st == 0, st
         st = L.amq_binary_gemm(Wsp.data_ptr(), as_.data_ptr(), cfg["V"], H, k_w, pH.data_ptr(), bH.data_ptr(), n * B,
                                k_p, None, 0, Y.data_ptr(), s)
@@ -397,6 +399,31 @@ def bench_gru(amq, dev, steps, warmup):
 
     ms_seq = wall_time_ms(seq, max(2, steps // n), 2) / n
     return ms, ms_seq
+
+
+def bench_gru_sequence(amq, dev, B=64, S=35, calls=30, warmup=5):
+    """GRU 1024/1024 W2/A2 at a batch where the sequence call takes the input products off the recurrent chain:
+    ms per step through amq_gru_sequence and through per-step amq_gru_step calls."""
+    import torch
+    from paper_1802_00150_amd import inputs
+    cfg = inputs.gru_proj(steps=8)
+    I, H, k_w, k_a, T = cfg["I"], cfg["H"], cfg["k_w"], cfg["k_a"], cfg["T"]
+    q = setup_lstm(amq, cfg, dev)
+    g = torch.Generator(device="cpu").manual_seed(11)
+    xs = torch.randn((S, B, I), generator=g).to(dev)
+    h = torch.zeros((B, H), device=dev)
+    ws = amq.gru_sequence_workspace(I, H, B, k_a, dev)
+
+    def seq():
+        h.zero_()
+        amq.gru_sequence(*q, I, H, None, None, xs, h, k_a, T, ws=ws)
+
+    def steps():
+        h.zero_()
+        for t in range(S):
+            amq.gru_step(*q, I, H, None, None, xs[t], h, k_a, T, ws=ws, h_out=h)
+
+    return wall_time_ms(seq, calls, warmup) / S, wall_time_ms(steps, calls, warmup) / S
 
 
 def bench_lm(amq, dev, B, steps, warmup):
@@ -685,6 +712,9 @@ def main():
         ms, ms_seq = bench_gru(amq, dev, 100, 10)
         also["gru_b256_with_projection_steps_per_s"] = 1e3 / ms
         also["gru_b256_projection_over_16_steps_at_once_steps_per_s"] = 1e3 / ms_seq
+        ms_gs, ms_gp = bench_gru_sequence(amq, dev)
+        also["gru_h1024_b64_w2a2_sequence_call_steps_per_s"] = 1e3 / ms_gs
+        also["gru_h1024_b64_w2a2_per_step_call_steps_per_s"] = 1e3 / ms_gp
 
     if "lm" in sections:
         # full language-model step at the paper's large shape: embedding lookup, LSTM 1024, output layer

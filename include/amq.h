@@ -263,6 +263,22 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
                  float* h_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * `steps` consecutive GRU steps (the cell of amq_gru_step) on inputs xs [steps][B][I] that are all given:
+ * h [B][H] is read as the initial state and overwritten with the final one; hs (nullable)
+ * [steps][B][H] receives every h_t.  Same arithmetic as `steps` calls of amq_gru_step, bit for bit.  Where
+ * the shape allows (2 to 128 batch tiles of 16 on at most 2048 row-block x tile tasks, I, H <= 1024, codes
+ * of at most 3 bits) and the workspace has amq_gru_sequence_workspace_bytes, the input products leave the
+ * recurrent chain as in amq_lstm_sequence; otherwise, and with a workspace of only amq_gru_workspace_bytes,
+ * the steps are launched one by one.
+ *   workspace: at least amq_gru_workspace_bytes(I, H, B, k_a) bytes, 256-byte aligned.
+ */
+size_t amq_gru_sequence_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a);
+int amq_gru_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
+                     const float* alpha_h, int64_t I, int64_t H, int k_w, const float* bias_x,
+                     const float* bias_h, const float* xs, int64_t steps, float* h, int64_t B, int k_a,
+                     int T, float* hs, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * GRU step in the original form of the cell (the reset gate multiplies the previous state
  * before the candidate's hidden-side product):
  *   r = sigmoid(ax_r + ah_r), z = sigmoid(ax_z + ah_z),

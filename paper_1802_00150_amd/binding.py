@@ -22,6 +22,7 @@ EXPORTS = [
     "amq_lstm_workspace_bytes", "amq_lstm_step", "amq_lstm_step_static", "amq_lstm_step_packed",
     "amq_lstm_step_packed_grouped", "amq_stream_read_probe", "amq_lstm_sequence",
     "amq_lstm_sequence_flag_offset", "amq_lstm_sequence_workspace_bytes", "amq_debug_set_sequence_spin_limit",
+    "amq_gru_sequence", "amq_gru_sequence_workspace_bytes",
     "amq_debug_lstm_split_half",
     "amq_gru_workspace_bytes", "amq_gru_step",
     "amq_embedding_lookup", "amq_log_softmax", "amq_softmax_layer_workspace_bytes", "amq_softmax_layer",
@@ -66,6 +67,10 @@ def lib():
         L.amq_lstm_sequence_flag_offset.restype = _sz
         L.amq_lstm_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
         L.amq_lstm_sequence_workspace_bytes.restype = _sz
+        L.amq_gru_sequence_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+        L.amq_gru_sequence_workspace_bytes.restype = _sz
+        L.amq_gru_sequence.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _i64, _p, _i64, _int, _int, _p,
+                                       _p, _sz, _p]
         L.amq_debug_lstm_split_half.argtypes = [_p, _p, _p, _p, _i64, _i64, _int, _p, _p, _p, _p, _i64, _int, _int, _p, _sz,
                                                 _int, _p]
         L.amq_debug_set_sequence_spin_limit.argtypes = [C.c_uint]
@@ -403,6 +408,26 @@ def gru_step(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, x, h_prev, k_a, T
                               _dev(x, torch.float32), _dev(h_prev, torch.float32), B, k_a, T,
                               _dev(h_out, torch.float32), ws.data_ptr(), ws.numel(), _stream()))
     return h_out
+
+
+def gru_sequence_workspace(I, H, B, k_a, device):
+    """Workspace with which gru_sequence takes the input products off the recurrent chain (B > 1)."""
+    nbytes = int(lib().amq_gru_sequence_workspace_bytes(I, H, B, k_a))
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def gru_sequence(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, xs, h, k_a, T, ws=None, hs=None):
+    """xs [steps, B, I]; h [B, H] is updated in place; hs [steps, B, H] optional."""
+    k_w = Wxp.shape[0]
+    steps, B, _ = xs.shape
+    if ws is None:
+        ws = gru_sequence_workspace(I, H, B, k_a, xs.device)
+    _check(lib().amq_gru_sequence(_dev(Wxp, torch.int32), _dev(alpha_x, torch.float32), _dev(Whp, torch.int32),
+                                  _dev(alpha_h, torch.float32), I, H, k_w, _opt(bias_x), _opt(bias_h),
+                                  _dev(xs, torch.float32), steps, _dev(h, torch.float32), B, k_a, T,
+                                  None if hs is None else _dev(hs, torch.float32), ws.data_ptr(), ws.numel(),
+                                  _stream()))
+    return h
 
 
 def embedding_lookup(Ep, alpha_e, n, ids):

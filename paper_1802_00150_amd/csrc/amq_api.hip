@@ -113,9 +113,9 @@ struct SeqWs {
   size_t total;
 };
 
-SeqWs carve_seq(void* ws, int64_t I, int64_t H, int64_t B, int k_a) {
+SeqWs carve_seq(void* ws, int64_t I, int64_t H, int64_t B, int k_a, int gates = 4, int n_pre = 1) {
   SeqWs w;
-  w.step = carve(ws, I, H, B, k_a, 4, 1);
+  w.step = carve(ws, I, H, B, k_a, gates, n_pre);
   size_t off = w.step.total;
   char* base = static_cast<char*>(ws);
   auto take = [&](size_t bytes) {
@@ -609,6 +609,50 @@ int amq_debug_lstm_split_half(const uint32_t* Wxp, const float* alpha_x, const u
   return hip_status(amq::launch_step_front(q, nullptr, &b, k_w, k_a, amq::kEpiLstm, s));
 }
 
+static amq::BmvArgs gru_args(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                             int64_t I, int64_t H, const float* bias_x, const float* bias_h, const uint32_t* Xp,
+                             const float* beta_x, const uint32_t* Hp, const float* beta_h, const float* h_prev,
+                             int64_t B, float* h_out) {
+  amq::BmvArgs b{};
+  b.blk[0] = amq::BmvBlock{Wxp, alpha_x, Xp, beta_x, (int)I};
+  b.blk[1] = amq::BmvBlock{Whp, alpha_h, Hp, beta_h, (int)H};
+  b.m = 3 * H;
+  b.H = H;
+  b.batch = (int)B;
+  b.bias0 = bias_x;
+  b.bias1 = bias_h;
+  b.h_prev = h_prev;
+  b.h_out = h_out;
+  b.groups = 1;
+  return b;
+}
+
+// The launches of one GRU step on a carved workspace (arguments already validated).
+static int gru_step_launch(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                           int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h, const float* x,
+                           const float* h_prev, int64_t B, int k_a, int T, float* h_out, const StepWs& w,
+                           hipStream_t s) {
+  amq::QuantArgs q{};
+  q.seg[0] = amq::QuantSeg{x, I, (int)I, (int)B, w.xp, w.beta_x};
+  q.seg[1] = amq::QuantSeg{h_prev, H, (int)H, (int)B, w.hp, w.beta_h};
+  q.T = T;
+  q.mode = amq::kQuantFull;
+  int st = hip_status(amq::launch_quantize(q, k_a, s));
+  if (st != AMQ_OK) return st;
+  const amq::BmvArgs b = gru_args(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, w.xp, w.beta_x, w.hp, w.beta_h,
+                                  h_prev, B, h_out);
+  if (amq::bmv_supported((int)I, (int)H, k_a, B, amq::kEpiGru))
+    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiGru, s));
+  if (amq::mfma_supported(B)) return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiGru, s));
+  amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias_x, 0, w.pre0);
+  st = run_product(gx, s);
+  if (st != AMQ_OK) return st;
+  amq::GemmArgs gh = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.hp, w.beta_h, B, k_a, bias_h, 0, w.pre1);
+  st = run_product(gh, s);
+  if (st != AMQ_OK) return st;
+  return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
+}
+
 int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
                  int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h, const float* x,
                  const float* h_prev, int64_t B, int k_a, int T, float* h_out, void* workspace,
@@ -617,50 +661,76 @@ int amq_gru_step(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp,
   int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, x, h_prev, B, k_a, T, h_out, workspace,
                       workspace_bytes, need);
   if (st != AMQ_OK) return st;
-  StepWs w = carve(workspace, I, H, B, k_a, 3, 2);
+  const StepWs w = carve(workspace, I, H, B, k_a, 3, 2);
+  return gru_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias_x, bias_h, x, h_prev, B, k_a, T, h_out, w,
+                         static_cast<hipStream_t>(stream));
+}
+
+size_t amq_gru_sequence_workspace_bytes(int64_t I, int64_t H, int64_t B, int k_a) {
+  if (I <= 0 || H <= 0 || B <= 0 || !bits_ok(k_a)) return 0;
+  return carve_seq(nullptr, I, H, B, k_a, 3, 2).total;
+}
+
+int amq_gru_sequence(const uint32_t* Wxp, const float* alpha_x, const uint32_t* Whp, const float* alpha_h,
+                     int64_t I, int64_t H, int k_w, const float* bias_x, const float* bias_h, const float* xs,
+                     int64_t steps, float* h, int64_t B, int k_a, int T, float* hs, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  if (steps <= 0) return AMQ_ERR_INVALID;
+  const size_t need = (I > 0 && H > 0 && B > 0 && bits_ok(k_a)) ? carve(nullptr, I, H, B, k_a, 3, 2).total : 0;
+  int st = check_step(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, xs, h, B, k_a, T, h, workspace, workspace_bytes, need);
+  if (st != AMQ_OK) return st;
+  if (steps >= (1 << 30)) return AMQ_ERR_UNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  amq::QuantArgs q{};
-  q.seg[0] = amq::QuantSeg{x, I, (int)I, (int)B, w.xp, w.beta_x};
-  q.seg[1] = amq::QuantSeg{h_prev, H, (int)H, (int)B, w.hp, w.beta_h};
-  q.T = T;
-  q.mode = amq::kQuantFull;
-  st = hip_status(amq::launch_quantize(q, k_a, s));
-  if (st != AMQ_OK) return st;
-  if (amq::bmv_supported((int)I, (int)H, k_a, B, amq::kEpiGru)) {
-    amq::BmvArgs b{};
-    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
-    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
-    b.m = 3 * H;
-    b.H = H;
-    b.batch = (int)B;
-    b.bias0 = bias_x;
-    b.bias1 = bias_h;
-    b.h_prev = h_prev;
-    b.h_out = h_out;
-    b.groups = 1;
-    return hip_status(amq::launch_bmv(b, k_w, k_a, amq::kEpiGru, s));
+  const StepWs w = carve(workspace, I, H, B, k_a, 3, 2);
+  const SeqWs sw = carve_seq(workspace, I, H, B, k_a, 3, 2);
+  const amq::BmvArgs probe = gru_args(Wxp, alpha_x, Whp, alpha_h, I, H, bias_x, bias_h, sw.xq[0], sw.xbeta[0], w.hp,
+                                      w.beta_h, h, B, h);
+  if (workspace_bytes >= sw.total && amq::step_split_supported(probe, k_w, k_a, amq::kEpiGru)) {
+    // As in amq_lstm_sequence: the inputs are given, so W_x x_t leaves the recurrent chain.  Front launch of
+    // step t: quantize h_{t-1}, quantize x_{t+1}, x-side sums of step t; back launch: h-side sums + the
+    // stored x-side sums + cell, h updated in place.  The first step quantizes h, x_0 and x_1 and runs the
+    // whole-step kernel.  Same results as amq_gru_step called step by step, bit for bit.
+    auto x_seg = [&](int64_t u) {
+      return amq::QuantSeg{xs + u * B * I, I, (int)I, (int)B, sw.xq[u % 2], sw.xbeta[u % 2]};
+    };
+    for (int64_t t = 0; t < steps; ++t) {
+      amq::BmvArgs b = probe;
+      b.blk[0].Xp = sw.xq[t % 2];
+      b.blk[0].beta = sw.xbeta[t % 2];
+      b.Y = sw.xsum;
+      b.hs_out = hs ? hs + t * B * H : nullptr;
+      amq::QuantArgs q{}, q2{};
+      q.seg[0] = amq::QuantSeg{h, H, (int)H, (int)B, w.hp, w.beta_h};
+      q.T = q2.T = T;
+      q.mode = q2.mode = amq::kQuantFull;
+      if (t == 0) {
+        q.seg[1] = x_seg(0);
+        if (steps > 1) q2.seg[0] = x_seg(1);
+        st = hip_status(amq::launch_step_front(q, steps > 1 ? &q2 : nullptr, nullptr, k_w, k_a, amq::kEpiGru, s));
+        if (st != AMQ_OK) return st;
+        st = hip_status(amq::launch_mfma4_pair(b, k_w, k_a, amq::kEpiGru, s));
+      } else {
+        if (t + 1 < steps) q.seg[1] = x_seg(t + 1);
+        st = hip_status(amq::launch_step_front(q, nullptr, &b, k_w, k_a, amq::kEpiGru, s));
+        if (st != AMQ_OK) return st;
+        st = hip_status(amq::launch_step_back(b, k_w, k_a, amq::kEpiGru, s));
+      }
+      if (st != AMQ_OK) return st;
+    }
+    return AMQ_OK;
   }
-  if (amq::mfma_supported(B)) {
-    amq::BmvArgs b{};
-    b.blk[0] = amq::BmvBlock{Wxp, alpha_x, w.xp, w.beta_x, (int)I};
-    b.blk[1] = amq::BmvBlock{Whp, alpha_h, w.hp, w.beta_h, (int)H};
-    b.m = 3 * H;
-    b.H = H;
-    b.batch = (int)B;
-    b.bias0 = bias_x;
-    b.bias1 = bias_h;
-    b.h_prev = h_prev;
-    b.h_out = h_out;
-    b.groups = 1;
-    return hip_status(launch_matrix_core(b, k_w, k_a, amq::kEpiGru, s));
+  // step-by-step launches; with hs given each step writes its slot and reads the one before, and the last
+  // slot is copied to h at the end
+  for (int64_t t = 0; t < steps; ++t) {
+    const float* prev = (hs && t > 0) ? hs + (t - 1) * B * H : h;
+    float* out = hs ? hs + t * B * H : h;
+    st = gru_step_launch(Wxp, alpha_x, Whp, alpha_h, I, H, k_w, bias_x, bias_h, xs + t * B * I, prev, B, k_a, T, out, w,
+                         s);
+    if (st != AMQ_OK) return st;
   }
-  amq::GemmArgs gx = gemm_args(Wxp, alpha_x, 3 * H, I, k_w, w.xp, w.beta_x, B, k_a, bias_x, 0, w.pre0);
-  st = run_product(gx, s);
-  if (st != AMQ_OK) return st;
-  amq::GemmArgs gh = gemm_args(Whp, alpha_h, 3 * H, H, k_w, w.hp, w.beta_h, B, k_a, bias_h, 0, w.pre1);
-  st = run_product(gh, s);
-  if (st != AMQ_OK) return st;
-  return hip_status(amq::launch_gru_pointwise(w.pre0, w.pre1, h_prev, h_out, B, H, s));
+  if (hs) return hip_status(hipMemcpyAsync(h, hs + (steps - 1) * B * H, sizeof(float) * (size_t)B * H,
+                                           hipMemcpyDeviceToDevice, s));
+  return AMQ_OK;
 }
 
 // Workspace of the reset-before GRU step: that of amq_gru_step, then a third pre-activation

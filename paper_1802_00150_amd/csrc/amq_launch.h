@@ -159,7 +159,7 @@ struct BmvArgs {
   const float* h_prev;  // GRU
   float* h_out;
   float* c_out;
-  float* hs_out;        // LSTM, nullable
+  float* hs_out;        // nullable second destination of h_t: LSTM; GRU in the paired kernel and its split forms
   float* lse_part;      // store mode, nullable: per batch entry and slot a (max, sum exp(y - max)) pair over
                         // the outputs one wave produced, [batch][lse_slots][2]
   int lse_slots;        // filled by the launcher: slots per batch entry

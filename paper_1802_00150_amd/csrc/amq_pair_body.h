@@ -382,7 +382,11 @@ __device__ __forceinline__ void pair_body(const BmvArgs& a, int rowblocks, int b
       const float rg = sigmoidf_dev(yx[0] + yh[0] + bias0[0] + bias1[0]);
       const float z = sigmoidf_dev(yx[1] + yh[1] + bias0[1] + bias1[1]);
       const float nn = tanhf_dev(fmaf(rg, yh[2] + bias1[2], yx[2] + bias0[2]));
-      if (bok[bt] && uok) a.h_out[t] = fmaf(z, prev[bt] - nn, nn);
+      if (bok[bt] && uok) {
+        const float h = fmaf(z, prev[bt] - nn, nn);
+        a.h_out[t] = h;
+        if (a.hs_out) a.hs_out[t] = h;
+      }
     }
   }
   AMQ_PHASE_WHEN(bx == 0 && by == 0, AMQ_PHASE_OF(a), 8, 8);

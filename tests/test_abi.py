@@ -82,6 +82,15 @@ def test_validation_rejects_before_touching_the_device(L):
     assert half(x_next=null) == INVALID
     assert half(c=null) == INVALID
     assert half(bytes=need_seq - 1) == INVALID
+    need_g = L.amq_gru_workspace_bytes(8, 8, 4, 2)
+    assert L.amq_gru_sequence_workspace_bytes(8, 8, 4, 2) > need_g
+    assert L.amq_gru_sequence_workspace_bytes(8, 0, 4, 2) == 0
+    gseq = lambda **kw: L.amq_gru_sequence(p, p, p, p, 8, 8, 2, None, None, kw.get("xs", p), kw.get("steps", 3),
+                                           kw.get("h", p), 4, 2, 2, None, ws, kw.get("bytes", need_g), None)
+    assert gseq(steps=0) == INVALID
+    assert gseq(xs=null) == INVALID
+    assert gseq(h=null) == INVALID
+    assert gseq(bytes=need_g - 1) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, null, p, p, p, p, 1, 2, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 8, 8, 2, None, p, p, p, p, p, 1, 7, p, p, None) == INVALID
     assert L.amq_lstm_step_packed(p, p, p, p, 16385, 16, 2, None, p, p, p, p, p, 4, 2, p, p, None) == UNSUPPORTED

@@ -94,6 +94,50 @@ def test_gru_step_random(amq, I, H, B, k_w, k_a):
     assert_vec_close(host(dh), h_ref, "h in place")
 
 
+@pytest.mark.parametrize("I,H,B,k_w,k_a,steps", [(256, 128, 40, 2, 2, 5), (100, 70, 33, 3, 3, 4), (1024, 1024, 64, 2, 2, 3),
+                                                 (64, 40, 300, 2, 3, 2), (256, 128, 40, 2, 2, 1),
+                                                 # step-by-step forms: one batch tile, batch 1, a vector above 1024
+                                                 (40, 24, 3, 2, 2, 4), (300, 300, 1, 2, 2, 3), (1100, 64, 40, 2, 2, 3),
+                                                 # 4-bit activations: no split form
+                                                 (128, 64, 48, 2, 4, 3)])
+def test_gru_sequence(amq, I, H, B, k_w, k_a, steps):
+    # A whole GRU sequence in one call: every h_t and the final state must equal those of gru_step called
+    # step by step exactly (the sequence call only regroups the work: W_x x_t off the recurrent chain where
+    # the shape allows), with and without the list of hidden states, with the large and with the small
+    # workspace; and agree with the oracle's step-by-step loop.
+    import torch
+    g = np.random.default_rng(I * 7 + H + B + steps)
+    Wx = (g.standard_normal((3 * H, I)) * 0.08).astype(np.float32)
+    Wh = (g.standard_normal((3 * H, H)) * 0.08).astype(np.float32)
+    bx = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    bh = (g.standard_normal(3 * H) * 0.1).astype(np.float32)
+    xs = g.standard_normal((steps, B, I)).astype(np.float32)
+    h0 = np.tanh(g.standard_normal((B, H))).astype(np.float32)
+    Wxp, ax = quantized(Wx, k_w)
+    Whp, ah = quantized(Wh, k_w)
+    d = [to_dev(t) for t in (Wxp, ax, Whp, ah)]
+    dxs, dbx, dbh = to_dev(xs), to_dev(bx), to_dev(bh)
+    say("gru sequence I=%d H=%d B=%d kw=%d ka=%d steps=%d" % (I, H, B, k_w, k_a, steps))
+    dh = to_dev(h0)
+    per_step = []
+    for t in range(steps):
+        amq.gru_step(*d, I, H, dbx, dbh, dxs[t], dh, k_a, 2, h_out=dh)
+        per_step.append(host(dh))
+    for ws in (amq.gru_sequence_workspace(I, H, B, k_a, dxs.device), amq.gru_workspace(I, H, B, k_a, dxs.device)):
+        for with_hs in (True, False):
+            sh = to_dev(h0)
+            hs = torch.full((steps, B, H), float("nan"), dtype=torch.float32, device=sh.device) if with_hs else None
+            amq.gru_sequence(*d, I, H, dbx, dbh, dxs, sh, k_a, 2, ws=ws, hs=hs)
+            assert np.array_equal(host(sh), per_step[-1]), "final h differs from the per-step calls"
+            if with_hs:
+                for t in range(steps):
+                    assert np.array_equal(host(hs[t]), per_step[t]), "h_%d differs from the per-step call" % t
+    h = h0.copy()
+    for t in range(steps):
+        h = oracle.gru_step(Wxp, ax, Whp, ah, I, H, bx, bh, xs[t], h, k_a, 2)
+    assert_vec_close(per_step[-1], h, "h final")
+
+
 @pytest.mark.parametrize("I,H,B,k_w,k_a", [(300, 300, 1, 2, 2), (1024, 512, 9, 3, 3), (1024, 1024, 64, 3, 3),
                                            (200, 136, 21, 2, 3)])
 def test_lstm_step_packed(amq, I, H, B, k_w, k_a):
