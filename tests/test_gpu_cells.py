@@ -521,6 +521,42 @@ def test_config3_lstm_1024_batch64(amq):
         assert miss[1] > 0
 
 
+def test_config3_sequence_call_as_benchmarked(amq):
+    # The launch configuration bench.py times: all 35 steps of config 3 through one amq_lstm_sequence call
+    # with the sequence workspace (front and back launch per step).  Every h_t must equal, bit for bit, the
+    # trajectory of amq_lstm_step calls -- which test_config3_lstm_1024_batch64 checks step by step against the
+    # oracle -- and the oracle's step applied to the GPU's own h_{t-1}, c_{t-1} must agree on sampled steps.
+    import torch
+    from paper_1802_00150_amd import inputs
+    c = inputs.lstm_large()
+    I, H, B, k_w, k_a, T = c["I"], c["H"], c["B"], c["k_w"], c["k_a"], c["T"]
+    steps = c["xs"].shape[0]
+    assert steps == 35
+    Wxp, ax = amq.quantize_weights(to_dev(c["Wx"]), k_w, T)
+    Whp, ah = amq.quantize_weights(to_dev(c["Wh"]), k_w, T)
+    xs = to_dev(c["xs"])
+    say("config 3 through one sequence call")
+    dh, dc = to_dev(np.zeros((B, H), np.float32)), to_dev(np.zeros((B, H), np.float32))
+    hs = torch.full((steps, B, H), float("nan"), dtype=torch.float32, device=dh.device)
+    amq.lstm_sequence(Wxp, ax, Whp, ah, I, H, None, xs, dh, dc, k_a, T, ws=amq.lstm_sequence_workspace(I, H, B, k_a, dh.device),
+                      hs=hs)
+    sh, sc = to_dev(np.zeros((B, H), np.float32)), to_dev(np.zeros((B, H), np.float32))
+    ws = amq.lstm_workspace(I, H, B, k_a, dh.device)
+    cs_steps = []
+    for t in range(steps):
+        amq.lstm_step(Wxp, ax, Whp, ah, I, H, None, xs[t], sh, sc, k_a, T, ws=ws, h_out=sh, c_out=sc)
+        assert np.array_equal(host(hs[t]), host(sh)), "h_%d of the sequence call differs from the per-step trajectory" % t
+        cs_steps.append(host(sc))
+    assert np.array_equal(host(dh), host(sh)) and np.array_equal(host(dc), host(sc))
+    Wxo, axo = host(Wxp).view(np.uint32), host(ax)
+    Who, aho = host(Whp).view(np.uint32), host(ah)
+    hs_g = host(hs)
+    for t in (1, 17, 34):    # the oracle's step on the GPU's own previous state
+        h_own, c_own = oracle.lstm_step(Wxo, axo, Who, aho, I, H, None, c["xs"][t], hs_g[t - 1], cs_steps[t - 1], k_a, T)
+        assert_vec_close(hs_g[t], h_own, "h_%d against the oracle on the GPU's own state" % t)
+        assert_vec_close(cs_steps[t], c_own, "c_%d against the oracle on the GPU's own state" % t)
+
+
 def test_config4_gru_batch256_with_projection(amq):
     # all 35 steps: the recurrent step teacher-forced (asserted) and free-running (first step outside
     # tolerance reported), and the W2/A3 projection of every h_t -> fp32 logits
